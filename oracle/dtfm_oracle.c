@@ -1,0 +1,533 @@
+/*
+ * CPU oracle for the scheduler cost model and search of "Decentralized Training of Foundation
+ * Models in Heterogeneous Environments" (arXiv 2206.01288).
+ *
+ * THIS IS TEST INFRASTRUCTURE. It is plain, slow and written for checking by eye against the
+ * paper; only the test-suite, the smoke check and the benchmark's cpu_baseline leg may call it.
+ * It shares no code with the GPU library.
+ *
+ * Notation follows the paper's Sec. 2: N devices, latency matrix A (alpha), bandwidth matrix B
+ * (beta), data-parallel degree D_dp, pipeline degree D_pp (D_dp * D_pp = N), c_dp / c_pp bytes.
+ * A candidate allocation is a permutation perm[0..N): position q holds the device that runs
+ * stage j = q / D_dp for micro-batch slot i = q % D_dp, i.e. sigma_{i,j} of Sec. 2; the
+ * data-parallel group of Sec. 3.1 is C_j = { perm[j*D_dp + i] : i }.
+ *
+ * All arithmetic is IEEE fp64, round to nearest, one rounding per written operation (compile
+ * with -ffp-contract=off).
+ *
+ * Parity status of each function (what pins it, in tests/test_oracle_*.py):
+ *   orc_weights                 pinned: hand-computed entries, homogeneous and asymmetric cases
+ *   orc_datap                   pinned: brute-force definition, D_dp=2 special case, closed form
+ *   orc_bottleneck_match        pinned: enumeration of all matchings, bounds, library feasibility
+ *   orc_open_tsp_held_karp      pinned: enumeration of all stage orders, closed forms
+ *   orc_comm_cost               pinned: definition-level enumeration on tiny N, closed forms,
+ *                               invariances
+ *   orc_local_search ALL_PAIRS  pinned: neighbourhood enumerated independently on tiny N,
+ *                               monotonicity, fixed points, homogeneous no-move case
+ *   orc_local_search GAIN4      gain formula pinned by hand computation; the choice of stage
+ *                               pair per round and acceptance rule are this build's reading:
+ *                               parity unpinned beyond invariants
+ *   orc_philox4x32_10           pinned: published known-answer vectors
+ *   orc_evolve                  invariants only (valid permutations, elitism, determinism);
+ *                               the GA operators are this build's reading: parity unpinned
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_ALL_PAIRS 0
+#define ORC_GAIN4 1
+
+/* ------------------------------------------------------------------------------------------ */
+/* Sec. 2: communication graph G. Each edge carries the average of the two directions.         */
+/* Eq. 2 term: 2 (alpha + c_dp / (D_dp beta));  Eq. 3 term: 2 (alpha + c_pp / beta).           */
+/* The shard c_dp / D_dp is formed first (Sec. 3.2: each device manages c_dp / D_dp bytes).    */
+/* Diagonal entries are never used by the formulas; they are set to 0.                         */
+void orc_weights(const double *lat, const double *bw, int N, double c_dp, double c_pp, int D_dp,
+                 double *W_dp, double *W_pp)
+{
+    double shard = c_dp / (double)D_dp;
+    for (int d = 0; d < N; d++) {
+        for (int e = 0; e < N; e++) {
+            if (d == e) {
+                W_dp[d * N + e] = 0.0;
+                W_pp[d * N + e] = 0.0;
+                continue;
+            }
+            double alpha = 0.5 * (lat[d * N + e] + lat[e * N + d]);
+            double beta = 0.5 * (bw[d * N + e] + bw[e * N + d]);
+            W_dp[d * N + e] = 2.0 * (alpha + shard / beta);
+            W_pp[d * N + e] = 2.0 * (alpha + c_pp / beta);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Eq. 2: DataP-Cost(C_j) = max over d in C_j of the sum over the other d' in C_j.             */
+/* The sum runs over the slots of the stage in order, skipping the device itself, from +0.0.   */
+double orc_datap_stage(const double *W_dp, int N, const int *C, int D_dp)
+{
+    double worst = 0.0;
+    for (int i = 0; i < D_dp; i++) {
+        double sum = 0.0;
+        for (int k = 0; k < D_dp; k++) {
+            if (k == i) continue;
+            sum = sum + W_dp[C[i] * N + C[k]];
+        }
+        if (i == 0 || sum > worst) worst = sum;
+    }
+    return worst;
+}
+
+/* Sec. 3.2, second display: the slowest data-parallel group bounds the data-parallel cost.    */
+double orc_datap(const double *W_dp, int N, const int *perm, int D_dp, int D_pp)
+{
+    double worst = 0.0;
+    for (int j = 0; j < D_pp; j++) {
+        double c = orc_datap_stage(W_dp, N, perm + j * D_dp, D_dp);
+        if (j == 0 || c > worst) worst = c;
+    }
+    return worst;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Eq. 3: min over perfect matchings M of max over (d,d') in M of w[d][d'], for an n x n block. */
+
+/* Kuhn's augmenting-path search in the graph of entries <= t. */
+static int try_row(const double *w, int n, double t, int r, int *seen, int *col_row)
+{
+    for (int c = 0; c < n; c++) {
+        if (w[r * n + c] <= t && !seen[c]) {
+            seen[c] = 1;
+            if (col_row[c] < 0 || try_row(w, n, t, col_row[c], seen, col_row)) {
+                col_row[c] = r;
+                return 1;
+            }
+        }
+    }
+    return 0;
+}
+
+/* 1 iff the entries <= t contain a perfect matching. */
+int orc_threshold_feasible(const double *w, int n, double t)
+{
+    int *col_row = (int *)malloc(sizeof(int) * n);
+    int *seen = (int *)malloc(sizeof(int) * n);
+    int ok = 1;
+    for (int c = 0; c < n; c++) col_row[c] = -1;
+    for (int r = 0; r < n && ok; r++) {
+        for (int c = 0; c < n; c++) seen[c] = 0;
+        ok = try_row(w, n, t, r, seen, col_row);
+    }
+    free(col_row);
+    free(seen);
+    return ok;
+}
+
+static int cmp_double(const void *a, const void *b)
+{
+    double x = *(const double *)a, y = *(const double *)b;
+    return (x > y) - (x < y);
+}
+
+/* The optimum is one of the block's entries: the smallest entry t at which the graph of
+ * entries <= t has a perfect matching. Feasibility is monotone in t, so bisect over the sorted
+ * entries. */
+double orc_bottleneck_match(const double *w, int n)
+{
+    int m = n * n;
+    double *s = (double *)malloc(sizeof(double) * m);
+    memcpy(s, w, sizeof(double) * m);
+    qsort(s, m, sizeof(double), cmp_double);
+    int lo = 0, hi = m - 1; /* the largest entry is always feasible */
+    while (lo < hi) {
+        int mid = (lo + hi) / 2;
+        if (orc_threshold_feasible(w, n, s[mid])) hi = mid; else lo = mid + 1;
+    }
+    double t = s[lo];
+    free(s);
+    return t;
+}
+
+/* Definition of Eq. 3 written out: every one of the n! perfect matchings. */
+static void brute_match_rec(const double *w, int n, int r, int used, double cur, double *best)
+{
+    if (r == n) {
+        if (cur < *best) *best = cur;
+        return;
+    }
+    for (int c = 0; c < n; c++) {
+        if (used & (1 << c)) continue;
+        double e = w[r * n + c];
+        brute_match_rec(w, n, r + 1, used | (1 << c), (r == 0 || e > cur) ? e : cur, best);
+    }
+}
+
+double orc_bottleneck_match_brute(const double *w, int n)
+{
+    double best = INFINITY;
+    brute_match_rec(w, n, 0, 0, 0.0, &best);
+    return best;
+}
+
+/* Coarsened graph of Sec. 3.3: one node per C_j, edge (j,j') weighted by Eq. 3 on the block
+ * W_pp[C_j][C_j']. Ghat is D_pp x D_pp, symmetric, zero diagonal. `brute` selects the
+ * enumeration of all matchings. */
+void orc_coarsen(const double *W_pp, int N, const int *perm, int D_dp, int D_pp, int brute,
+                 double *Ghat)
+{
+    double *blk = (double *)malloc(sizeof(double) * D_dp * D_dp);
+    for (int j = 0; j < D_pp; j++) {
+        Ghat[j * D_pp + j] = 0.0;
+        for (int k = j + 1; k < D_pp; k++) {
+            for (int r = 0; r < D_dp; r++)
+                for (int c = 0; c < D_dp; c++)
+                    blk[r * D_dp + c] = W_pp[perm[j * D_dp + r] * N + perm[k * D_dp + c]];
+            double v = brute ? orc_bottleneck_match_brute(blk, D_dp) : orc_bottleneck_match(blk, D_dp);
+            Ghat[j * D_pp + k] = v;
+            Ghat[k * D_pp + j] = v;
+        }
+    }
+    free(blk);
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Eq. 4: open-loop travelling salesman over the coarsened graph: the cheapest path that visits
+ * every stage node once, free end points, cost = sum of its n-1 edges added left to right.     */
+
+/* Held-Karp: best[S][v] = cheapest path that visits exactly the node set S and ends in v. */
+double orc_open_tsp_held_karp(const double *Ghat, int n)
+{
+    if (n <= 1) return 0.0;
+    size_t full = ((size_t)1 << n) - 1;
+    double *best = (double *)malloc(sizeof(double) * (full + 1) * n);
+    for (size_t S = 1; S <= full; S++) {
+        for (int v = 0; v < n; v++) {
+            if (!(S & ((size_t)1 << v))) continue;
+            size_t rest = S ^ ((size_t)1 << v);
+            if (rest == 0) {
+                best[S * n + v] = 0.0;
+                continue;
+            }
+            double m = INFINITY;
+            for (int u = 0; u < n; u++) {
+                if (!(rest & ((size_t)1 << u))) continue;
+                double c = best[rest * n + u] + Ghat[u * n + v];
+                if (c < m) m = c;
+            }
+            best[S * n + v] = m;
+        }
+    }
+    double m = INFINITY;
+    for (int v = 0; v < n; v++)
+        if (best[full * n + v] < m) m = best[full * n + v];
+    free(best);
+    return m;
+}
+
+/* Definition written out: every one of the n! directed visiting orders. */
+static void brute_tsp_rec(const double *Ghat, int n, int last, int used, int count, double cur,
+                          double *best)
+{
+    if (count == n) {
+        if (cur < *best) *best = cur;
+        return;
+    }
+    for (int v = 0; v < n; v++) {
+        if (used & (1 << v)) continue;
+        double nxt = (count == 0) ? 0.0 : cur + Ghat[last * n + v];
+        brute_tsp_rec(Ghat, n, v, used | (1 << v), count + 1, nxt, best);
+    }
+}
+
+double orc_open_tsp_brute(const double *Ghat, int n)
+{
+    if (n <= 1) return 0.0;
+    double best = INFINITY;
+    brute_tsp_rec(Ghat, n, -1, 0, 0, 0.0, &best);
+    return best;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Eq. 1: Comm-Cost = DataP-Cost + PipelineP-Cost for one candidate. */
+double orc_comm_cost(const double *W_dp, const double *W_pp, int N, int D_dp, int D_pp,
+                     const int *perm, int brute)
+{
+    double *Ghat = (double *)malloc(sizeof(double) * D_pp * D_pp);
+    orc_coarsen(W_pp, N, perm, D_dp, D_pp, brute, Ghat);
+    double pp = brute ? orc_open_tsp_brute(Ghat, D_pp) : orc_open_tsp_held_karp(Ghat, D_pp);
+    double dp = orc_datap(W_dp, N, perm, D_dp, D_pp);
+    free(Ghat);
+    return dp + pp;
+}
+
+void orc_eval_population(const double *W_dp, const double *W_pp, int N, int D_dp, int D_pp,
+                         const int *perm, int P, double *cost)
+{
+    for (int p = 0; p < P; p++)
+        cost[p] = orc_comm_cost(W_dp, W_pp, N, D_dp, D_pp, perm + (size_t)p * N, 0);
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Local search (Sec. 3.4). One round tries one swap per candidate and applies it only if the
+ * true cost (Eq. 1) strictly decreases.
+ *
+ * ALL_PAIRS: every position pair a < b, in lexicographic order, is a move; the move with the
+ * lowest resulting cost is chosen, the first such on ties.
+ *
+ * GAIN4 (the paper's neighbourhood, Sec. 3.4 "Improving Local Search Strategy"): round r looks
+ * at stage pair number r mod (D_pp (D_pp-1)/2) in lexicographic (j < j') order. (d1,d2) is the
+ * fastest link inside C_j (smallest W_pp over slot pairs i < i', first on ties), (d1',d2') the
+ * fastest inside C_j'. The four swaps d1<->d1', d1<->d2', d2<->d1', d2<->d2' are ranked by
+ *   Gain(x<->y) = mean_{d'' in C_j'} w[x][d''] - w[x][mate(x)] + mean_{d'' in C_j} w[y][d''] - w[y][mate(y)]
+ * (w = W_pp, sets taken before the swap, sums in slot order, terms combined left to right);
+ * the swap of largest Gain (first on ties) is the round's single move.                        */
+
+static double gain4(const double *W_pp, int N, int D_dp, const int *Cj, const int *Cjp, int x,
+                    int mate_x, int y, int mate_y)
+{
+    double sx = 0.0, sy = 0.0;
+    for (int i = 0; i < D_dp; i++) sx = sx + W_pp[x * N + Cjp[i]];
+    for (int i = 0; i < D_dp; i++) sy = sy + W_pp[y * N + Cj[i]];
+    double g = sx / (double)D_dp;
+    g = g - W_pp[x * N + mate_x];
+    g = g + sy / (double)D_dp;
+    g = g - W_pp[y * N + mate_y];
+    return g;
+}
+
+/* slot indices (i < i') of the fastest link inside the stage C */
+static void fastest_link(const double *W_pp, int N, int D_dp, const int *C, int *s1, int *s2)
+{
+    double best = INFINITY;
+    *s1 = 0;
+    *s2 = 1;
+    for (int i = 0; i < D_dp; i++)
+        for (int k = i + 1; k < D_dp; k++) {
+            double w = W_pp[C[i] * N + C[k]];
+            if (w < best) {
+                best = w;
+                *s1 = i;
+                *s2 = k;
+            }
+        }
+}
+
+/* Positions (a < b) of GAIN4's proposed swap for round r. Also returns the four gains. */
+void orc_gain4_propose(const double *W_pp, int N, int D_dp, int D_pp, const int *perm, int r,
+                       int *pos_a, int *pos_b, double *gains4)
+{
+    int npairs = D_pp * (D_pp - 1) / 2;
+    int t = r % npairs, j = 0, jp = 1, cnt = 0;
+    for (int a = 0; a < D_pp; a++)
+        for (int b = a + 1; b < D_pp; b++) {
+            if (cnt == t) { j = a; jp = b; }
+            cnt++;
+        }
+    const int *Cj = perm + j * D_dp, *Cjp = perm + jp * D_dp;
+    int s[2], sp[2];
+    fastest_link(W_pp, N, D_dp, Cj, &s[0], &s[1]);
+    fastest_link(W_pp, N, D_dp, Cjp, &sp[0], &sp[1]);
+    double bestg = 0.0;
+    int bk = -1;
+    for (int k = 0; k < 4; k++) {
+        int xi = k / 2, yi = k % 2; /* (d1,d1'), (d1,d2'), (d2,d1'), (d2,d2') */
+        double g = gain4(W_pp, N, D_dp, Cj, Cjp, Cj[s[xi]], Cj[s[1 - xi]], Cjp[sp[yi]], Cjp[sp[1 - yi]]);
+        if (gains4) gains4[k] = g;
+        if (bk < 0 || g > bestg) { bestg = g; bk = k; }
+    }
+    *pos_a = j * D_dp + s[bk / 2];
+    *pos_b = jp * D_dp + sp[bk % 2];
+}
+
+/* move index <-> position pair for ALL_PAIRS: (0,1),(0,2),...,(0,N-1),(1,2),... */
+static long pair_index(int N, int a, int b)
+{
+    return (long)a * N - (long)a * (a + 1) / 2 + (b - a - 1);
+}
+
+/* perm: P x N in/out. cost: P out (cost of the final perm). applied: P x rounds out, may be
+ * NULL: the move index applied in each round (ALL_PAIRS: pair index; GAIN4: pair index of the
+ * swapped positions), or -1 when nothing was applied. */
+void orc_local_search(const double *W_dp, const double *W_pp, int N, int D_dp, int D_pp,
+                      int *perm, int P, int rounds, int neighbourhood, double *cost, long *applied)
+{
+    for (int p = 0; p < P; p++) {
+        int *x = perm + (size_t)p * N;
+        double cur = orc_comm_cost(W_dp, W_pp, N, D_dp, D_pp, x, 0);
+        for (int r = 0; r < rounds; r++) {
+            int ba = -1, bb = -1;
+            double bc = INFINITY;
+            if (neighbourhood == ORC_ALL_PAIRS) {
+                for (int a = 0; a < N; a++)
+                    for (int b = a + 1; b < N; b++) {
+                        int t = x[a]; x[a] = x[b]; x[b] = t;
+                        double c = orc_comm_cost(W_dp, W_pp, N, D_dp, D_pp, x, 0);
+                        t = x[a]; x[a] = x[b]; x[b] = t;
+                        if (c < bc) { bc = c; ba = a; bb = b; }
+                    }
+            } else {
+                orc_gain4_propose(W_pp, N, D_dp, D_pp, x, r, &ba, &bb, NULL);
+                int t = x[ba]; x[ba] = x[bb]; x[bb] = t;
+                bc = orc_comm_cost(W_dp, W_pp, N, D_dp, D_pp, x, 0);
+                t = x[ba]; x[ba] = x[bb]; x[bb] = t;
+            }
+            long mv = -1;
+            if (ba >= 0 && bc < cur) {
+                int t = x[ba]; x[ba] = x[bb]; x[bb] = t;
+                cur = bc;
+                mv = pair_index(N, ba, bb);
+            }
+            if (applied) applied[(size_t)p * rounds + r] = mv;
+        }
+        cost[p] = cur;
+    }
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Philox4x32-10 counter-based generator (Salmon, Moraes, Dror, Shaw: "Parallel random numbers:
+ * as easy as 1, 2, 3", SC'11): ten rounds of two 32x32->64 multiplies, with the key bumped by
+ * the Weyl constants between rounds. */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; round++) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The t-th 32-bit draw of (stream, candidate k, generation g): word t%4 of the Philox block
+ * with counter (t/4, k, g, stream) and key (seed low word, seed high word). */
+static uint32_t draw(uint64_t seed, uint32_t stream, uint32_t g, uint32_t k, uint32_t t)
+{
+    uint32_t ctr[4] = { t / 4u, k, g, stream }, key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) }, out[4];
+    orc_philox4x32_10(ctr, key, out);
+    return out[t % 4u];
+}
+
+/* integer in [0, n) from one 32-bit draw */
+static uint32_t randint(uint32_t x, uint32_t n)
+{
+    return (uint32_t)(((uint64_t)x * (uint64_t)n) >> 32);
+}
+
+uint32_t orc_draw_randint(uint64_t seed, uint32_t stream, uint32_t g, uint32_t k, uint32_t t, uint32_t n)
+{
+    return randint(draw(seed, stream, g, k, t), n);
+}
+
+enum { STREAM_INIT = 0, STREAM_SELECT = 1, STREAM_CROSSOVER = 2, STREAM_MUTATION = 3 };
+
+typedef struct {
+    int P;              /* population size */
+    int lambda;         /* offspring per generation */
+    int m_x;            /* crossover: device draws per offspring */
+    int m_m;            /* mutation: random transpositions per offspring */
+    int ls_moves;       /* local-search rounds per offspring */
+    int neighbourhood;  /* ORC_ALL_PAIRS or ORC_GAIN4 */
+    int warm_start;     /* 1: population[] holds the initial population */
+} orc_ga_params;
+
+/* uniform random permutation: Fisher-Yates from the identity, i = N-1 .. 1, j = randint(i+1) */
+void orc_init_candidate(uint64_t seed, int k, int N, int *perm)
+{
+    for (int q = 0; q < N; q++) perm[q] = q;
+    for (int i = N - 1; i >= 1; i--) {
+        uint32_t j = randint(draw(seed, STREAM_INIT, 0, (uint32_t)k, (uint32_t)(N - 1 - i)), (uint32_t)(i + 1));
+        int t = perm[i]; perm[i] = perm[j]; perm[j] = t;
+    }
+}
+
+/* One offspring (Sec. 3.4 "Hybrid Genetic Algorithm"): two uniformly random parents; the child
+ * starts as parent 1 and m_x times takes a random device d: if d sits in a different stage in
+ * parent 2, d is swapped with the device at a random slot of that stage in the child ("randomly
+ * swap some nodes between the parents"); then m_m uniformly random position transpositions. */
+void orc_make_offspring(uint64_t seed, int g, int k, const int *pop, int P, int N, int D_dp, int m_x,
+                        int m_m, int *child, int *parents2)
+{
+    int p1 = (int)randint(draw(seed, STREAM_SELECT, (uint32_t)g, (uint32_t)k, 0), (uint32_t)P);
+    int p2 = (int)randint(draw(seed, STREAM_SELECT, (uint32_t)g, (uint32_t)k, 1), (uint32_t)P);
+    if (parents2) { parents2[0] = p1; parents2[1] = p2; }
+    const int *par2 = pop + (size_t)p2 * N;
+    int *pos_child = (int *)malloc(sizeof(int) * N);
+    int *pos_par2 = (int *)malloc(sizeof(int) * N);
+    memcpy(child, pop + (size_t)p1 * N, sizeof(int) * N);
+    for (int q = 0; q < N; q++) { pos_child[child[q]] = q; pos_par2[par2[q]] = q; }
+    for (int t = 0; t < m_x; t++) {
+        int d = (int)randint(draw(seed, STREAM_CROSSOVER, (uint32_t)g, (uint32_t)k, (uint32_t)(2 * t)), (uint32_t)N);
+        int slot = (int)randint(draw(seed, STREAM_CROSSOVER, (uint32_t)g, (uint32_t)k, (uint32_t)(2 * t + 1)), (uint32_t)D_dp);
+        int s1 = pos_child[d] / D_dp, s2 = pos_par2[d] / D_dp;
+        if (s1 == s2) continue;
+        int qa = pos_child[d], qb = s2 * D_dp + slot;
+        int e = child[qb];
+        child[qa] = e; child[qb] = d;
+        pos_child[e] = qa; pos_child[d] = qb;
+    }
+    for (int t = 0; t < m_m; t++) {
+        int a = (int)randint(draw(seed, STREAM_MUTATION, (uint32_t)g, (uint32_t)k, (uint32_t)(2 * t)), (uint32_t)N);
+        int b = (int)randint(draw(seed, STREAM_MUTATION, (uint32_t)g, (uint32_t)k, (uint32_t)(2 * t + 1)), (uint32_t)N);
+        int x = child[a]; child[a] = child[b]; child[b] = x;
+    }
+    free(pos_child);
+    free(pos_par2);
+}
+
+typedef struct { double cost; int origin; } keyed;
+
+static int cmp_keyed(const void *a, const void *b)
+{
+    const keyed *x = (const keyed *)a, *y = (const keyed *)b;
+    if (x->cost < y->cost) return -1;
+    if (x->cost > y->cost) return 1;
+    return (x->origin > y->origin) - (x->origin < y->origin);
+}
+
+/* Generational restatement of the paper's loop: every generation makes lambda offspring from the
+ * generation-start population, improves each by local search, then keeps the P best of parents
+ * and offspring ordered by (cost, origin index), parents numbered before offspring, so that an
+ * offspring enters only by beating an incumbent ("add o*, remove the worst if o* is better").
+ * population: P x N (in when warm_start, out), cost: P out (ascending after >= 1 generation),
+ * best_trace: one value per generation = lowest cost in the population after replacement. */
+void orc_evolve(const double *W_dp, const double *W_pp, int N, int D_dp, int D_pp, uint64_t seed,
+                int generations, const orc_ga_params *prm, int *population, double *cost,
+                double *best_trace)
+{
+    int P = prm->P, L = prm->lambda;
+    int *off = (int *)malloc(sizeof(int) * (size_t)L * N);
+    int *next = (int *)malloc(sizeof(int) * (size_t)P * N);
+    double *off_cost = (double *)malloc(sizeof(double) * L);
+    double *next_cost = (double *)malloc(sizeof(double) * P);
+    keyed *keys = (keyed *)malloc(sizeof(keyed) * (size_t)(P + L));
+    if (!prm->warm_start)
+        for (int k = 0; k < P; k++) orc_init_candidate(seed, k, N, population + (size_t)k * N);
+    orc_eval_population(W_dp, W_pp, N, D_dp, D_pp, population, P, cost);
+    for (int g = 0; g < generations; g++) {
+        for (int k = 0; k < L; k++)
+            orc_make_offspring(seed, g, k, population, P, N, D_dp, prm->m_x, prm->m_m, off + (size_t)k * N, NULL);
+        orc_local_search(W_dp, W_pp, N, D_dp, D_pp, off, L, prm->ls_moves, prm->neighbourhood, off_cost, NULL);
+        for (int i = 0; i < P; i++) { keys[i].cost = cost[i]; keys[i].origin = i; }
+        for (int k = 0; k < L; k++) { keys[P + k].cost = off_cost[k]; keys[P + k].origin = P + k; }
+        qsort(keys, (size_t)(P + L), sizeof(keyed), cmp_keyed);
+        for (int i = 0; i < P; i++) {
+            int o = keys[i].origin;
+            const int *src = (o < P) ? population + (size_t)o * N : off + (size_t)(o - P) * N;
+            memcpy(next + (size_t)i * N, src, sizeof(int) * N);
+            next_cost[i] = keys[i].cost;
+        }
+        memcpy(population, next, sizeof(int) * (size_t)P * N);
+        memcpy(cost, next_cost, sizeof(double) * P);
+        best_trace[g] = cost[0];
+    }
+    free(off); free(next); free(off_cost); free(next_cost); free(keys);
+}
