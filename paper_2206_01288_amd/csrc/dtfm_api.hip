@@ -1,0 +1,253 @@
+// C ABI of libdtfm: argument checking, problem handle, scratch arena, dispatch to the kernels.
+#include "dtfm_internal.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+static thread_local char g_hip_error[256] = "";
+
+int dtfm_hip_fail(hipError_t e, const char *what)
+{
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+    (void)hipGetLastError();  // clear the sticky-less error slot
+    return DTFM_ERR_HIP;
+}
+
+extern "C" const char *dtfm_last_hip_error(void) { return g_hip_error; }
+
+extern "C" const char *dtfm_status_string(int status)
+{
+    switch (status) {
+    case DTFM_OK: return "ok";
+    case DTFM_ERR_NULL: return "null pointer";
+    case DTFM_ERR_SHAPE: return "bad shape (need N = D_dp * D_pp, all >= 1, D_pp <= 16, D_dp <= 64, N <= 1024)";
+    case DTFM_ERR_VALUE: return "bad value (latency/size must be finite and >= 0, bandwidth finite and > 0)";
+    case DTFM_ERR_ARG: return "bad argument";
+    case DTFM_ERR_HIP: return "HIP runtime error";
+    case DTFM_ERR_UNSUPPORTED: return "unsupported for this problem shape";
+    default: return "unknown status";
+    }
+}
+
+static int ensure_scratch(dtfm_problem *pr, size_t bytes)
+{
+    if (bytes <= pr->scratch_bytes) return DTFM_OK;
+    // earlier work on any stream may still use the old arena
+    DTFM_HIP(hipDeviceSynchronize());
+    if (pr->scratch != nullptr) {
+        DTFM_HIP(hipFree(pr->scratch));
+        pr->scratch = nullptr;
+        pr->scratch_bytes = 0;
+    }
+    size_t want = bytes + bytes / 8;  // head room so slightly larger calls do not reallocate
+    hipError_t e = hipMalloc((void **)&pr->scratch, want);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        want = bytes;
+        DTFM_HIP(hipMalloc((void **)&pr->scratch, want));
+    }
+    pr->scratch_bytes = want;
+    return DTFM_OK;
+}
+
+extern "C" int dtfm_create_problem(const double *latency, const double *bandwidth, int N, double c_dp,
+                                   double c_pp, int D_dp, int D_pp, dtfm_problem **out)
+{
+    if (out == nullptr) return DTFM_ERR_NULL;
+    *out = nullptr;
+    if (latency == nullptr || bandwidth == nullptr) return DTFM_ERR_NULL;
+    if (N < 1 || D_dp < 1 || D_pp < 1 || (long long)D_dp * D_pp != N || D_pp > DTFM_MAX_DPP ||
+        D_dp > DTFM_MAX_DDP || N > DTFM_MAX_N)
+        return DTFM_ERR_SHAPE;
+    if (!isfinite(c_dp) || !isfinite(c_pp) || c_dp < 0.0 || c_pp < 0.0) return DTFM_ERR_VALUE;
+    for (int d = 0; d < N; d++)
+        for (int e = 0; e < N; e++) {
+            if (d == e) continue;
+            double a = latency[(size_t)d * N + e], b = bandwidth[(size_t)d * N + e];
+            if (!isfinite(a) || a < 0.0 || !isfinite(b) || !(b > 0.0)) return DTFM_ERR_VALUE;
+        }
+
+    dtfm_problem *pr = new (std::nothrow) dtfm_problem();
+    if (pr == nullptr) return DTFM_ERR_HIP;
+    memset(pr, 0, sizeof(*pr));
+    pr->N = N;
+    pr->D_dp = D_dp;
+    pr->D_pp = D_pp;
+    pr->npairs = D_pp * (D_pp - 1) / 2;
+    pr->c_dp = c_dp;
+    pr->c_pp = c_pp;
+
+    // subsets of the D_pp stage nodes ordered by size, for the layered Held-Karp sweep
+    std::vector<uint32_t> subs;
+    subs.reserve(((size_t)1 << D_pp));
+    for (int k = 0; k <= D_pp + 1; k++) pr->hk_off.off[k] = 0;
+    for (int k = 1; k <= D_pp; k++) {
+        pr->hk_off.off[k] = (int)subs.size();
+        for (uint32_t S = 1; S < (1u << D_pp); S++)
+            if (__builtin_popcount(S) == k) subs.push_back(S);
+    }
+    pr->hk_off.off[D_pp + 1] = (int)subs.size();
+
+    double *lat_dev = nullptr, *bw_dev = nullptr;
+    size_t mat = (size_t)N * N * sizeof(double);
+    int rc = DTFM_OK;
+    auto fail = [&](int code) {
+        if (lat_dev) (void)hipFree(lat_dev);
+        if (bw_dev) (void)hipFree(bw_dev);
+        dtfm_destroy_problem(pr);
+        return code;
+    };
+#define CREATE_HIP(call)                                                    \
+    do {                                                                    \
+        hipError_t e__ = (call);                                            \
+        if (e__ != hipSuccess) return fail(dtfm_hip_fail(e__, #call));      \
+    } while (0)
+    CREATE_HIP(hipGetDevice(&pr->device));
+    CREATE_HIP(hipMalloc((void **)&pr->W_dp, mat));
+    CREATE_HIP(hipMalloc((void **)&pr->W_pp, mat));
+    CREATE_HIP(hipMalloc((void **)&pr->hk_subsets, subs.size() * sizeof(uint32_t)));
+    CREATE_HIP(hipMalloc((void **)&lat_dev, mat));
+    CREATE_HIP(hipMalloc((void **)&bw_dev, mat));
+    CREATE_HIP(hipMemcpy(pr->hk_subsets, subs.data(), subs.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+    CREATE_HIP(hipMemcpy(lat_dev, latency, mat, hipMemcpyHostToDevice));
+    CREATE_HIP(hipMemcpy(bw_dev, bandwidth, mat, hipMemcpyHostToDevice));
+    // the shard of Sec. 3.2: each device of a stage manages c_dp / D_dp bytes
+    double shard = c_dp / (double)D_dp;
+    rc = dtfm_weights_enqueue(lat_dev, bw_dev, N, shard, c_pp, pr->W_dp, pr->W_pp, (hipStream_t) nullptr);
+    if (rc != DTFM_OK) return fail(rc);
+    CREATE_HIP(hipDeviceSynchronize());
+    CREATE_HIP(hipFree(lat_dev));
+    lat_dev = nullptr;
+    CREATE_HIP(hipFree(bw_dev));
+    bw_dev = nullptr;
+#undef CREATE_HIP
+    *out = pr;
+    return DTFM_OK;
+}
+
+extern "C" void dtfm_destroy_problem(dtfm_problem *pr)
+{
+    if (pr == nullptr) return;
+    (void)hipDeviceSynchronize();
+    if (pr->W_dp) (void)hipFree(pr->W_dp);
+    if (pr->W_pp) (void)hipFree(pr->W_pp);
+    if (pr->hk_subsets) (void)hipFree(pr->hk_subsets);
+    if (pr->scratch) (void)hipFree(pr->scratch);
+    delete pr;
+}
+
+extern "C" int dtfm_get_weights(const dtfm_problem *pr, double *W_dp_host, double *W_pp_host)
+{
+    if (pr == nullptr) return DTFM_ERR_NULL;
+    size_t mat = (size_t)pr->N * pr->N * sizeof(double);
+    DTFM_HIP(hipDeviceSynchronize());
+    if (W_dp_host) DTFM_HIP(hipMemcpy(W_dp_host, pr->W_dp, mat, hipMemcpyDeviceToHost));
+    if (W_pp_host) DTFM_HIP(hipMemcpy(W_pp_host, pr->W_pp, mat, hipMemcpyDeviceToHost));
+    return DTFM_OK;
+}
+
+extern "C" int dtfm_eval_population(dtfm_problem *pr, const int32_t *perm, int P, double *cost,
+                                    void *hip_stream)
+{
+    if (pr == nullptr) return DTFM_ERR_NULL;
+    if (P < 0) return DTFM_ERR_ARG;
+    if (P == 0) return DTFM_OK;
+    if (perm == nullptr || cost == nullptr) return DTFM_ERR_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    dtfm_arena measure = {nullptr, 0};
+    dtfm_eval_carve(pr, measure, (size_t)P);
+    int rc = ensure_scratch(pr, measure.off);
+    if (rc != DTFM_OK) return rc;
+    dtfm_arena ar = {pr->scratch, 0};
+    dtfm_eval_bufs b = dtfm_eval_carve(pr, ar, (size_t)P);
+    return dtfm_eval_enqueue(pr, b, perm, (size_t)P, cost, st);
+}
+
+extern "C" int dtfm_coarsened_graph(dtfm_problem *pr, const int32_t *perm, int P, double *ghat,
+                                    double *datap, void *hip_stream)
+{
+    if (pr == nullptr) return DTFM_ERR_NULL;
+    if (P < 0) return DTFM_ERR_ARG;
+    if (P == 0) return DTFM_OK;
+    if (perm == nullptr) return DTFM_ERR_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    dtfm_arena measure = {nullptr, 0};
+    dtfm_eval_carve(pr, measure, (size_t)P);
+    int rc = ensure_scratch(pr, measure.off);
+    if (rc != DTFM_OK) return rc;
+    dtfm_arena ar = {pr->scratch, 0};
+    dtfm_eval_bufs b = dtfm_eval_carve(pr, ar, (size_t)P);
+    rc = dtfm_eval_enqueue(pr, b, perm, (size_t)P, nullptr, st);
+    if (rc != DTFM_OK) return rc;
+    size_t n = pr->D_pp;
+    if (ghat) DTFM_HIP(hipMemcpyAsync(ghat, b.ghat, (size_t)P * n * n * sizeof(double), hipMemcpyDeviceToDevice, st));
+    if (datap) DTFM_HIP(hipMemcpyAsync(datap, b.datap, (size_t)P * sizeof(double), hipMemcpyDeviceToDevice, st));
+    return DTFM_OK;
+}
+
+extern "C" int dtfm_validate_population(dtfm_problem *pr, const int32_t *perm, int P, int32_t *bad_rows,
+                                        void *hip_stream)
+{
+    if (pr == nullptr || bad_rows == nullptr) return DTFM_ERR_NULL;
+    if (P < 0) return DTFM_ERR_ARG;
+    if (P > 0 && perm == nullptr) return DTFM_ERR_NULL;
+    return dtfm_validate_enqueue(pr, perm, (size_t)P, bad_rows, (hipStream_t)hip_stream);
+}
+
+static int check_neighbourhood(const dtfm_problem *pr, int neighbourhood)
+{
+    if (neighbourhood != DTFM_ALL_PAIRS && neighbourhood != DTFM_GAIN4) return DTFM_ERR_ARG;
+    // the paper's neighbourhood needs a link inside a stage and a second stage to swap with
+    if (neighbourhood == DTFM_GAIN4 && (pr->D_dp < 2 || pr->D_pp < 2)) return DTFM_ERR_UNSUPPORTED;
+    return DTFM_OK;
+}
+
+extern "C" int dtfm_local_search(dtfm_problem *pr, int32_t *perm, int P, int moves, int neighbourhood,
+                                 double *cost, int64_t *applied, void *hip_stream)
+{
+    if (pr == nullptr) return DTFM_ERR_NULL;
+    if (P < 0 || moves < 0) return DTFM_ERR_ARG;
+    int rc = check_neighbourhood(pr, neighbourhood);
+    if (rc != DTFM_OK) return rc;
+    if (P == 0) return DTFM_OK;
+    if (perm == nullptr || cost == nullptr) return DTFM_ERR_NULL;
+    dtfm_arena measure = {nullptr, 0};
+    dtfm_ls_carve(pr, measure, (size_t)P, neighbourhood);
+    rc = ensure_scratch(pr, measure.off);
+    if (rc != DTFM_OK) return rc;
+    dtfm_arena ar = {pr->scratch, 0};
+    dtfm_ls_bufs b = dtfm_ls_carve(pr, ar, (size_t)P, neighbourhood);
+    return dtfm_ls_enqueue(pr, b, perm, (size_t)P, moves, neighbourhood, cost, applied, (hipStream_t)hip_stream);
+}
+
+extern "C" int dtfm_evolve(dtfm_problem *pr, uint64_t seed, int generations, const dtfm_ga_params *prm,
+                           int32_t *population, double *cost, double *best_trace, void *hip_stream)
+{
+    if (pr == nullptr || prm == nullptr || population == nullptr || cost == nullptr) return DTFM_ERR_NULL;
+    if (generations < 0 || prm->P < 1 || prm->lambda < 1 || prm->m_x < 0 || prm->m_m < 0 || prm->ls_moves < 0)
+        return DTFM_ERR_ARG;
+    if (generations > 0 && best_trace == nullptr) return DTFM_ERR_NULL;
+    int rc = check_neighbourhood(pr, prm->neighbourhood);
+    if (rc == DTFM_ERR_UNSUPPORTED && prm->ls_moves == 0) rc = DTFM_OK;  // neighbourhood unused
+    if (rc != DTFM_OK) return rc;
+    dtfm_arena measure = {nullptr, 0};
+    dtfm_ga_carve(pr, measure, *prm);
+    rc = ensure_scratch(pr, measure.off);
+    if (rc != DTFM_OK) return rc;
+    dtfm_arena ar = {pr->scratch, 0};
+    dtfm_ga_bufs b = dtfm_ga_carve(pr, ar, *prm);
+    return dtfm_ga_enqueue(pr, b, seed, generations, *prm, population, cost, best_trace, (hipStream_t)hip_stream);
+}
+
+extern "C" int dtfm_philox_blocks(uint64_t seed, uint32_t stream, uint32_t g, uint32_t k, uint32_t first_block,
+                                  int n_blocks, uint32_t *out, void *hip_stream)
+{
+    if (n_blocks < 0) return DTFM_ERR_ARG;
+    if (n_blocks > 0 && out == nullptr) return DTFM_ERR_NULL;
+    return dtfm_philox_enqueue(seed, stream, g, k, first_block, n_blocks, out, (hipStream_t)hip_stream);
+}

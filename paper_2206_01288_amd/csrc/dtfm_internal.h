@@ -1,0 +1,98 @@
+// Internal declarations shared by the translation units of libdtfm (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dtfm.h"
+
+#define DTFM_WAVE 64
+
+// Largest D_pp whose Held-Karp table (2^D_pp x D_pp fp64) is kept in LDS by the general kernel:
+// 2^10 * 10 * 8 B = 80 KiB of the CU's 160 KiB.
+#define DTFM_HK_LDS_MAX_DPP 10
+// Workgroups (= concurrently live tables) of the Held-Karp kernel when the table lives in HBM.
+#define DTFM_HK_GLOBAL_GRID 512
+
+struct dtfm_layer_off {
+    int off[DTFM_MAX_DPP + 2];  // off[k] = first index of the subsets of popcount k; off[n+1] = end
+};
+
+struct dtfm_problem {
+    int N, D_dp, D_pp, npairs;
+    int device;
+    double c_dp, c_pp;
+    double *W_dp;           // device, N*N
+    double *W_pp;           // device, N*N
+    uint32_t *hk_subsets;   // device, 2^D_pp - 1 subsets ordered by (popcount, value)
+    dtfm_layer_off hk_off;
+    char *scratch;          // device arena, grown on demand
+    size_t scratch_bytes;
+    bool fast64;            // shape handled by the fused small-shape kernels
+};
+
+// Bump allocator over the problem's scratch arena. With base == nullptr it only measures.
+struct dtfm_arena {
+    char *base;
+    size_t off;
+    template <typename T>
+    T *take(size_t count)
+    {
+        size_t bytes = (count * sizeof(T) + 255) & ~(size_t)255;
+        T *p = reinterpret_cast<T *>(base + off);
+        off += bytes;
+        return p;
+    }
+};
+
+int dtfm_hip_fail(hipError_t e, const char *what);
+#define DTFM_HIP(call)                                        \
+    do {                                                      \
+        hipError_t e__ = (call);                              \
+        if (e__ != hipSuccess) return dtfm_hip_fail(e__, #call); \
+    } while (0)
+
+// ---- general-shape evaluation (dtfm_eval.hip) -------------------------------------------------
+struct dtfm_eval_bufs {
+    double *datap;   // rows
+    double *ghat;    // rows * D_pp * D_pp
+    double *hk_tab;  // DTFM_HK_GLOBAL_GRID tables, or null when the table fits LDS
+};
+dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows);
+// enqueues a2..a6 for `rows` candidates; cost may be null (then only datap/ghat are produced)
+int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int32_t *perm,
+                      size_t rows, double *cost, hipStream_t st);
+int dtfm_weights_enqueue(const double *lat_dev, const double *bw_dev, int N, double shard,
+                         double c_pp, double *W_dp, double *W_pp, hipStream_t st);
+
+// ---- search (dtfm_search.hip) -----------------------------------------------------------------
+struct dtfm_ls_bufs {
+    double *cur;        // P: current cost of each candidate
+    int32_t *tmp_perm;  // rows * N: candidates with a move applied
+    double *tmp_cost;   // rows
+    int32_t *move_ab;   // 2 * P (GAIN4: proposed positions)
+    size_t chunk;       // candidates per ALL_PAIRS chunk
+    size_t rows;        // rows evaluated per eval call
+    dtfm_eval_bufs ev;
+};
+dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int neighbourhood);
+int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm, size_t P, int moves,
+                    int neighbourhood, double *cost, int64_t *applied, hipStream_t st);
+
+struct dtfm_ga_bufs {
+    int32_t *off;       // lambda * N
+    double *off_cost;   // lambda
+    int32_t *next;      // P * N
+    double *next_cost;  // P
+    int32_t *src;       // P: origin index of each survivor
+    dtfm_ls_bufs ls;
+};
+dtfm_ga_bufs dtfm_ga_carve(const dtfm_problem *pr, dtfm_arena &ar, const dtfm_ga_params &prm);
+int dtfm_ga_enqueue(const dtfm_problem *pr, const dtfm_ga_bufs &b, uint64_t seed, int generations,
+                    const dtfm_ga_params &prm, int32_t *population, double *cost, double *best_trace,
+                    hipStream_t st);
+int dtfm_philox_enqueue(uint64_t seed, uint32_t stream, uint32_t g, uint32_t k, uint32_t first_block,
+                        int n_blocks, uint32_t *out, hipStream_t st);
+int dtfm_validate_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t P, int32_t *bad_rows,
+                          hipStream_t st);

@@ -1,0 +1,536 @@
+// Search kernels (Sec. 3.4): swap-move local search (exhaustive and the paper's four-candidate
+// neighbourhood) and the generation-wise genetic loop (selection, crossover, mutation,
+// replacement), general shapes. Every cost they compare is the full cost of Eq. 1 as produced by
+// the evaluation kernels, so a move's cost is bit-identical to evaluating the swapped allocation.
+#include "dtfm_internal.h"
+
+#include <math.h>
+
+// Rows evaluated per call while enumerating the exhaustive neighbourhood.
+#define DTFM_LS_ROWS_MAX ((size_t)1 << 18)
+
+// ------------------------------------------------------------------------------------------------
+// index <-> pair (a < b) among n items in lexicographic order (0,1),(0,2),...,(0,n-1),(1,2),...
+__device__ __forceinline__ long long pair_base(int n, int a)
+{
+    return (long long)a * n - (long long)a * (a + 1) / 2;
+}
+
+__device__ __forceinline__ void pair_decode(int n, long long m, int &a, int &b)
+{
+    double disc = (2.0 * n - 1.0) * (2.0 * n - 1.0) - 8.0 * (double)m;
+    int g = (int)(((2.0 * n - 1.0) - sqrt(disc > 0.0 ? disc : 0.0)) * 0.5);
+    if (g < 0) g = 0;
+    if (g > n - 2) g = n - 2;
+    while (g > 0 && pair_base(n, g) > m) g--;
+    while (g < n - 2 && pair_base(n, g + 1) <= m) g++;
+    a = g;
+    b = g + 1 + (int)(m - pair_base(n, g));
+}
+
+__device__ __forceinline__ long long pair_encode(int n, int a, int b)
+{
+    return pair_base(n, a) + (b - a - 1);
+}
+
+// ------------------------------------------------------------------------------------------------
+// ALL_PAIRS: materialise, for candidates p0 .. p0+cp-1, every allocation one swap away
+// (row (p - p0) * M + m = candidate p with the positions of move m exchanged).
+__global__ void k_make_swapped(const int32_t *__restrict__ perm, int N, long long M, size_t p0,
+                               int32_t *__restrict__ tmp_perm)
+{
+    size_t rowi = blockIdx.x;
+    size_t pc = rowi / (size_t)M;
+    long long m = (long long)(rowi - pc * (size_t)M);
+    int a, b;
+    pair_decode(N, m, a, b);
+    const int32_t *src = perm + (p0 + pc) * N;
+    int32_t *dst = tmp_perm + rowi * N;
+    for (int q = threadIdx.x; q < N; q += blockDim.x) {
+        int s = q == a ? b : (q == b ? a : q);
+        dst[q] = src[s];
+    }
+}
+
+// ALL_PAIRS: per candidate, the cheapest move (lowest index on ties); applied only if strictly
+// cheaper than the current cost.
+__global__ void k_pick_apply(int32_t *__restrict__ perm, int N, long long M, size_t p0,
+                             const double *__restrict__ tmp_cost, double *__restrict__ cur,
+                             int64_t *__restrict__ applied, int moves, int r)
+{
+    __shared__ double s_c[256];
+    __shared__ long long s_i[256];
+    size_t pc = blockIdx.x, p = p0 + pc;
+    const double *c = tmp_cost + pc * (size_t)M;
+    double best = INFINITY;
+    long long bi = -1;
+    for (long long m = threadIdx.x; m < M; m += blockDim.x) {
+        double v = c[m];
+        if (v < best) {  // ascending m within a thread: first minimiser kept
+            best = v;
+            bi = m;
+        }
+    }
+    s_c[threadIdx.x] = best;
+    s_i[threadIdx.x] = bi;
+    __syncthreads();
+    for (int o = blockDim.x / 2; o >= 1; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            double oc = s_c[threadIdx.x + o];
+            long long oi = s_i[threadIdx.x + o];
+            bool take = oi >= 0 && (s_i[threadIdx.x] < 0 || oc < s_c[threadIdx.x] ||
+                                    (oc == s_c[threadIdx.x] && oi < s_i[threadIdx.x]));
+            if (take) {
+                s_c[threadIdx.x] = oc;
+                s_i[threadIdx.x] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        long long mv = -1;
+        if (s_i[0] >= 0 && s_c[0] < cur[p]) {
+            int a, b;
+            pair_decode(N, s_i[0], a, b);
+            int32_t *row = perm + p * N;
+            int32_t t = row[a];
+            row[a] = row[b];
+            row[b] = t;
+            cur[p] = s_c[0];
+            mv = s_i[0];
+        }
+        if (applied != nullptr) applied[p * (size_t)moves + r] = mv;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// GAIN4 proposal for round r, one wavefront per candidate. Stage pair (j, j') = pair number
+// r mod D_pp(D_pp-1)/2; fastest link inside each stage = lexicographically first minimiser of W_pp
+// over slot pairs; the four end-point swaps ranked by the paper's Gain (sums over the pre-swap
+// sets in slot order from +0.0, divided by D_dp, four terms combined left to right), first
+// maximiser wins. Writes the swapped allocation and the two positions.
+__global__ void k_gain4_propose(const double *__restrict__ W_pp, const int32_t *__restrict__ perm,
+                                int N, int D_dp, int D_pp, int r, int32_t *__restrict__ tmp_perm,
+                                int32_t *__restrict__ move_ab)
+{
+    const int lane = threadIdx.x;
+    size_t p = blockIdx.x;
+    int npairs = D_pp * (D_pp - 1) / 2;
+    int j, jp;
+    pair_decode(D_pp, r % npairs, j, jp);
+    const int32_t *row = perm + p * N;
+    const int32_t *Cs[2] = {row + j * D_dp, row + jp * D_dp};
+    int slot[2][2];
+    double link[2];
+    long long E = (long long)D_dp * (D_dp - 1) / 2;
+    for (int s = 0; s < 2; s++) {
+        const int32_t *C = Cs[s];
+        double best = INFINITY;
+        long long be = E;
+        for (long long e = lane; e < E; e += DTFM_WAVE) {
+            int i, k;
+            pair_decode(D_dp, e, i, k);
+            double w = W_pp[(size_t)C[i] * N + C[k]];
+            if (w < best) {
+                best = w;
+                be = e;
+            }
+        }
+        for (int o = 32; o >= 1; o >>= 1) {
+            double ow = __shfl_xor(best, o);
+            long long oe = __shfl_xor(be, o);
+            if (ow < best || (ow == best && oe < be)) {
+                best = ow;
+                be = oe;
+            }
+        }
+        if (be >= E) be = 0;  // only on malformed (non-finite) weights
+        pair_decode(D_dp, be, slot[s][0], slot[s][1]);
+        link[s] = best;
+    }
+    // lanes 0,1: mean over C_j' of w[x][.] for x = d1, d2; lanes 2,3: mean over C_j of w[y][.]
+    double mean = 0.0;
+    if (lane < 4) {
+        int s = lane >> 1;                      // which stage the moving device is in
+        int dev = Cs[s][slot[s][lane & 1]];
+        const int32_t *other = Cs[1 - s];
+        double sum = 0.0;
+        for (int i = 0; i < D_dp; i++) sum = __dadd_rn(sum, W_pp[(size_t)dev * N + other[i]]);
+        mean = __ddiv_rn(sum, (double)D_dp);
+    }
+    double mx[2] = {__shfl(mean, 0), __shfl(mean, 1)};
+    double my[2] = {__shfl(mean, 2), __shfl(mean, 3)};
+    double bestg = 0.0;
+    int bk = -1;
+    for (int k = 0; k < 4; k++) {
+        double g = mx[k >> 1];
+        g = __dadd_rn(g, -link[0]);   // w[x][mate(x)]: the fast link inside C_j
+        g = __dadd_rn(g, my[k & 1]);
+        g = __dadd_rn(g, -link[1]);   // w[y][mate(y)]: the fast link inside C_j'
+        if (bk < 0 || g > bestg) {
+            bestg = g;
+            bk = k;
+        }
+    }
+    int a = j * D_dp + slot[0][bk >> 1], b = jp * D_dp + slot[1][bk & 1];
+    int32_t *dst = tmp_perm + p * N;
+    for (int q = lane; q < N; q += DTFM_WAVE) {
+        int s = q == a ? b : (q == b ? a : q);
+        dst[q] = row[s];
+    }
+    if (lane == 0) {
+        move_ab[2 * p] = a;
+        move_ab[2 * p + 1] = b;
+    }
+}
+
+// GAIN4: accept the proposed swap iff its cost is strictly lower.
+__global__ void k_accept(int32_t *__restrict__ perm, int N, const double *__restrict__ tmp_cost,
+                         double *__restrict__ cur, const int32_t *__restrict__ move_ab,
+                         int64_t *__restrict__ applied, int moves, int r, size_t P)
+{
+    size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    long long mv = -1;
+    if (tmp_cost[p] < cur[p]) {
+        int a = move_ab[2 * p], b = move_ab[2 * p + 1];
+        int32_t *row = perm + p * N;
+        int32_t t = row[a];
+        row[a] = row[b];
+        row[b] = t;
+        cur[p] = tmp_cost[p];
+        mv = pair_encode(N, a, b);
+    }
+    if (applied != nullptr) applied[p * (size_t)moves + r] = mv;
+}
+
+__global__ void k_copy_f64(const double *__restrict__ src, double *__restrict__ dst, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+__global__ void k_copy_i32(const int32_t *__restrict__ src, int32_t *__restrict__ dst, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+__global__ void k_fill_i64(int64_t *__restrict__ dst, int64_t v, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = v;
+}
+
+dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int neighbourhood)
+{
+    dtfm_ls_bufs b;
+    size_t N = pr->N, M = N * (N - 1) / 2;
+    b.cur = ar.take<double>(P);
+    b.move_ab = ar.take<int32_t>(2 * P);
+    if (neighbourhood == DTFM_ALL_PAIRS && M > 0) {
+        size_t chunk = DTFM_LS_ROWS_MAX / M;
+        if (chunk < 1) chunk = 1;
+        if (chunk > P) chunk = P;
+        b.chunk = chunk;
+        b.rows = chunk * M > P ? chunk * M : P;
+    } else {
+        b.chunk = P;
+        b.rows = P;
+    }
+    b.tmp_perm = ar.take<int32_t>(b.rows * N);
+    b.tmp_cost = ar.take<double>(b.rows);
+    b.ev = dtfm_eval_carve(pr, ar, b.rows);
+    return b;
+}
+
+int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm, size_t P, int moves,
+                    int neighbourhood, double *cost, int64_t *applied, hipStream_t st)
+{
+    if (P == 0) return DTFM_OK;
+    const int N = pr->N;
+    const long long M = (long long)N * (N - 1) / 2;
+    int rc = dtfm_eval_enqueue(pr, b.ev, perm, P, b.cur, st);
+    if (rc != DTFM_OK) return rc;
+    for (int r = 0; r < moves; r++) {
+        if (neighbourhood == DTFM_ALL_PAIRS) {
+            if (M == 0) {
+                if (applied != nullptr) {
+                    size_t n = P * (size_t)moves;
+                    hipLaunchKernelGGL(k_fill_i64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, applied,
+                                       (int64_t)-1, n);
+                    DTFM_HIP(hipGetLastError());
+                }
+                break;
+            }
+            for (size_t p0 = 0; p0 < P; p0 += b.chunk) {
+                size_t cp = P - p0 < b.chunk ? P - p0 : b.chunk;
+                size_t rows = cp * (size_t)M;
+                hipLaunchKernelGGL(k_make_swapped, dim3((unsigned)rows), dim3(DTFM_WAVE), 0, st, perm, N, M, p0,
+                                   b.tmp_perm);
+                DTFM_HIP(hipGetLastError());
+                rc = dtfm_eval_enqueue(pr, b.ev, b.tmp_perm, rows, b.tmp_cost, st);
+                if (rc != DTFM_OK) return rc;
+                hipLaunchKernelGGL(k_pick_apply, dim3((unsigned)cp), dim3(256), 0, st, perm, N, M, p0, b.tmp_cost,
+                                   b.cur, applied, moves, r);
+                DTFM_HIP(hipGetLastError());
+            }
+        } else {
+            hipLaunchKernelGGL(k_gain4_propose, dim3((unsigned)P), dim3(DTFM_WAVE), 0, st, pr->W_pp, perm, N,
+                               pr->D_dp, pr->D_pp, r, b.tmp_perm, b.move_ab);
+            DTFM_HIP(hipGetLastError());
+            rc = dtfm_eval_enqueue(pr, b.ev, b.tmp_perm, P, b.tmp_cost, st);
+            if (rc != DTFM_OK) return rc;
+            hipLaunchKernelGGL(k_accept, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, perm, N, b.tmp_cost,
+                               b.cur, b.move_ab, applied, moves, r, P);
+            DTFM_HIP(hipGetLastError());
+        }
+    }
+    hipLaunchKernelGGL(k_copy_f64, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, b.cur, cost, P);
+    DTFM_HIP(hipGetLastError());
+    return DTFM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds; each round multiplies counter
+// words 0 and 2 by the two round multipliers, mixes the high halves with words 1, 3 and the key,
+// and the key advances by the two Weyl increments.
+struct philox_out {
+    uint32_t w[4];
+};
+
+__device__ __forceinline__ philox_out philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                    uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int i = 0; i < 10; i++) {
+        uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    philox_out o;
+    o.w[0] = c0;
+    o.w[1] = c1;
+    o.w[2] = c2;
+    o.w[3] = c3;
+    return o;
+}
+
+enum { STREAM_INIT = 0, STREAM_SELECT = 1, STREAM_CROSSOVER = 2, STREAM_MUTATION = 3 };
+
+__device__ __forceinline__ uint32_t randint(uint32_t x, uint32_t n) { return __umulhi(x, n); }
+
+__global__ void k_philox_blocks(uint32_t k0, uint32_t k1, uint32_t stream, uint32_t g, uint32_t k,
+                                uint32_t first_block, int n_blocks, uint32_t *__restrict__ out)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= n_blocks) return;
+    philox_out o = philox4x32_10(first_block + (uint32_t)b, k, g, stream, k0, k1);
+    for (int i = 0; i < 4; i++) out[4 * b + i] = o.w[i];
+}
+
+int dtfm_philox_enqueue(uint64_t seed, uint32_t stream, uint32_t g, uint32_t k, uint32_t first_block,
+                        int n_blocks, uint32_t *out, hipStream_t st)
+{
+    if (n_blocks == 0) return DTFM_OK;
+    hipLaunchKernelGGL(k_philox_blocks, dim3((n_blocks + 63) / 64), dim3(64), 0, st, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), stream, g, k, first_block, n_blocks, out);
+    DTFM_HIP(hipGetLastError());
+    return DTFM_OK;
+}
+
+// Initial population: candidate k = Fisher-Yates shuffle of the identity, i = N-1 .. 1,
+// j = randint(i+1) from draw number N-1-i of stream INIT. The draws are generated by all lanes,
+// the dependent swaps by lane 0.
+__global__ void k_init_population(uint32_t k0, uint32_t k1, int N, int32_t *__restrict__ pop)
+{
+    extern __shared__ int32_t sm[];
+    int32_t *perm = sm, *jd = sm + N;
+    uint32_t k = blockIdx.x;
+    for (int q = threadIdx.x; q < N; q += blockDim.x) perm[q] = q;
+    for (int blk = threadIdx.x; 4 * blk < N - 1; blk += blockDim.x) {
+        philox_out o = philox4x32_10((uint32_t)blk, k, 0u, STREAM_INIT, k0, k1);
+        for (int i = 0; i < 4; i++) {
+            int t = 4 * blk + i;
+            if (t < N - 1) jd[t] = (int32_t)randint(o.w[i], (uint32_t)(N - t));  // i+1 = N-1-t+1
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int t = 0; t < N - 1; t++) {
+            int i = N - 1 - t, j = jd[t];
+            int32_t x = perm[i];
+            perm[i] = perm[j];
+            perm[j] = x;
+        }
+    }
+    __syncthreads();
+    for (int q = threadIdx.x; q < N; q += blockDim.x) pop[(size_t)k * N + q] = perm[q];
+}
+
+// One offspring per workgroup: selection (two uniform parents), crossover (child = parent 1; m_x
+// times a random device that parent 2 keeps in another stage is swapped with the device at a
+// random slot of that stage), mutation (m_m random transpositions). Copies and inversions are
+// done by all lanes, the dependent steps by lane 0 in LDS.
+__global__ void k_make_offspring(uint32_t k0, uint32_t k1, uint32_t g, const int32_t *__restrict__ pop,
+                                 int P, int N, int D_dp, int m_x, int m_m, int32_t *__restrict__ off)
+{
+    extern __shared__ int32_t sm[];
+    int32_t *child = sm, *pos_child = sm + N, *pos_par2 = sm + 2 * N;
+    uint32_t k = blockIdx.x;
+    philox_out sel = philox4x32_10(0u, k, g, STREAM_SELECT, k0, k1);
+    int p1 = (int)randint(sel.w[0], (uint32_t)P), p2 = (int)randint(sel.w[1], (uint32_t)P);
+    const int32_t *par1 = pop + (size_t)p1 * N, *par2 = pop + (size_t)p2 * N;
+    for (int q = threadIdx.x; q < N; q += blockDim.x) {
+        int32_t d = par1[q];
+        child[q] = d;
+        pos_child[d] = q;
+        pos_par2[par2[q]] = q;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        philox_out o;
+        for (int t = 0; t < m_x; t++) {
+            if ((t & 1) == 0) o = philox4x32_10((uint32_t)(t >> 1), k, g, STREAM_CROSSOVER, k0, k1);
+            int d = (int)randint(o.w[2 * (t & 1)], (uint32_t)N);
+            int slot = (int)randint(o.w[2 * (t & 1) + 1], (uint32_t)D_dp);
+            int qa = pos_child[d];
+            int s1 = qa / D_dp, s2 = pos_par2[d] / D_dp;
+            if (s1 == s2) continue;
+            int qb = s2 * D_dp + slot;
+            int e = child[qb];
+            child[qa] = e;
+            child[qb] = d;
+            pos_child[e] = qa;
+            pos_child[d] = qb;
+        }
+        for (int t = 0; t < m_m; t++) {
+            if ((t & 1) == 0) o = philox4x32_10((uint32_t)(t >> 1), k, g, STREAM_MUTATION, k0, k1);
+            int a = (int)randint(o.w[2 * (t & 1)], (uint32_t)N);
+            int b = (int)randint(o.w[2 * (t & 1) + 1], (uint32_t)N);
+            int32_t x = child[a];
+            child[a] = child[b];
+            child[b] = x;
+        }
+    }
+    __syncthreads();
+    for (int q = threadIdx.x; q < N; q += blockDim.x) off[(size_t)k * N + q] = child[q];
+}
+
+// Replacement: rank of element i among parents (origin 0..P-1) and offspring (origin P..P+L-1)
+// under the order (cost, origin); the P lowest survive, placed at their rank.
+__global__ void k_rank(const double *__restrict__ cost, const double *__restrict__ off_cost, int P, int L,
+                       double *__restrict__ next_cost, int32_t *__restrict__ src,
+                       double *__restrict__ trace_slot)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= P + L) return;
+    double ci = i < P ? cost[i] : off_cost[i - P];
+    int rank = 0;
+    for (int j = 0; j < P; j++) {
+        double cj = cost[j];
+        rank += (cj < ci || (cj == ci && j < i)) ? 1 : 0;
+    }
+    for (int j = 0; j < L; j++) {
+        double cj = off_cost[j];
+        rank += (cj < ci || (cj == ci && P + j < i)) ? 1 : 0;
+    }
+    if (rank < P) {
+        next_cost[rank] = ci;
+        src[rank] = i;
+        if (rank == 0) *trace_slot = ci;
+    }
+}
+
+__global__ void k_gather_rows(const int32_t *__restrict__ pop, const int32_t *__restrict__ off, int P, int N,
+                              const int32_t *__restrict__ src, int32_t *__restrict__ next)
+{
+    size_t r = blockIdx.x;
+    int o = src[r];
+    const int32_t *s = o < P ? pop + (size_t)o * N : off + (size_t)(o - P) * N;
+    for (int q = threadIdx.x; q < N; q += blockDim.x) next[r * N + q] = s[q];
+}
+
+dtfm_ga_bufs dtfm_ga_carve(const dtfm_problem *pr, dtfm_arena &ar, const dtfm_ga_params &prm)
+{
+    dtfm_ga_bufs b;
+    size_t P = prm.P, L = prm.lambda, N = pr->N;
+    b.off = ar.take<int32_t>(L * N);
+    b.off_cost = ar.take<double>(L);
+    b.next = ar.take<int32_t>(P * N);
+    b.next_cost = ar.take<double>(P);
+    b.src = ar.take<int32_t>(P);
+    b.ls = dtfm_ls_carve(pr, ar, P > L ? P : L, prm.neighbourhood);
+    return b;
+}
+
+int dtfm_ga_enqueue(const dtfm_problem *pr, const dtfm_ga_bufs &b, uint64_t seed, int generations,
+                    const dtfm_ga_params &prm, int32_t *population, double *cost, double *best_trace,
+                    hipStream_t st)
+{
+    const int N = pr->N, P = prm.P, L = prm.lambda;
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    if (!prm.warm_start) {
+        hipLaunchKernelGGL(k_init_population, dim3(P), dim3(DTFM_WAVE), 2 * N * sizeof(int32_t), st, k0, k1, N,
+                           population);
+        DTFM_HIP(hipGetLastError());
+    }
+    int rc = dtfm_eval_enqueue(pr, b.ls.ev, population, P, cost, st);
+    if (rc != DTFM_OK) return rc;
+    for (int g = 0; g < generations; g++) {
+        hipLaunchKernelGGL(k_make_offspring, dim3(L), dim3(DTFM_WAVE), 3 * N * sizeof(int32_t), st, k0, k1,
+                           (uint32_t)g, population, P, N, pr->D_dp, prm.m_x, prm.m_m, b.off);
+        DTFM_HIP(hipGetLastError());
+        rc = dtfm_ls_enqueue(pr, b.ls, b.off, L, prm.ls_moves, prm.neighbourhood, b.off_cost, nullptr, st);
+        if (rc != DTFM_OK) return rc;
+        hipLaunchKernelGGL(k_rank, dim3((P + L + 255) / 256), dim3(256), 0, st, cost, b.off_cost, P, L,
+                           b.next_cost, b.src, best_trace + g);
+        DTFM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(k_gather_rows, dim3(P), dim3(DTFM_WAVE), 0, st, population, b.off, P, N, b.src, b.next);
+        DTFM_HIP(hipGetLastError());
+        size_t n = (size_t)P * N;
+        hipLaunchKernelGGL(k_copy_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, b.next, population, n);
+        DTFM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(k_copy_f64, dim3((P + 255) / 256), dim3(256), 0, st, b.next_cost, cost, (size_t)P);
+        DTFM_HIP(hipGetLastError());
+    }
+    return DTFM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Validity of an allocation (Sec. 2): every device exactly once.
+__global__ void k_validate(const int32_t *__restrict__ perm, int N, int32_t *__restrict__ bad_rows)
+{
+    extern __shared__ int32_t seen[];
+    __shared__ int bad;
+    size_t p = blockIdx.x;
+    if (threadIdx.x == 0) bad = 0;
+    for (int q = threadIdx.x; q < N; q += blockDim.x) seen[q] = 0;
+    __syncthreads();
+    for (int q = threadIdx.x; q < N; q += blockDim.x) {
+        int d = perm[p * N + q];
+        if (d < 0 || d >= N) bad = 1;
+        else if (atomicAdd(&seen[d], 1) != 0) bad = 1;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && bad) atomicAdd(bad_rows, 1);
+}
+
+__global__ void k_zero_i32(int32_t *p) { *p = 0; }
+
+int dtfm_validate_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t P, int32_t *bad_rows,
+                          hipStream_t st)
+{
+    hipLaunchKernelGGL(k_zero_i32, dim3(1), dim3(1), 0, st, bad_rows);
+    DTFM_HIP(hipGetLastError());
+    if (P == 0) return DTFM_OK;
+    hipLaunchKernelGGL(k_validate, dim3((unsigned)P), dim3(DTFM_WAVE), pr->N * sizeof(int32_t), st, perm, pr->N,
+                       bad_rows);
+    DTFM_HIP(hipGetLastError());
+    return DTFM_OK;
+}

@@ -1,0 +1,155 @@
+"""GPU parity: libdtfm (through the C ABI) against the CPU oracle, cost model part (Eqs. 1-4)."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2206_01288_amd as dtfm
+import workloads
+from tests.gpu_util import assert_costs_equal, both, custom, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C2b", "C3h", "C4", "C5"])
+def test_weights_bit_exact(name):
+    w = workloads.config(name)
+    o, g = both(w)
+    W_dp, W_pp = dtfm.get_weights(g)
+    assert np.array_equal(W_dp, o.W_dp) and np.array_equal(W_pp, o.W_pp)
+
+
+def test_weights_asymmetric_input():
+    lat, bw = workloads.network_two_site_asymmetric(4)
+    w = workloads.Workload("asym", 8, 4, 2, 4e8, 1e7, lat, bw, 0)
+    o, g = both(w)
+    W_dp, W_pp = dtfm.get_weights(g)
+    assert np.array_equal(W_dp, o.W_dp) and np.array_equal(W_pp, o.W_pp)
+
+
+def test_config1_population_and_every_allocation():
+    w = workloads.config("C1")
+    o, g = both(w)
+    perms = workloads.random_population(64, 8, seed=1)
+    assert_costs_equal(host(dtfm.eval_population(g, dev(perms))), o.eval_population(perms))
+    allp = np.array(list(itertools.permutations(range(8))), dtype=np.int32)
+    c = host(dtfm.eval_population(g, dev(allp)))
+    ref = o.eval_population(allp)
+    assert_costs_equal(c, ref)
+    assert int(np.argmin(c)) == int(np.argmin(ref))     # argmin, lowest index on ties
+
+
+@pytest.mark.parametrize("name,P", [("C2", 4096), ("C2b", 1024), ("C3h", 256)])
+def test_config2_full_population(name, P):
+    w = workloads.config(name)
+    o, g = both(w)
+    perms = workloads.random_population(P, 64, seed=1)
+    dperm = dev(perms)
+    c = host(dtfm.eval_population(g, dperm))
+    assert_costs_equal(c, o.eval_population(perms))
+    assert int(np.argmin(c)) == int(np.argmin(o.eval_population(perms)))
+    ghat, datap = dtfm.coarsened_graph(g, dperm[:64].contiguous())
+    ghat, datap = host(ghat), host(datap)
+    for p in range(64):
+        assert np.array_equal(ghat[p], o.coarsen(perms[p]))
+        assert datap[p] == o.datap(perms[p])
+    if name == "C3h":
+        assert np.all(c == c[0])
+
+
+def test_config4_full_population_sampled():
+    w = workloads.config("C4")
+    o, g = both(w)
+    perms = workloads.random_population(1024, 256, seed=1)
+    c = host(dtfm.eval_population(g, dev(perms)))
+    idx = np.random.default_rng(0).choice(1024, size=48, replace=False)
+    assert_costs_equal(c[idx], o.eval_population(perms[idx]))
+    # properties that hold for every row: reversal of the pipeline keeps the bits
+    rev = perms.reshape(1024, 16, 16)[:, ::-1, :].reshape(1024, 256).copy()
+    assert np.array_equal(host(dtfm.eval_population(g, dev(rev))), c)
+
+
+def test_config5_population_sampled():
+    w = workloads.config("C5")
+    o, g = both(w)
+    perms = workloads.random_population(256, 1024, seed=1)
+    dperm = dev(perms)
+    c = host(dtfm.eval_population(g, dperm))
+    idx = [0, 1, 100, 255]
+    assert_costs_equal(c[idx], o.eval_population(perms[idx]))
+    ghat, datap = dtfm.coarsened_graph(g, dperm[:2].contiguous())
+    assert np.array_equal(host(ghat)[1], o.coarsen(perms[1]))
+    rev = perms.reshape(256, 16, 64)[:, ::-1, :].reshape(256, 1024).copy()
+    assert np.array_equal(host(dtfm.eval_population(g, dev(rev))), c)
+
+
+@pytest.mark.parametrize("D_dp,D_pp", [(1, 1), (1, 5), (5, 1), (2, 2), (3, 4), (7, 3), (4, 9), (3, 10),
+                                        (2, 11), (5, 12), (33, 2), (64, 3), (16, 8), (8, 16)])
+def test_odd_and_degenerate_shapes(D_dp, D_pp):
+    N = D_dp * D_pp
+    w = custom(N, D_dp, D_pp, seed=N + 1)
+    o, g = both(w)
+    for P in (1, 67):
+        perms = workloads.random_population(P, N, seed=P)
+        assert_costs_equal(host(dtfm.eval_population(g, dev(perms))), o.eval_population(perms))
+
+
+def test_ragged_population_sizes_and_empty():
+    w = workloads.config("C2")
+    o, g = both(w)
+    for P in (1, 3, 63, 65, 255, 257):
+        perms = workloads.random_population(P, 64, seed=P)
+        assert_costs_equal(host(dtfm.eval_population(g, dev(perms))), o.eval_population(perms))
+    empty = torch.empty((0, 64), dtype=torch.int32, device="cuda")
+    assert dtfm.eval_population(g, empty).numel() == 0
+
+
+def test_ties_heavy_matching_blocks():
+    # rounded weights: many equal entries in every matching block and many equal path sums
+    lat, bw = workloads.network_iid(48, seed=5)
+    lat = np.round(lat * 200) / 200 + 0.005
+    bw = np.full_like(bw, 1e9)
+    w = workloads.Workload("ties", 48, 6, 8, 0.0, 0.0, lat, bw, 0)
+    o, g = both(w)
+    perms = workloads.random_population(300, 48, seed=2)
+    assert_costs_equal(host(dtfm.eval_population(g, dev(perms))), o.eval_population(perms))
+
+
+def test_deterministic_and_stream_ordered():
+    w = workloads.config("C2")
+    o, g = both(w)
+    perms = dev(workloads.random_population(1000, 64, seed=9))
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        a = dtfm.eval_population(g, perms)
+        b = dtfm.eval_population(g, perms)
+    s.synchronize()
+    assert torch.equal(a, b)
+
+
+def test_validate_population():
+    w = workloads.config("C2")
+    o, g = both(w)
+    perms = workloads.random_population(100, 64, seed=3)
+    assert dtfm.validate_population(g, dev(perms)) == 0
+    perms[7, 3] = perms[7, 4]
+    perms[50, 0] = 64
+    perms[99, 63] = -1
+    assert dtfm.validate_population(g, dev(perms)) == 3
+
+
+def test_error_paths_on_device():
+    w = workloads.config("C1")
+    o, g = both(w)
+    L = dtfm.load_library()
+    perms = dev(workloads.random_population(4, 8, seed=0))
+    cost = torch.empty(4, dtype=torch.float64, device="cuda")
+    assert L.dtfm_eval_population(g.handle, perms.data_ptr(), -1, cost.data_ptr(), None) == 4
+    assert L.dtfm_eval_population(g.handle, None, 4, cost.data_ptr(), None) == 1
+    assert L.dtfm_local_search(g.handle, perms.data_ptr(), 4, 1, 7, cost.data_ptr(), None, None) == 4
+    w1 = custom(5, 1, 5, seed=1)
+    o1, g1 = both(w1)
+    p1 = dev(workloads.random_population(4, 5, seed=0))
+    assert L.dtfm_local_search(g1.handle, p1.data_ptr(), 4, 1, dtfm.GAIN4, cost.data_ptr(), None, None) == 6

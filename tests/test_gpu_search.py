@@ -1,0 +1,150 @@
+"""GPU parity: local search and evolutionary loop against the CPU oracle, bit for bit."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2206_01288_amd as dtfm
+import workloads
+from tests.gpu_util import assert_costs_equal, both, custom, dev, host
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _ls_parity(w, perms, moves, nb):
+    o, g = both(w)
+    ref_perm, ref_cost, ref_applied = o.local_search(perms, moves, nb)
+    d = dev(perms)
+    cost, applied = dtfm.local_search(g, d, moves, nb, want_applied=True)
+    assert np.array_equal(host(d), ref_perm)
+    assert np.array_equal(host(applied), ref_applied)
+    assert_costs_equal(host(cost), ref_cost)
+    return ref_applied
+
+
+def test_all_pairs_config1():
+    w = workloads.config("C1")
+    applied = _ls_parity(w, workloads.random_population(64, 8, seed=1), 6, dtfm.ALL_PAIRS)
+    assert (applied >= 0).any() and (applied < 0).any()
+
+
+def test_all_pairs_config3_sample():
+    w = workloads.config("C3")
+    applied = _ls_parity(w, workloads.random_population(6, 64, seed=1), 3, dtfm.ALL_PAIRS)
+    assert (applied >= 0).all()
+
+
+def test_all_pairs_homogeneous_never_moves():
+    w = workloads.config("C3h")
+    o, g = both(w)
+    perms = workloads.random_population(96, 64, seed=1)
+    d = dev(perms)
+    cost, applied = dtfm.local_search(g, d, 2, dtfm.ALL_PAIRS, want_applied=True)
+    assert np.array_equal(host(d), perms) and np.all(host(applied) == -1)
+    c = host(cost)
+    alpha, beta = 0.1e-3, 100e9 / 8
+    closed = 2 * 7 * (alpha + w.c_dp / (8 * beta)) + 7 * 2 * (alpha + w.c_pp / beta)
+    assert np.all(c == c[0]) and abs(c[0] - closed) <= 1e-12 * closed
+
+
+def test_all_pairs_ties_take_lowest_index():
+    lat, bw = workloads.network_paper_table("paper_case4_network.txt", 3)
+    w = workloads.Workload("case4", 12, 3, 4, 1e8, 4e6, lat, bw, 0)
+    _ls_parity(w, workloads.random_population(40, 12, seed=8), 4, dtfm.ALL_PAIRS)
+
+
+@pytest.mark.parametrize("D_dp,D_pp,P,moves", [(2, 2, 9, 3), (3, 4, 33, 5), (1, 6, 5, 2), (6, 1, 5, 2), (1, 1, 3, 2)])
+def test_all_pairs_odd_shapes(D_dp, D_pp, P, moves):
+    N = D_dp * D_pp
+    _ls_parity(custom(N, D_dp, D_pp, seed=N), workloads.random_population(P, N, seed=4), moves, dtfm.ALL_PAIRS)
+
+
+def test_gain4_config2():
+    w = workloads.config("C2")
+    applied = _ls_parity(w, workloads.random_population(64, 64, seed=5), 40, dtfm.GAIN4)
+    assert (applied >= 0).any()
+
+
+def test_gain4_paper_table_ties():
+    w = workloads.config("C2b")
+    _ls_parity(w, workloads.random_population(32, 64, seed=6), 30, dtfm.GAIN4)
+
+
+def test_gain4_config4_and_5_small():
+    w = workloads.config("C4")
+    _ls_parity(w, workloads.random_population(6, 256, seed=5), 4, dtfm.GAIN4)
+    w = workloads.config("C5")
+    _ls_parity(w, workloads.random_population(2, 1024, seed=5), 3, dtfm.GAIN4)
+
+
+@pytest.mark.parametrize("D_dp,D_pp", [(2, 2), (3, 5), (2, 7), (9, 2)])
+def test_gain4_odd_shapes(D_dp, D_pp):
+    N = D_dp * D_pp
+    _ls_parity(custom(N, D_dp, D_pp, seed=N), workloads.random_population(20, N, seed=4), 12, dtfm.GAIN4)
+
+
+def test_zero_moves_is_plain_evaluation():
+    w = workloads.config("C2")
+    o, g = both(w)
+    perms = workloads.random_population(50, 64, seed=2)
+    d = dev(perms)
+    cost, _ = dtfm.local_search(g, d, 0, dtfm.ALL_PAIRS)
+    assert np.array_equal(host(d), perms)
+    assert_costs_equal(host(cost), o.eval_population(perms))
+
+
+# ---------------------------------------------------------------- Philox + evolve
+def test_philox_known_answers_on_device():
+    with open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) as f:
+        rows = [[int(t, 16) for t in l.split()] for l in f if l.strip() and not l.startswith("#")]
+    for v in rows:
+        # counter = (block, k, g, stream); key = (seed low, seed high)
+        out = dtfm.philox_blocks(seed=v[4] | (v[5] << 32), stream_id=v[3], g=v[2], k=v[1], first_block=v[0],
+                                 n_blocks=1)
+        assert [int(x) & 0xFFFFFFFF for x in host(out)] == v[6:10]
+    out = host(dtfm.philox_blocks(seed=7, stream_id=2, g=3, k=5, first_block=10, n_blocks=5))
+    for b in range(5):
+        assert [int(x) & 0xFFFFFFFF for x in out[4 * b:4 * b + 4]] == oracle.philox4x32_10([10 + b, 5, 3, 2], [7, 0])
+
+
+def _evolve_parity(w, seed, gens, P, **kw):
+    o, g = both(w)
+    rp, rc, rt = o.evolve(seed, gens, P, **kw)
+    pop, cost, trace = dtfm.evolve(g, seed, gens, P, **kw)
+    assert np.array_equal(host(pop), rp)
+    assert_costs_equal(host(cost), rc)
+    assert np.array_equal(host(trace), rt)
+    return rt
+
+
+def test_evolve_config1():
+    w = workloads.config("C1")
+    _evolve_parity(w, 0, 12, 16, ls_moves=2, neighbourhood=dtfm.GAIN4)
+    _evolve_parity(w, 2, 6, 16, ls_moves=3, neighbourhood=dtfm.ALL_PAIRS)
+    _evolve_parity(w, 3, 0, 7)
+    _evolve_parity(w, 4, 5, 9, lam=4, m_x=3, m_m=2, ls_moves=0)
+
+
+def test_evolve_config2_shape():
+    w = workloads.config("C2")
+    trace = _evolve_parity(w, 1, 6, 48, ls_moves=8, neighbourhood=dtfm.GAIN4)
+    assert np.all(np.diff(trace) <= 0)
+
+
+def test_evolve_config5_shape_small_population():
+    w = workloads.config("C5")
+    _evolve_parity(w, 7, 2, 5, ls_moves=2, neighbourhood=dtfm.GAIN4)
+
+
+def test_evolve_warm_start_and_determinism():
+    w = workloads.config("C2")
+    o, g = both(w)
+    pop0 = workloads.random_population(24, 64, seed=3)
+    rp, rc, rt = o.evolve(5, 3, 24, ls_moves=4, population=pop0)
+    pop, cost, trace = dtfm.evolve(g, 5, 3, 24, ls_moves=4, population=dev(pop0))
+    assert np.array_equal(host(pop), rp) and np.array_equal(host(trace), rt)
+    pop2, cost2, trace2 = dtfm.evolve(g, 5, 3, 24, ls_moves=4, population=dev(pop0))
+    assert torch.equal(pop, pop2) and torch.equal(cost, cost2) and torch.equal(trace, trace2)
