@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the scheduler hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Workload: configuration C2 of the build (N=64 devices, D_DP=8, D_PP=8, GPT-1.3B-shaped message
+sizes, 8 regions x 8 devices synthetic geo-distributed network, population 4096).
+
+A step is one pass of the whole hot path = one generation of the evolutionary search on the
+device: parent selection, crossover, mutation, `ls_moves` local-search rounds on every offspring
+(proposal, full cost evaluation of the proposed allocation, accept), evaluation, replacement and
+trace. `value` counts every candidate allocation whose cost (Eq. 1: DataP + bottleneck matchings +
+Held-Karp) was evaluated inside the timed region, per second. Inputs are resident in HBM before
+the timed region starts.
+
+Besides the contract line this prints, in the same JSON object:
+  roofline      the population-evaluation work (kernel(s) behind dtfm_eval_population), timed
+                with HIP events on the launch stream, against the chip's vector-ALU peak;
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+# ---- algorithmic operation count of one candidate evaluation (N, D_dp, D_pp) -------------------
+# DataP (Eq. 2): N (D_dp-1) fp64 adds and N + D_pp max.
+# Matching (Eq. 3), chosen algorithm = min-max subset DP over the columns of each D_dp x D_dp
+#   block: D_dp 2^(D_dp-1) transitions of one max and one min each, per stage pair, on 16-bit ranks
+#   (packed two per 32-bit lane-op). The part that any algorithm must do is reading/comparing the
+#   D_dp^2 entries of every block once (reported as `matching_compulsory_ops`).
+# Held-Karp (Eq. 4): D_pp (D_pp-1) 2^(D_pp-2) relaxations of one fp64 add and one fp64 min.
+# Peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.32 T lane-ops/s for 32/64-bit vector ops
+# (fp64 add/min/max issue at full rate), twice that for packed 16-bit ops.
+VALU_LANE_OPS_PER_S = 256 * 4 * 16 * 2.4e9
+
+
+def algorithmic_ops(N, D_dp, D_pp):
+    pairs = D_pp * (D_pp - 1) // 2
+    dp = N * (D_dp - 1) + N + D_pp
+    match16 = pairs * (D_dp * 2 ** (D_dp - 1) - D_dp) * 2
+    hk = D_pp * (D_pp - 1) * 2 ** (D_pp - 2) * 2 if D_pp >= 2 else 0
+    return {"datap_fp64": dp, "matching_u16": match16, "held_karp_fp64": hk,
+            "matching_compulsory_ops": pairs * D_dp * D_dp}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (candidates are independent; see DESIGN.md "
+              "for how the path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2206_01288_amd as dtfm
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dtfm.load_library()  # fails loudly when the HIP library is not built
+
+    w = workloads.config("C2")
+    P, N = w.P, w.N
+    ls_moves, nb = 8, dtfm.GAIN4
+    prob = dtfm.create_problem(w.latency, w.bandwidth, w.c_dp, w.c_pp, w.D_dp, w.D_pp)
+    pop0 = torch.from_numpy(workloads.random_population(P, N, seed=1)).cuda()
+
+    # ---- the timed steps: K generations of the evolutionary search ---------------------------
+    pop = pop0.clone()
+    if args.warmup > 0:
+        pop, _, _ = dtfm.evolve(prob, seed=1, generations=args.warmup, P=P, ls_moves=ls_moves,
+                                neighbourhood=nb, population=pop)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pop, cost, trace = dtfm.evolve(prob, seed=2, generations=args.steps, P=P, ls_moves=ls_moves,
+                                   neighbourhood=nb, population=pop)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    evals = P + args.steps * P * (1 + ls_moves)     # initial population + per offspring: LS rounds + 1
+    elapsed = t1 - t0
+    best = float(trace[-1].item()) if args.steps > 0 else float("nan")
+
+    # ---- roofline of the population-evaluation work, HIP events on the launch stream ---------
+    def time_eval(Pe, reps):
+        perms = torch.from_numpy(workloads.random_population(Pe, N, seed=3)).cuda()
+        out = torch.empty(Pe, dtype=torch.float64, device="cuda")
+        for _ in range(3):
+            dtfm.eval_population(prob, perms, out)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record()
+            dtfm.eval_population(prob, perms, out)
+            b.record()
+        torch.cuda.synchronize()
+        ms = np.array([a.elapsed_time(b) for a, b in ev])
+        return float(ms.mean()) * 1e-3
+
+    ops = algorithmic_ops(N, w.D_dp, w.D_pp)
+    t_small = time_eval(P, 50)
+    P_big = 1 << 20
+    t_big = time_eval(P_big, 10)
+    ops64 = ops["datap_fp64"] + ops["held_karp_fp64"]
+    ops16 = ops["matching_u16"]
+    total_ops = ops64 + ops16
+    # blended peak: the time the ALUs need at full issue rate for this op mix
+    t_min_per_cand = ops64 / VALU_LANE_OPS_PER_S + ops16 / (2 * VALU_LANE_OPS_PER_S)
+    peak = total_ops / t_min_per_cand / 1e12
+    achieved = total_ops * P_big / t_big / 1e12
+    roofline = {"bound": "alu", "achieved": achieved, "peak": peak, "unit": "Tops/s",
+                "frac": achieved / peak, "traffic": None,
+                "kernel": "dtfm_eval_population", "launch_candidates": P_big,
+                "launch_seconds": t_big, "ops_per_candidate": ops,
+                "eval_population_cands_per_s": {"P=4096": P / t_small, "P=1048576": P_big / t_big}}
+
+    # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        opr = oracle.Problem(w.latency, w.bandwidth, w.c_dp, w.c_pp, w.D_dp, w.D_pp)
+        threads = max(1, min(16, os.cpu_count() or 1))
+        sample = workloads.random_population(8 * P, N, seed=3)
+        chunks = np.array_split(sample, threads * 4)
+        c0 = time.perf_counter()
+        with ThreadPoolExecutor(threads) as ex:
+            res = list(ex.map(opr.eval_population, chunks))
+        c1 = time.perf_counter()
+        cpu = {"value": sample.shape[0] / (c1 - c0), "unit": "candidates/s", "cores": threads, "kind": "oracle",
+               "sample": "%d random C2 candidates, full cost evaluation each (oracle eval_population), "
+                         "%d threads over contiguous chunks" % (sample.shape[0], threads)}
+        # the GPU result on the same rows must agree with what was just timed
+        g = dtfm.eval_population(prob, torch.from_numpy(sample[:P]).cuda()).cpu().numpy()
+        assert np.array_equal(g, np.concatenate(res)[:P]), "GPU and oracle disagree"
+
+    line = {
+        "metric": "candidate allocations evaluated/sec (N=64, D_DP=8, D_PP=8)",
+        "value": evals / elapsed,
+        "unit": "candidates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / max(args.steps, 1) * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": "C2: N=64, D_DP=8, D_PP=8, GPT-1.3B-shaped sizes, 8x8-region synthetic network, "
+                               "population 4096; step = one GA generation (select, crossover, mutation, "
+                               "%d GAIN4 local-search rounds, evaluation, replacement)" % ls_moves,
+                   "population": P, "offspring_per_generation": P, "ls_moves": ls_moves,
+                   "evaluations_in_timed_region": evals},
+        "generations_per_s": args.steps / elapsed,
+        "best_cost_after_last_step_s": best,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
