@@ -126,6 +126,11 @@ extern "C" int dtfm_create_problem(const double *latency, const double *bandwidt
     CREATE_HIP(hipFree(bw_dev));
     bw_dev = nullptr;
 #undef CREATE_HIP
+    if (dtfm_fast64_applicable(pr)) {
+        rc = dtfm_fast64_prepare(pr);
+        if (rc != DTFM_OK) return fail(rc);
+        pr->fast64 = true;
+    }
     *out = pr;
     return DTFM_OK;
 }
@@ -138,6 +143,7 @@ extern "C" void dtfm_destroy_problem(dtfm_problem *pr)
     if (pr->W_pp) (void)hipFree(pr->W_pp);
     if (pr->hk_subsets) (void)hipFree(pr->hk_subsets);
     if (pr->scratch) (void)hipFree(pr->scratch);
+    dtfm_fast64_release(pr);
     delete pr;
 }
 

@@ -226,6 +226,9 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
                       size_t rows, double *cost, hipStream_t st)
 {
     if (rows == 0) return DTFM_OK;
+    if (pr->fast64)
+        return cost != nullptr ? dtfm_fast64_enqueue(pr, perm, rows, cost, nullptr, nullptr, st)
+                               : dtfm_fast64_enqueue(pr, perm, rows, nullptr, b.ghat, b.datap, st);
     const int N = pr->N, n = pr->D_pp;
     int threads = ((N + DTFM_WAVE - 1) / DTFM_WAVE) * DTFM_WAVE;
     if (threads > 1024) threads = 1024;

@@ -29,7 +29,12 @@ struct dtfm_problem {
     dtfm_layer_off hk_off;
     char *scratch;          // device arena, grown on demand
     size_t scratch_bytes;
-    bool fast64;            // shape handled by the fused small-shape kernels
+    // fused kernel for the 64-device shape (N = 64, D_dp = 8, D_pp = 8)
+    bool fast64;
+    uint16_t *f64_rank;     // device, N*N: rank of W_pp[d][d'] among all off-diagonal weights
+    double *f64_rank_val;   // device, N*N: rank -> weight
+    uint32_t *f64_steps;    // device: per-lane item tables of the layered programmes
+    int f64_grid;           // workgroups launched (one per CU)
 };
 
 // Bump allocator over the problem's scratch arena. With base == nullptr it only measures.
@@ -65,6 +70,14 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
                       size_t rows, double *cost, hipStream_t st);
 int dtfm_weights_enqueue(const double *lat_dev, const double *bw_dev, int N, double shard,
                          double c_pp, double *W_dp, double *W_pp, hipStream_t st);
+
+// ---- fused evaluation, 64-device shape (dtfm_fast64.hip) ---------------------------------------
+bool dtfm_fast64_applicable(const dtfm_problem *pr);
+int dtfm_fast64_prepare(dtfm_problem *pr);
+void dtfm_fast64_release(dtfm_problem *pr);
+// any of cost / ghat (rows*64) / datap (rows) may be null
+int dtfm_fast64_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows, double *cost, double *ghat,
+                        double *datap, hipStream_t st);
 
 // ---- search (dtfm_search.hip) -----------------------------------------------------------------
 struct dtfm_ls_bufs {
