@@ -38,6 +38,7 @@ def _newest_dep():
 def build(force: bool = False, verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    extra = os.environ.get("DTFM_EXTRA_HIPCC_FLAGS", "").split()
     dep_time = _newest_dep()
     jobs = []
     objs = []
@@ -45,7 +46,7 @@ def build(force: bool = False, verbose: bool = True) -> str:
         obj = os.path.join(OBJ, src[:-4] + ".o")
         objs.append(obj)
         if force or not os.path.exists(obj) or os.path.getmtime(obj) < dep_time:
-            jobs.append([hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj])
+            jobs.append([hipcc] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj])
 
     def run(cmd):
         if verbose:

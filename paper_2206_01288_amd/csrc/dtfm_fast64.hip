@@ -18,6 +18,7 @@
 
 #include <math.h>
 
+#include <mutex>
 #include <utility>
 #include <vector>
 
@@ -26,7 +27,8 @@ namespace {
 constexpr int NDEV = 64, NPAIR = 28, NGROUP = 4, PAIRS_PER_GROUP = 7;
 constexpr int BINOM8[9] = {1, 8, 28, 56, 70, 56, 28, 8, 1};
 
-constexpr int match_steps(int k) { return (NGROUP * BINOM8[k] + 63) / 64; }   // k = 2..8
+// matching steps of layer k: each group's C(8,k) subsets padded to whole 16-lane passes
+constexpr int match_steps(int k) { return (NGROUP * ((BINOM8[k] + 15) / 16) * 16 + 63) / 64; }   // k = 2..8
 constexpr int hk_steps(int k) { return (BINOM8[k] * k + 63) / 64; }
 constexpr int match_first(int k)
 {
@@ -46,7 +48,7 @@ constexpr int N_HSTEP = hk_first(9);      // 19
 // LDS: shared rank table, then one slice per wavefront
 constexpr int LDS_RANK_BYTES = NDEV * NDEV * 2;        // 8 KiB
 constexpr int OFF_GT = 0;                              // u16 [4 groups][256 subsets][8]  16 KiB
-constexpr int OFF_HK = 0;                              // fp64 [256 subsets][8] (after matching)
+constexpr int OFF_HK = 0;                              // fp64 [8 end nodes][256 subsets] (after matching)
 constexpr int OFF_WST = 16384;                         // u16 [4 groups][64 entries][8]    4 KiB
 constexpr int OFF_GHAT = OFF_WST + 4096;               // fp64 [8][8]
 constexpr int OFF_PB = OFF_GHAT + 512;                 // u8 [64] perm, stage-major
@@ -104,6 +106,7 @@ __device__ __forceinline__ void match_layer(unsigned char *wl, const step_consts
             acc.w = pk_min(acc.w, pk_max(g.w, w.w));
         }
         if (meta >> 31) *reinterpret_cast<uint4 *>(wl + OFF_GT + self) = acc;
+        __builtin_amdgcn_sched_barrier(0);   // keep one step's loads in flight, not the whole layer's
     }
     WAVE_LDS_SYNC();
 }
@@ -115,17 +118,18 @@ __device__ __forceinline__ void hk_layer(unsigned char *wl, const step_consts &s
 #pragma unroll
     for (int s = 0; s < hk_steps(K); s++) {
         const uint32_t nib = sc.h_nib[hk_first(K) + s], a = sc.h_a[hk_first(K) + s], b = sc.h_b[hk_first(K) + s];
-        const uint32_t rest_base = a & 0xFFFFu;   // byte offset of tab[S \ v][0]
+        const uint32_t rest8 = a & 0xFFFFu;       // byte offset of tab[0][S \ v]
         const uint32_t v8 = a >> 16;              // v * 8
         double best = INFINITY;
 #pragma unroll
         for (int t = 0; t < K - 1; t++) {
             const uint32_t u = (nib >> (4 * t)) & 15u;
-            const double x = *reinterpret_cast<const double *>(wl + OFF_HK + rest_base + u * 8u);
+            const double x = *reinterpret_cast<const double *>(wl + OFF_HK + rest8 + u * 2048u);
             const double e = *reinterpret_cast<const double *>(wl + OFF_GHAT + u * 64u + v8);
             best = fmin(best, __dadd_rn(x, e));
         }
         if (b >> 31) *reinterpret_cast<double *>(wl + OFF_HK + (b & 0xFFFFu)) = best;
+        __builtin_amdgcn_sched_barrier(0);
     }
     WAVE_LDS_SYNC();
 }
@@ -161,6 +165,19 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
 
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
     for (size_t cand = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; cand < P; cand += nwaves) {
+        // The step constants are loop invariant; hide that from the optimiser, which would otherwise
+        // hoist every address derived from them out of the loop and spill hundreds of registers.
+#pragma unroll
+        for (int i = 0; i < N_MSTEP; i++) {
+            asm volatile("" : "+v"(sc.m_nib[i]));
+            asm volatile("" : "+v"(sc.m_meta[i]));
+        }
+#pragma unroll
+        for (int i = 0; i < N_HSTEP; i++) {
+            asm volatile("" : "+v"(sc.h_nib[i]));
+            asm volatile("" : "+v"(sc.h_a[i]));
+            asm volatile("" : "+v"(sc.h_b[i]));
+        }
         // ---- a1: candidate row, position = lane: stage = lane / 8, slot = lane % 8 ----
         const int d = perm[cand * NDEV + lane];
         wl[OFF_PB + lane] = (unsigned char)d;
@@ -216,6 +233,7 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
                 *reinterpret_cast<const uint4 *>(wl + OFF_WST + (g * 64 + c) * 16);
         }
         WAVE_LDS_SYNC();
+#ifndef EXP_SKIP_MATCH
         match_layer<2>(wl, sc);
         match_layer<3>(wl, sc);
         match_layer<4>(wl, sc);
@@ -223,6 +241,7 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
         match_layer<6>(wl, sc);
         match_layer<7>(wl, sc);
         match_layer<8>(wl, sc);
+#endif
 
         // ---- a4 (3): winning rank -> fp64 weight; lane = (u, v) entry of the coarsened graph ----
         double e = 0.0;
@@ -241,8 +260,9 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
         if (ghat_out != nullptr) ghat_out[cand * 64 + lane] = e;
 
         // ---- a5: Held-Karp over the 8 stage nodes ----
-        if (lane < 8) *reinterpret_cast<double *>(wl + OFF_HK + ((1 << lane) * 8 + lane) * 8) = 0.0;
+        if (lane < 8) *reinterpret_cast<double *>(wl + OFF_HK + (lane * 256 + (1 << lane)) * 8) = 0.0;
         WAVE_LDS_SYNC();
+#ifndef EXP_SKIP_HK
         hk_layer<2>(wl, sc);
         hk_layer<3>(wl, sc);
         hk_layer<4>(wl, sc);
@@ -250,7 +270,8 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
         hk_layer<6>(wl, sc);
         hk_layer<7>(wl, sc);
         hk_layer<8>(wl, sc);
-        double pp = *reinterpret_cast<const double *>(wl + OFF_HK + (255 * 8 + (lane & 7)) * 8);
+#endif
+        double pp = *reinterpret_cast<const double *>(wl + OFF_HK + ((lane & 7) * 256 + 255) * 8);
         pp = fmin(pp, __shfl_xor(pp, 1));
         pp = fmin(pp, __shfl_xor(pp, 2));
         pp = fmin(pp, __shfl_xor(pp, 4));
@@ -292,6 +313,87 @@ __global__ void k_rank_weights(const double *__restrict__ W_pp, int N, uint16_t 
     rank_val[r] = w;   // equal weights write equal bits
 }
 
+// ---- which subset each lane handles, and in which order it visits the subset's columns ----------
+// A 128-bit LDS read is served 16 lanes at a time; within such a pass two lanes that read different
+// addresses with equal (address / 16) % 16 take an extra cycle each. Which subset S a lane owns and
+// the order in which it removes S's columns are free, so they are chosen once (deterministic local
+// search) to keep the predecessor reads gt[S \ c] of the 16 lanes of a pass on distinct slots.
+struct match_item {
+    uint8_t S, ord[8];
+    bool valid;
+};
+
+int pass_cost(const match_item *it, int k)
+{
+    int total = 0;
+    for (int t = 0; t <= k; t++) {   // t == k: the write of gt[S]
+        int cnt[16] = {0};
+        bool seen[256] = {false};
+        int worst = 0;
+        for (int i = 0; i < 16; i++) {
+            if (!it[i].valid) continue;
+            int a = t < k ? (it[i].S ^ (1 << it[i].ord[t])) : it[i].S;
+            if (seen[a]) continue;   // same address: broadcast
+            seen[a] = true;
+            if (++cnt[a & 15] > worst) worst = cnt[a & 15];
+        }
+        total += worst;
+    }
+    return total;
+}
+
+std::vector<match_item> arrange_layer(int k)
+{
+    std::vector<match_item> arr;
+    for (uint32_t S = 1; S < 256; S++)
+        if (__builtin_popcount(S) == k) {
+            match_item m = {};
+            m.S = (uint8_t)S;
+            m.valid = true;
+            int t = 0;
+            for (int c = 0; c < 8; c++)
+                if (S & (1u << c)) m.ord[t++] = (uint8_t)c;
+            arr.push_back(m);
+        }
+    while (arr.size() % 16) arr.push_back(match_item{});
+    const int np = (int)arr.size() / 16;
+    std::vector<int> cost(np);
+    for (int p = 0; p < np; p++) cost[p] = pass_cost(&arr[p * 16], k);
+    uint64_t rng = 0x9E3779B97F4A7C15ull + (uint64_t)k;
+    auto next = [&rng](uint32_t n) {
+        rng = rng * 6364136223846793005ull + 1442695040888963407ull;
+        return (uint32_t)((rng >> 33) % n);
+    };
+    const int iters = 30000;
+    for (int it = 0; it < iters; it++) {
+        // accept equal-cost moves always, worse moves (by 1) early on with small probability
+        const bool allow_worse = it < iters / 2 && next(16) == 0;
+        int p = (int)next(np), i = (int)next(16);
+        if (next(2) == 0 || np == 1) {
+            match_item &m = arr[p * 16 + i];
+            if (!m.valid || k < 2) continue;
+            int a = (int)next(k), b = (int)next(k);
+            if (a == b) continue;
+            std::swap(m.ord[a], m.ord[b]);
+            int c = pass_cost(&arr[p * 16], k);
+            if (c <= cost[p] || (allow_worse && c == cost[p] + 1)) cost[p] = c;
+            else std::swap(m.ord[a], m.ord[b]);
+        } else {
+            int q = (int)next(np), j = (int)next(16);
+            if (q == p) continue;
+            std::swap(arr[p * 16 + i], arr[q * 16 + j]);
+            int cp = pass_cost(&arr[p * 16], k), cq = pass_cost(&arr[q * 16], k);
+            int d = cp + cq - cost[p] - cost[q];
+            if (d <= 0 || (allow_worse && d == 1)) {
+                cost[p] = cp;
+                cost[q] = cq;
+            } else
+                std::swap(arr[p * 16 + i], arr[q * 16 + j]);
+        }
+    }
+    return arr;
+}
+
 }  // namespace
 
 bool dtfm_fast64_applicable(const dtfm_problem *pr) { return pr->N == 64 && pr->D_dp == 8 && pr->D_pp == 8; }
@@ -311,22 +413,29 @@ int dtfm_fast64_prepare(dtfm_problem *pr)
     uint32_t *m_nib = tab.data(), *m_meta = m_nib + N_MSTEP * 64;
     uint32_t *h_nib = m_meta + N_MSTEP * 64, *h_a = h_nib + N_HSTEP * 64, *h_b = h_a + N_HSTEP * 64;
     int ms = 0, hs = 0;
+    static std::vector<match_item> arrangement[9];   // problem independent: built once per process
+    static std::once_flag arranged;
+    std::call_once(arranged, [] {
+        for (int k = 2; k <= 8; k++) arrangement[k] = arrange_layer(k);
+    });
     for (int k = 2; k <= 8; k++) {
         std::vector<uint32_t> layer;
         for (uint32_t S = 1; S < 256; S++)
             if (__builtin_popcount(S) == k) layer.push_back(S);
-        const int C = (int)layer.size();
-        // matching: item i = (group i / C, subset layer[i % C])
+        // matching: passes of 16 lanes, each within one group; the same arrangement for every group
+        const std::vector<match_item> &arr = arrangement[k];
+        const int ppg = (int)arr.size() / 16;   // passes per group
         for (int s = 0; s < match_steps(k); s++, ms++)
             for (int lane = 0; lane < 64; lane++) {
-                int i = s * 64 + lane;
-                if (i >= NGROUP * C) continue;
-                uint32_t g = i / C, S = layer[i % C], nib = 0;
-                int t = 0;
-                for (int c = 0; c < 8; c++)
-                    if (S & (1u << c)) nib |= (uint32_t)c << (4 * t++);
+                int pass = s * 4 + lane / 16;
+                if (pass >= NGROUP * ppg) continue;
+                uint32_t g = pass / ppg;
+                const match_item &it = arr[(pass % ppg) * 16 + lane % 16];
+                if (!it.valid) continue;
+                uint32_t nib = 0;
+                for (int t = 0; t < k; t++) nib |= (uint32_t)it.ord[t] << (4 * t);
                 m_nib[ms * 64 + lane] = nib;
-                m_meta[ms * 64 + lane] = ((g * 256 + S) * 16) | (g << 16) | 0x80000000u;
+                m_meta[ms * 64 + lane] = ((g * 256 + it.S) * 16) | (g << 16) | 0x80000000u;
             }
         // Held-Karp: item i = (subset, end node v in it), subsets ascending, v ascending
         std::vector<std::pair<uint32_t, int>> items;
@@ -342,8 +451,8 @@ int dtfm_fast64_prepare(dtfm_problem *pr)
                 for (int u = 0; u < 8; u++)
                     if (rest & (1u << u)) nib |= (uint32_t)u << (4 * t++);
                 h_nib[hs * 64 + lane] = nib;
-                h_a[hs * 64 + lane] = (rest * 64) | ((v * 8) << 16);
-                h_b[hs * 64 + lane] = ((S * 8 + v) * 8) | 0x80000000u;
+                h_a[hs * 64 + lane] = (rest * 8) | ((v * 8) << 16);
+                h_b[hs * 64 + lane] = ((v * 256 + S) * 8) | 0x80000000u;
             }
     }
     DTFM_HIP(hipMalloc((void **)&pr->f64_steps, tab.size() * sizeof(uint32_t)));
