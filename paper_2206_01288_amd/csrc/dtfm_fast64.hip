@@ -11,21 +11,27 @@
 //                      one 32-bit register, 16-bit packed max/min. Every lane walks the subsets in
 //                      the same order, so the whole table lives in registers with compile-time
 //                      indices: no table traffic, no index arithmetic, 2 ALU ops per transition.
-//   Held-Karp (Eq. 4)  per candidate, fp64 table [v][S] in LDS, one lane per (S, v) item, layers
-//                      of equal |S|; which item a lane owns in each step is fixed and comes from a
-//                      small table built with the problem (held in registers).
+//   Held-Karp (Eq. 4)  two candidates at a time, their fp64 values side by side in 128-bit LDS
+//                      entries; one lane per (S, v) item, layers of equal |S| kept in two
+//                      alternating compact buffers. Which item a lane owns in each step, and the
+//                      byte offsets of the entries it reads, are fixed: they come from a table built
+//                      once (LDS-resident) whose slot assignment avoids LDS bank conflicts.
 //   DataP (Eq. 2)      lane = position; 8 gathers of W_dp (L2-resident 32 KiB table) summed in
 //                      slot order (the device's own slot adds the zero diagonal), wave max.
 #include "dtfm_internal.h"
 
 #include <math.h>
 
+#include <mutex>
 #include <utility>
 #include <vector>
 
 namespace {
 
 constexpr int NDEV = 64, CANDS = 4;   // candidates per wavefront pass
+// Row stride of the rank table in LDS, in 16-bit entries. 66 instead of 64 skews consecutive rows by
+// one 4-byte bank, so that lanes reading the same column of different rows hit different banks.
+constexpr int RSTRIDE = 66;
 constexpr int BINOM8[9] = {1, 8, 28, 56, 70, 56, 28, 8, 1};
 
 // the subsets of {0..7} grouped by size: LAYER.s[k][i] = i-th subset with k elements, ascending
@@ -47,25 +53,31 @@ constexpr layer_table make_layers()
 }
 constexpr layer_table LAYER = make_layers();
 
-constexpr int hk_steps(int k) { return (BINOM8[k] * k + 63) / 64; }
-constexpr int hk_first(int k)
+constexpr int hk_steps(int k) { return (BINOM8[k] * k + 63) / 64; }    // 64-lane steps of layer k
+constexpr int hk_words4(int k) { return (k + 3) / 4; }                 // 128-bit table words per item
+constexpr int hk_tab_first(int k)                                       // first table word of layer k
 {
     int o = 0;
-    for (int i = 2; i < k; i++) o += hk_steps(i);
+    for (int i = 2; i < k; i++) o += hk_steps(i) * hk_words4(i);
     return o;
 }
-constexpr int N_HSTEP = hk_first(9);   // 19
+constexpr int HK_TAB_WORDS4 = hk_tab_first(9);          // 29 (x 64 lanes x 16 B = 29696 B)
+constexpr int HK_BUF_ENTRIES = 5 * 64;                  // largest layer: 5 steps of 64 lanes
 
-// LDS: shared rank table, then one slice per wavefront
-constexpr int LDS_RANK_BYTES = NDEV * NDEV * 2;        // 8 KiB
-constexpr int OFF_HK = 0;                              // fp64 [8 end nodes][256 subsets]   16 KiB
-constexpr int OFF_GHAT = 16384;                        // fp64 [4 candidates][8][8]          2 KiB
-constexpr int OFF_PB = OFF_GHAT + CANDS * 512;         // u8 [4 candidates][64] perm, stage-major
-constexpr int WAVE_LDS_BYTES = OFF_PB + CANDS * 64;    // 18688
+// LDS: rank table and Held-Karp item table shared by the workgroup, then one slice per wavefront
+constexpr int LDS_RANK_BYTES = ((NDEV * RSTRIDE * 2 + 15) / 16) * 16;   // 8.25 KiB
+constexpr int LDS_HKTAB_BYTES = HK_TAB_WORDS4 * 64 * 16;           // 29 KiB
+constexpr int OFF_BUF0 = 0;                                        // double2 [320]: even layers
+constexpr int OFF_BUF1 = OFF_BUF0 + HK_BUF_ENTRIES * 16;           // double2 [320]: odd layers
+constexpr int OFF_GHAT = OFF_BUF1 + HK_BUF_ENTRIES * 16;           // double2 [2 candidate pairs][8][8]
+constexpr int OFF_PB = OFF_GHAT + 2 * 1024;                        // u8 [4 candidates][64] perm, stage-major
+constexpr int WAVE_LDS_BYTES = OFF_PB + CANDS * 64;                // 12544
 constexpr int WAVES_PER_BLOCK = 8;
-constexpr int LDS_TOTAL = LDS_RANK_BYTES + WAVES_PER_BLOCK * WAVE_LDS_BYTES;   // 157696 <= 160 KiB
+constexpr int LDS_TOTAL = LDS_RANK_BYTES + LDS_HKTAB_BYTES + WAVES_PER_BLOCK * WAVE_LDS_BYTES;
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;   // explicitly LDS-qualified
 
 __device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b)
 {
@@ -88,32 +100,44 @@ __device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b)
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");  \
     } while (0)
 
-struct hk_consts {
-    uint32_t nib[N_HSTEP], a[N_HSTEP], b[N_HSTEP];
-};
-
-// One layer of Held-Karp: every lane owns (S, v) items with |S| = K. ghat_off: byte offset of this
-// candidate's coarsened graph inside the wavefront's LDS slice.
+// One layer of Held-Karp for a pair of candidates: every lane owns (S, v) items with |S| = K.
+// Item table (128-bit words, lane-major): word 0 = byte offset of the item's own entry in this
+// layer's buffer | valid << 31; words 1..K-1 = one per predecessor u in S \ v:
+// (byte offset of tab[S \ v][u] in the previous layer's buffer) | (byte offset of ghat[u][v]) << 16.
 template <int K>
-__device__ __forceinline__ void hk_layer(unsigned char *wl, const hk_consts &hc, uint32_t ghat_off)
+__device__ __forceinline__ double2 hk_layer(unsigned char *wl, const unsigned char *hktab, uint32_t ghat_off,
+                                            int lane)
 {
+    constexpr int PREV = (K & 1) ? OFF_BUF0 : OFF_BUF1, CUR = (K & 1) ? OFF_BUF1 : OFF_BUF0;
+    double2 best = make_double2(INFINITY, INFINITY);
 #pragma unroll
     for (int s = 0; s < hk_steps(K); s++) {
-        const uint32_t nib = hc.nib[hk_first(K) + s], a = hc.a[hk_first(K) + s], b = hc.b[hk_first(K) + s];
-        const uint32_t rest8 = a & 0xFFFFu;            // byte offset of tab[0][S \ v]
-        const uint32_t gcol = (a >> 16) + ghat_off;    // byte offset of ghat[0][v]
-        double best = INFINITY;
+        uint32_t word[8];
 #pragma unroll
-        for (int t = 0; t < K - 1; t++) {
-            const uint32_t u = (nib >> (4 * t)) & 15u;
-            const double x = *reinterpret_cast<const double *>(wl + OFF_HK + rest8 + u * 2048u);
-            const double e = *reinterpret_cast<const double *>(wl + gcol + u * 64u);
-            best = fmin(best, __dadd_rn(x, e));
+        for (int i = 0; i < hk_words4(K); i++) {
+            // volatile: keep this one dense 128-bit read per lane (the compiler would otherwise narrow
+            // it to the words actually used, which at a 16-byte lane stride conflicts heavily)
+            const u32x4 t = *(const volatile lds_u32x4 *)(
+                hktab + ((hk_tab_first(K) + s * hk_words4(K) + i) * 64 + lane) * 16);
+            word[4 * i + 0] = t.x;
+            word[4 * i + 1] = t.y;
+            word[4 * i + 2] = t.z;
+            word[4 * i + 3] = t.w;
         }
-        if (b >> 31) *reinterpret_cast<double *>(wl + OFF_HK + (b & 0xFFFFu)) = best;
+        best = make_double2(INFINITY, INFINITY);
+#pragma unroll
+        for (int t = 1; t < K; t++) {
+            const double2 x = *reinterpret_cast<const double2 *>(wl + PREV + (word[t] & 0xFFFFu));
+            const double2 e = *reinterpret_cast<const double2 *>(wl + ghat_off + (word[t] >> 16));
+            best.x = fmin(best.x, __dadd_rn(x.x, e.x));
+            best.y = fmin(best.y, __dadd_rn(x.y, e.y));
+        }
+        if (word[0] >> 31) *reinterpret_cast<double2 *>(wl + CUR + (word[0] & 0xFFFFu)) = best;
+        else best = make_double2(INFINITY, INFINITY);
         __builtin_amdgcn_sched_barrier(0);   // keep one step's loads in flight, not the whole layer's
     }
     WAVE_LDS_SYNC();
+    return best;
 }
 
 // byte k (0..7) of a 64-bit value held as two dwords
@@ -128,13 +152,20 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint16_t *R = reinterpret_cast<const uint16_t *>(smem);
-    unsigned char *wl = smem + LDS_RANK_BYTES + wave * WAVE_LDS_BYTES;
+    const unsigned char *hktab = smem + LDS_RANK_BYTES;
+    unsigned char *wl = smem + LDS_RANK_BYTES + LDS_HKTAB_BYTES + wave * WAVE_LDS_BYTES;
 
-    // rank table -> LDS (8 KiB, 16 bytes per thread per pass)
-    for (int i = threadIdx.x; i < LDS_RANK_BYTES / 16; i += blockDim.x)
-        reinterpret_cast<uint4 *>(smem)[i] = reinterpret_cast<const uint4 *>(rank_tab)[i];
-    // zero diagonals of the four coarsened graphs (never overwritten)
-    if (lane < CANDS * 8) *reinterpret_cast<double *>(wl + OFF_GHAT + (lane >> 3) * 512 + (lane & 7) * 72) = 0.0;
+    // rank table -> LDS, rows re-strided (two entries per thread per pass)
+    for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
+        const int row = i / (NDEV / 2), col2 = i - row * (NDEV / 2);
+        reinterpret_cast<uint32_t *>(smem)[row * (RSTRIDE / 2) + col2] = reinterpret_cast<const uint32_t *>(rank_tab)[i];
+    }
+    // Held-Karp item table -> LDS
+    for (int i = threadIdx.x; i < LDS_HKTAB_BYTES / 16; i += blockDim.x)
+        reinterpret_cast<uint4 *>(smem + LDS_RANK_BYTES)[i] = reinterpret_cast<const uint4 *>(step_tab)[i];
+    // zero diagonals of the four coarsened graphs (never overwritten): entry [pair][j][j][cand & 1]
+    if (lane < CANDS * 8)
+        *reinterpret_cast<double *>(wl + OFF_GHAT + (lane >> 4) * 1024 + (lane & 7) * 9 * 16 + ((lane >> 3) & 1) * 8) = 0.0;
     // matching role of this lane: candidate slot and the couple of stage pairs (2q, 2q+1) in
     // lexicographic pair order; lanes with q = 14, 15 repeat couple 13 and write nothing
     const int mc = lane >> 4, q = (lane & 15) < 14 ? (lane & 15) : 13;
@@ -184,10 +215,14 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
             // register footprint to two rows plus two layers of the table
             uint32_t wnext[8];
             {
-                const uint32_t rb0 = byte_of(rowdev[0], 0) * NDEV, rb1 = byte_of(rowdev[1], 0) * NDEV;
+                const uint32_t rb0 = byte_of(rowdev[0], 0) * RSTRIDE, rb1 = byte_of(rowdev[1], 0) * RSTRIDE;
 #pragma unroll
                 for (int c = 0; c < 8; c++)
+#ifdef EXP_SKIP_GATHER
+                    wnext[c] = rb0 + coloff[0][c] + ((rb1 + coloff[1][c]) << 16);
+#else
                     wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
+#endif
             }
 #pragma unroll
             for (int r = 0; r < 8; r++) {
@@ -196,10 +231,14 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
 #pragma unroll
                 for (int c = 0; c < 8; c++) w[c] = wnext[c];
                 if (r < 7) {
-                    const uint32_t rb0 = byte_of(rowdev[0], r + 1) * NDEV, rb1 = byte_of(rowdev[1], r + 1) * NDEV;
+                    const uint32_t rb0 = byte_of(rowdev[0], r + 1) * RSTRIDE, rb1 = byte_of(rowdev[1], r + 1) * RSTRIDE;
 #pragma unroll
                     for (int c = 0; c < 8; c++)
+#ifdef EXP_SKIP_GATHER
+                        wnext[c] = rb0 + coloff[0][c] + ((rb1 + coloff[1][c]) << 16);
+#else
                         wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
+#endif
                 }
 #pragma unroll
                 for (int i = 0; i < BINOM8[r + 1]; i++) {
@@ -222,76 +261,70 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
         // ---- winning ranks -> fp64 weights -> coarsened graphs in LDS ----
         {
             const double e0 = rank_val[gfull & 0xFFFFu], e1 = rank_val[gfull >> 16];
-            if (couple_valid) {
-                double *gh = reinterpret_cast<double *>(wl + OFF_GHAT + mc * 512);
-                gh[j1[0] * 8 + j2[0]] = e0;
-                gh[j2[0] * 8 + j1[0]] = e0;
-                gh[j1[1] * 8 + j2[1]] = e1;
-                gh[j2[1] * 8 + j1[1]] = e1;
+            if (couple_valid) {   // entry [candidate pair][u][v][candidate & 1]
+                double *gh = reinterpret_cast<double *>(wl + OFF_GHAT + (mc >> 1) * 1024) + (mc & 1);
+                gh[(j1[0] * 8 + j2[0]) * 2] = e0;
+                gh[(j2[0] * 8 + j1[0]) * 2] = e0;
+                gh[(j1[1] * 8 + j2[1]) * 2] = e1;
+                gh[(j2[1] * 8 + j1[1]) * 2] = e1;
             }
         }
         WAVE_LDS_SYNC();
 
-        // per-lane Held-Karp item tables (L2-resident, reloaded per pass so that they do not occupy
-        // registers during the matching programme; the asm keeps the loads from being hoisted)
-        hk_consts hc;
-        {
-            const uint32_t *st = step_tab;
-            asm volatile("" : "+s"(st));
-#pragma unroll
-            for (int i = 0; i < N_HSTEP; i++) {
-                hc.nib[i] = st[(0 * N_HSTEP + i) * 64 + lane];
-                hc.a[i] = st[(1 * N_HSTEP + i) * 64 + lane];
-                hc.b[i] = st[(2 * N_HSTEP + i) * 64 + lane];
-            }
-        }
-        // ---- per candidate: a5 Held-Karp, a2/a3 DataP, a6 total ----
+        // ---- per candidate pair: a5 Held-Karp, a2/a3 DataP, a6 total ----
 #pragma nounroll
-        for (int c = 0; c < CANDS; c++) {
-            // hide the tables' loop invariance: addresses derived from them must not be hoisted
-#pragma unroll
-            for (int i = 0; i < N_HSTEP; i++) {
-                asm volatile("" : "+v"(hc.nib[i]));
-                asm volatile("" : "+v"(hc.a[i]));
-                asm volatile("" : "+v"(hc.b[i]));
-            }
-            const size_t cand = quad * CANDS + c;
-            const bool live = cand < P;   // wave-uniform
-            const int d = c == 0 ? dev[0] : c == 1 ? dev[1] : c == 2 ? dev[2] : dev[3];
+        for (int pr = 0; pr < CANDS / 2; pr++) {
+            const size_t cand0 = quad * CANDS + 2 * pr;
             // DataP gathers first: their latency hides behind Held-Karp
-            const uint2 mates = *reinterpret_cast<const uint2 *>(wl + OFF_PB + c * 64 + (lane & ~7));
-            const double *wrow = W_dp + d * NDEV;
-            double wv[8];
+            double wv[2][8];
 #pragma unroll
-            for (int k = 0; k < 8; k++) wv[k] = wrow[byte_of(mates, k)];   // own slot: the zero diagonal
-            const uint32_t ghat_off = OFF_GHAT + c * 512;
-            if (ghat_out != nullptr && live)
-                ghat_out[cand * 64 + lane] = *reinterpret_cast<const double *>(wl + ghat_off + lane * 8);
-
-            if (lane < 8) *reinterpret_cast<double *>(wl + OFF_HK + (lane * 256 + (1 << lane)) * 8) = 0.0;
-            WAVE_LDS_SYNC();
-            hk_layer<2>(wl, hc, ghat_off);
-            hk_layer<3>(wl, hc, ghat_off);
-            hk_layer<4>(wl, hc, ghat_off);
-            hk_layer<5>(wl, hc, ghat_off);
-            hk_layer<6>(wl, hc, ghat_off);
-            hk_layer<7>(wl, hc, ghat_off);
-            hk_layer<8>(wl, hc, ghat_off);
-            double pp = *reinterpret_cast<const double *>(wl + OFF_HK + ((lane & 7) * 256 + 255) * 8);
-            pp = fmin(pp, __shfl_xor(pp, 1));
-            pp = fmin(pp, __shfl_xor(pp, 2));
-            pp = fmin(pp, __shfl_xor(pp, 4));
-
-            double sum = 0.0;
+            for (int h = 0; h < 2; h++) {
+                const int d = pr == 0 ? dev[h] : dev[2 + h];
+                const uint2 mates = *reinterpret_cast<const uint2 *>(wl + OFF_PB + (2 * pr + h) * 64 + (lane & ~7));
+                const double *wrow = W_dp + d * NDEV;
 #pragma unroll
-            for (int k = 0; k < 8; k++) sum = __dadd_rn(sum, wv[k]);
-#pragma unroll
-            for (int o = 32; o >= 1; o >>= 1) sum = fmax(sum, __shfl_xor(sum, o));
-            if (lane == 0 && live) {
-                if (cost != nullptr) cost[cand] = __dadd_rn(sum, pp);
-                if (datap_out != nullptr) datap_out[cand] = sum;
+                for (int k = 0; k < 8; k++) wv[h][k] = wrow[byte_of(mates, k)];   // own slot: the zero diagonal
             }
-            WAVE_LDS_SYNC();   // the next candidate reuses the table
+            const uint32_t ghat_off = OFF_GHAT + pr * 1024;
+            if (ghat_out != nullptr) {
+                const double2 g2 = *reinterpret_cast<const double2 *>(wl + ghat_off + lane * 16);
+                if (cand0 < P) ghat_out[cand0 * 64 + lane] = g2.x;
+                if (cand0 + 1 < P) ghat_out[(cand0 + 1) * 64 + lane] = g2.y;
+            }
+            // layer 1: tab[{v}][v] = 0 at entry v of the odd buffer
+            if (lane < 8) *reinterpret_cast<double2 *>(wl + OFF_BUF1 + lane * 16) = make_double2(0.0, 0.0);
+            WAVE_LDS_SYNC();
+#ifndef EXP_SKIP_HK
+            hk_layer<2>(wl, hktab, ghat_off, lane);
+            hk_layer<3>(wl, hktab, ghat_off, lane);
+            hk_layer<4>(wl, hktab, ghat_off, lane);
+            hk_layer<5>(wl, hktab, ghat_off, lane);
+            hk_layer<6>(wl, hktab, ghat_off, lane);
+            hk_layer<7>(wl, hktab, ghat_off, lane);
+#endif
+            // the 8 items of the last layer sit in lanes 0..7 (others hold +inf): PP = min over them
+            double2 pp = hk_layer<8>(wl, hktab, ghat_off, lane);
+#pragma unroll
+            for (int o = 1; o <= 4; o <<= 1) {
+                pp.x = fmin(pp.x, __shfl_xor(pp.x, o));
+                pp.y = fmin(pp.y, __shfl_xor(pp.y, o));
+            }
+            pp.x = __shfl(pp.x, 0);
+            pp.y = __shfl(pp.y, 0);
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                double sum = 0.0;
+#pragma unroll
+                for (int k = 0; k < 8; k++) sum = __dadd_rn(sum, wv[h][k]);
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) sum = fmax(sum, __shfl_xor(sum, o));
+                const size_t cand = cand0 + h;
+                if (lane == 0 && cand < P) {
+                    if (cost != nullptr) cost[cand] = __dadd_rn(sum, h == 0 ? pp.x : pp.y);
+                    if (datap_out != nullptr) datap_out[cand] = sum;
+                }
+            }
+            WAVE_LDS_SYNC();   // the next pair reuses the buffers
         }
     }
 }
@@ -319,11 +352,134 @@ __global__ void k_rank_weights(const double *__restrict__ W_pp, int N, uint16_t 
     rank_val[r] = w;   // equal weights write equal bits
 }
 
+// ---- Held-Karp item table (problem independent, built once per process) ------------------------
+// Layer k has C(8,k) k items (S, v). Each is given a (step, lane) position; its entry lives at
+// index step*64 + lane of the layer's buffer, so writes are dense. The free choices - which item
+// sits at which position and in which order it visits its predecessors - are settled by a
+// deterministic local search that minimises LDS bank conflicts of the two 128-bit reads per
+// transition: a 128-bit read is served 16 lanes at a time, and within such a group two lanes that
+// read different entries with equal (index % 16) cost an extra cycle.
+struct hk_item {
+    uint8_t S, v, ord[7];
+    bool valid;
+};
+
+int hk_group_cost(const hk_item *it, int k, const int (*prev_idx)[8])
+{
+    int total = 0;
+    for (int t = 0; t < k - 1; t++) {
+        int cnt_a[16] = {0}, cnt_g[16] = {0}, worst_a = 0, worst_g = 0;
+        bool seen_a[HK_BUF_ENTRIES] = {false}, seen_g[64] = {false};
+        for (int i = 0; i < 16; i++) {
+            if (!it[i].valid) continue;
+            int u = it[i].ord[t], a = prev_idx[it[i].S ^ (1 << it[i].v)][u], g = u * 8 + it[i].v;
+            if (!seen_a[a]) {
+                seen_a[a] = true;
+                if (++cnt_a[a & 15] > worst_a) worst_a = cnt_a[a & 15];
+            }
+            if (!seen_g[g]) {
+                seen_g[g] = true;
+                if (++cnt_g[g & 15] > worst_g) worst_g = cnt_g[g & 15];
+            }
+        }
+        total += worst_a + worst_g;
+    }
+    return total;
+}
+
+const std::vector<uint32_t> &hk_item_table()
+{
+    static std::vector<uint32_t> tab;
+    static std::once_flag once;
+    std::call_once(once, [] {
+        tab.assign((size_t)HK_TAB_WORDS4 * 64 * 4, 0u);
+        static int idx[2][256][8];   // entry index of (S, v) in its layer's buffer, by layer parity
+        for (int v = 0; v < 8; v++) idx[1][1 << v][v] = v;   // layer 1
+        uint64_t rng = 0x2545F4914F6CDD1Dull;
+        auto next = [&rng](uint32_t n) {
+            rng = rng * 6364136223846793005ull + 1442695040888963407ull;
+            return (uint32_t)((rng >> 33) % n);
+        };
+        for (int k = 2; k <= 8; k++) {
+            const int (*prev_idx)[8] = idx[(k - 1) & 1];
+            const int npos = hk_steps(k) * 64, ngrp = npos / 16;
+            std::vector<hk_item> pos(npos, hk_item{});
+            int n = 0;
+            for (int S = 1; S < 256; S++)
+                if (__builtin_popcount(S) == k)
+                    for (int v = 0; v < 8; v++)
+                        if (S & (1 << v)) {
+                            hk_item &m = pos[n++];
+                            m.S = (uint8_t)S;
+                            m.v = (uint8_t)v;
+                            m.valid = true;
+                            int t = 0;
+                            for (int u = 0; u < 8; u++)
+                                if (u != v && (S & (1 << u))) m.ord[t++] = (uint8_t)u;
+                        }
+            // layer 8 keeps its 8 items in lanes 0..7 (the kernel reduces over them)
+            if (k < 8) {
+                // spread the items over all 16-lane groups before searching
+                std::vector<hk_item> spread(npos, hk_item{});
+                for (int i = 0; i < n; i++) spread[(i % ngrp) * 16 + (i / ngrp)] = pos[i];
+                if (n <= ngrp * 16 && (n + ngrp - 1) / ngrp <= 16) pos = spread;
+            }
+            std::vector<int> cost(ngrp);
+            for (int g = 0; g < ngrp; g++) cost[g] = hk_group_cost(&pos[g * 16], k, prev_idx);
+            const int iters = k < 8 ? 40000 : 2000;
+            for (int it = 0; it < iters; it++) {
+                const bool allow_worse = it < iters / 2 && next(16) == 0;
+                int p = (int)next(npos);
+                if (next(2) == 0 || k == 8) {
+                    hk_item &m = pos[p];
+                    if (!m.valid || k < 3) continue;
+                    int a = (int)next(k - 1), b = (int)next(k - 1);
+                    if (a == b) continue;
+                    std::swap(m.ord[a], m.ord[b]);
+                    int c = hk_group_cost(&pos[(p / 16) * 16], k, prev_idx);
+                    if (c <= cost[p / 16] || (allow_worse && c == cost[p / 16] + 1)) cost[p / 16] = c;
+                    else std::swap(m.ord[a], m.ord[b]);
+                } else {
+                    int q = (int)next(npos);
+                    if (p / 16 == q / 16) continue;
+                    std::swap(pos[p], pos[q]);
+                    int cp = hk_group_cost(&pos[(p / 16) * 16], k, prev_idx);
+                    int cq = hk_group_cost(&pos[(q / 16) * 16], k, prev_idx);
+                    int d = cp + cq - cost[p / 16] - cost[q / 16];
+                    if (d <= 0 || (allow_worse && d == 1)) {
+                        cost[p / 16] = cp;
+                        cost[q / 16] = cq;
+                    } else
+                        std::swap(pos[p], pos[q]);
+                }
+            }
+            // emit the layer's table words and record where its entries live
+            for (int s = 0; s < hk_steps(k); s++)
+                for (int lane = 0; lane < 64; lane++) {
+                    const hk_item &m = pos[s * 64 + lane];
+                    if (!m.valid) continue;
+                    idx[k & 1][m.S][m.v] = s * 64 + lane;
+                    uint32_t word[8] = {0};
+                    word[0] = (uint32_t)((s * 64 + lane) * 16) | 0x80000000u;
+                    for (int t = 0; t < k - 1; t++) {
+                        int u = m.ord[t];
+                        word[1 + t] = (uint32_t)(prev_idx[m.S ^ (1 << m.v)][u] * 16) | ((uint32_t)((u * 8 + m.v) * 16) << 16);
+                    }
+                    for (int w = 0; w < hk_words4(k) * 4; w++) {
+                        size_t word4 = (size_t)hk_tab_first(k) + (size_t)s * hk_words4(k) + w / 4;
+                        tab[(word4 * 64 + lane) * 4 + w % 4] = word[w];
+                    }
+                }
+        }
+    });
+    return tab;
+}
+
 }  // namespace
 
 bool dtfm_fast64_applicable(const dtfm_problem *pr) { return pr->N == 64 && pr->D_dp == 8 && pr->D_pp == 8; }
 
-// Builds the rank tables and the per-lane Held-Karp item tables of a 64-device problem.
+// Builds the rank tables of a 64-device problem and uploads the Held-Karp item table.
 int dtfm_fast64_prepare(dtfm_problem *pr)
 {
     const int N = pr->N;
@@ -334,29 +490,7 @@ int dtfm_fast64_prepare(dtfm_problem *pr)
                        pr->f64_rank, pr->f64_rank_val);
     DTFM_HIP(hipGetLastError());
 
-    std::vector<uint32_t> tab((size_t)(3 * N_HSTEP) * 64, 0u);
-    uint32_t *h_nib = tab.data(), *h_a = h_nib + N_HSTEP * 64, *h_b = h_a + N_HSTEP * 64;
-    int hs = 0;
-    for (int k = 2; k <= 8; k++) {
-        // Held-Karp items of layer k: (subset, end node v in it), subsets ascending, v ascending
-        std::vector<std::pair<uint32_t, int>> items;
-        for (uint32_t S = 1; S < 256; S++)
-            if (__builtin_popcount(S) == k)
-                for (int v = 0; v < 8; v++)
-                    if (S & (1u << v)) items.push_back({S, v});
-        for (int s = 0; s < hk_steps(k); s++, hs++)
-            for (int lane = 0; lane < 64; lane++) {
-                int i = s * 64 + lane;
-                if (i >= (int)items.size()) continue;
-                uint32_t S = items[i].first, v = items[i].second, rest = S ^ (1u << v), nib = 0;
-                int t = 0;
-                for (int u = 0; u < 8; u++)
-                    if (rest & (1u << u)) nib |= (uint32_t)u << (4 * t++);
-                h_nib[hs * 64 + lane] = nib;
-                h_a[hs * 64 + lane] = (rest * 8) | ((v * 8) << 16);
-                h_b[hs * 64 + lane] = ((v * 256 + S) * 8) | 0x80000000u;
-            }
-    }
+    const std::vector<uint32_t> &tab = hk_item_table();
     DTFM_HIP(hipMalloc((void **)&pr->f64_steps, tab.size() * sizeof(uint32_t)));
     DTFM_HIP(hipMemcpy(pr->f64_steps, tab.data(), tab.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64),
