@@ -218,11 +218,7 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
                 const uint32_t rb0 = byte_of(rowdev[0], 0) * RSTRIDE, rb1 = byte_of(rowdev[1], 0) * RSTRIDE;
 #pragma unroll
                 for (int c = 0; c < 8; c++)
-#ifdef EXP_SKIP_GATHER
-                    wnext[c] = rb0 + coloff[0][c] + ((rb1 + coloff[1][c]) << 16);
-#else
                     wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
-#endif
             }
 #pragma unroll
             for (int r = 0; r < 8; r++) {
@@ -234,11 +230,7 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
                     const uint32_t rb0 = byte_of(rowdev[0], r + 1) * RSTRIDE, rb1 = byte_of(rowdev[1], r + 1) * RSTRIDE;
 #pragma unroll
                     for (int c = 0; c < 8; c++)
-#ifdef EXP_SKIP_GATHER
-                        wnext[c] = rb0 + coloff[0][c] + ((rb1 + coloff[1][c]) << 16);
-#else
                         wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
-#endif
                 }
 #pragma unroll
                 for (int i = 0; i < BINOM8[r + 1]; i++) {
@@ -294,14 +286,12 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
             // layer 1: tab[{v}][v] = 0 at entry v of the odd buffer
             if (lane < 8) *reinterpret_cast<double2 *>(wl + OFF_BUF1 + lane * 16) = make_double2(0.0, 0.0);
             WAVE_LDS_SYNC();
-#ifndef EXP_SKIP_HK
             hk_layer<2>(wl, hktab, ghat_off, lane);
             hk_layer<3>(wl, hktab, ghat_off, lane);
             hk_layer<4>(wl, hktab, ghat_off, lane);
             hk_layer<5>(wl, hktab, ghat_off, lane);
             hk_layer<6>(wl, hktab, ghat_off, lane);
             hk_layer<7>(wl, hktab, ghat_off, lane);
-#endif
             // the 8 items of the last layer sit in lanes 0..7 (others hold +inf): PP = min over them
             double2 pp = hk_layer<8>(wl, hktab, ghat_off, lane);
 #pragma unroll
