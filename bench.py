@@ -37,19 +37,25 @@ import workloads  # noqa: E402
 # ---- algorithmic operation count of one candidate evaluation (N, D_dp, D_pp) -------------------
 # DataP (Eq. 2): N (D_dp-1) fp64 adds and N + D_pp max.
 # Matching (Eq. 3), chosen algorithm = min-max subset DP over the columns of each D_dp x D_dp
-#   block: D_dp 2^(D_dp-1) transitions of one max and one min each, per stage pair, on 16-bit ranks
-#   (packed two per 32-bit lane-op). The part that any algorithm must do is reading/comparing the
-#   D_dp^2 entries of every block once (reported as `matching_compulsory_ops`).
+#   block on 16-bit ranks: a state with k columns takes k max and k-1 min, states with k >= 2:
+#   sum_k C(D_dp,k) (2k-1) 16-bit ops per stage pair (1785 at D_dp = 8), packed two per 32-bit
+#   lane-op. What ANY algorithm must do is look at the D_dp^2 entries of every block once
+#   (reported as `matching_compulsory_ops`).
 # Held-Karp (Eq. 4): D_pp (D_pp-1) 2^(D_pp-2) relaxations of one fp64 add and one fp64 min.
 # Peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.32 T lane-ops/s for 32/64-bit vector ops
 # (fp64 add/min/max issue at full rate), twice that for packed 16-bit ops.
 VALU_LANE_OPS_PER_S = 256 * 4 * 16 * 2.4e9
+# HBM bytes per candidate of the evaluation kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/k_eval_fast64_C2_P1048576.md (269.7 MB + 8.4 MB per 1,048,576 candidates,
+# each counter scaled by its reading for a 1 GiB device copy). Algorithmic: 4N + 8 = 264 B.
+MEASURED_HBM_BYTES_PER_CANDIDATE = 265.2
 
 
 def algorithmic_ops(N, D_dp, D_pp):
+    from math import comb
     pairs = D_pp * (D_pp - 1) // 2
     dp = N * (D_dp - 1) + N + D_pp
-    match16 = pairs * (D_dp * 2 ** (D_dp - 1) - D_dp) * 2
+    match16 = pairs * sum(comb(D_dp, k) * (2 * k - 1) for k in range(2, D_dp + 1))
     hk = D_pp * (D_pp - 1) * 2 ** (D_pp - 2) * 2 if D_pp >= 2 else 0
     return {"datap_fp64": dp, "matching_u16": match16, "held_karp_fp64": hk,
             "matching_compulsory_ops": pairs * D_dp * D_dp}
@@ -61,6 +67,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="only the population-evaluation launches plus one 1 GiB device copy (for rocprofv3 runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (candidates are independent; see DESIGN.md "
@@ -81,6 +89,22 @@ def main():
     prob = dtfm.create_problem(w.latency, w.bandwidth, w.c_dp, w.c_pp, w.D_dp, w.D_pp)
     pop0 = torch.from_numpy(workloads.random_population(P, N, seed=1)).cuda()
 
+    if args.roofline_only:
+        # what the committed rocprofv3 summaries are taken from: the evaluation kernel at the roofline
+        # launch size, and a plain copy of known size to calibrate the HBM byte counters
+        perms = torch.from_numpy(workloads.random_population(1 << 16, N, seed=3)).cuda().repeat(16, 1).contiguous()
+        out = torch.empty(perms.shape[0], dtype=torch.float64, device="cuda")
+        for _ in range(10):
+            dtfm.eval_population(prob, perms, out)
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"roofline_only": True, "eval_launch_candidates": int(perms.shape[0]),
+                          "copy_bytes_each_way": int(src.numel() * 4)}))
+        return
+
     # ---- the timed steps: K generations of the evolutionary search ---------------------------
     pop = pop0.clone()
     if args.warmup > 0:
@@ -98,7 +122,8 @@ def main():
 
     # ---- roofline of the population-evaluation work, HIP events on the launch stream ---------
     def time_eval(Pe, reps):
-        perms = torch.from_numpy(workloads.random_population(Pe, N, seed=3)).cuda()
+        base = torch.from_numpy(workloads.random_population(min(Pe, 1 << 16), N, seed=3)).cuda()
+        perms = base if Pe <= base.shape[0] else base.repeat(Pe // base.shape[0], 1).contiguous()
         out = torch.empty(Pe, dtype=torch.float64, device="cuda")
         for _ in range(3):
             dtfm.eval_population(prob, perms, out)
@@ -124,8 +149,10 @@ def main():
     peak = total_ops / t_min_per_cand / 1e12
     achieved = total_ops * P_big / t_big / 1e12
     roofline = {"bound": "alu", "achieved": achieved, "peak": peak, "unit": "Tops/s",
-                "frac": achieved / peak, "traffic": None,
-                "kernel": "dtfm_eval_population", "launch_candidates": P_big,
+                "frac": achieved / peak, "traffic": MEASURED_HBM_BYTES_PER_CANDIDATE * P_big,
+                "traffic_unit": "bytes per launch (rocprofv3 counters, see profiles/)",
+                "algorithmic_hbm_bytes_per_launch": (4 * N + 8) * P_big,
+                "kernel": "k_eval_fast64 (dtfm_eval_population)", "launch_candidates": P_big,
                 "launch_seconds": t_big, "ops_per_candidate": ops,
                 "eval_population_cands_per_s": {"P=4096": P / t_small, "P=1048576": P_big / t_big}}
 
