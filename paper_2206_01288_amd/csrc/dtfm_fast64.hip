@@ -71,7 +71,8 @@ constexpr int OFF_BUF0 = 0;                                        // double2 [3
 constexpr int OFF_BUF1 = OFF_BUF0 + HK_BUF_ENTRIES * 16;           // double2 [320]: odd layers
 constexpr int OFF_GHAT = OFF_BUF1 + HK_BUF_ENTRIES * 16;           // double2 [2 candidate pairs][8][8]
 constexpr int OFF_PB = OFF_GHAT + 2 * 1024;                        // u8 [4 candidates][64] perm, stage-major
-constexpr int WAVE_LDS_BYTES = OFF_PB + CANDS * 64;                // 12544
+constexpr int OFF_PBCUR = OFF_PB + CANDS * 64;                     // u8 [4][64]: current rows (local search)
+constexpr int WAVE_LDS_BYTES = OFF_PBCUR + CANDS * 64;             // 12800
 constexpr int WAVES_PER_BLOCK = 8;
 constexpr int LDS_TOTAL = LDS_RANK_BYTES + LDS_HKTAB_BYTES + WAVES_PER_BLOCK * WAVE_LDS_BYTES;
 
@@ -143,18 +144,26 @@ __device__ __forceinline__ double2 hk_layer(unsigned char *wl, const unsigned ch
 // byte k (0..7) of a 64-bit value held as two dwords
 __device__ __forceinline__ uint32_t byte_of(uint2 v, int k) { return ((k < 4 ? v.x : v.y) >> (8 * (k & 3))) & 0xFFu; }
 
-__global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
-k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank_tab,
-              const double *__restrict__ rank_val, const uint32_t *__restrict__ step_tab,
-              const int32_t *__restrict__ perm, size_t P, double *__restrict__ cost,
-              double *__restrict__ ghat_out, double *__restrict__ datap_out)
-{
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint16_t *R = reinterpret_cast<const uint16_t *>(smem);
-    const unsigned char *hktab = smem + LDS_RANK_BYTES;
-    unsigned char *wl = smem + LDS_RANK_BYTES + LDS_HKTAB_BYTES + wave * WAVE_LDS_BYTES;
+// Per-wavefront context: LDS pointers and the lane's fixed role in the matching programme.
+struct wave_ctx {
+    unsigned char *wl;            // this wavefront's LDS slice
+    const uint16_t *R;            // rank table (LDS)
+    const unsigned char *hktab;   // Held-Karp item table (LDS)
+    int lane;
+    int mc;                       // candidate slot 0..3 whose matchings this lane computes
+    bool couple_valid;            // lanes 14, 15 of each 16 repeat couple 13 and write nothing
+    int j1[2], j2[2];             // the lane's two stage pairs (j1 < j2)
+};
 
+// Loads the workgroup's tables into LDS and derives the lane roles. Ends with a workgroup barrier.
+__device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16_t *rank_tab, const uint32_t *step_tab)
+{
+    wave_ctx cx;
+    cx.lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    cx.R = reinterpret_cast<const uint16_t *>(smem);
+    cx.hktab = smem + LDS_RANK_BYTES;
+    cx.wl = smem + LDS_RANK_BYTES + LDS_HKTAB_BYTES + wave * WAVE_LDS_BYTES;
     // rank table -> LDS, rows re-strided (two entries per thread per pass)
     for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
         const int row = i / (NDEV / 2), col2 = i - row * (NDEV / 2);
@@ -164,13 +173,13 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
     for (int i = threadIdx.x; i < LDS_HKTAB_BYTES / 16; i += blockDim.x)
         reinterpret_cast<uint4 *>(smem + LDS_RANK_BYTES)[i] = reinterpret_cast<const uint4 *>(step_tab)[i];
     // zero diagonals of the four coarsened graphs (never overwritten): entry [pair][j][j][cand & 1]
-    if (lane < CANDS * 8)
-        *reinterpret_cast<double *>(wl + OFF_GHAT + (lane >> 4) * 1024 + (lane & 7) * 9 * 16 + ((lane >> 3) & 1) * 8) = 0.0;
-    // matching role of this lane: candidate slot and the couple of stage pairs (2q, 2q+1) in
-    // lexicographic pair order; lanes with q = 14, 15 repeat couple 13 and write nothing
-    const int mc = lane >> 4, q = (lane & 15) < 14 ? (lane & 15) : 13;
-    const bool couple_valid = (lane & 15) < 14;
-    int j1[2], j2[2];
+    if (cx.lane < CANDS * 8)
+        *reinterpret_cast<double *>(cx.wl + OFF_GHAT + (cx.lane >> 4) * 1024 + (cx.lane & 7) * 9 * 16 +
+                                    ((cx.lane >> 3) & 1) * 8) = 0.0;
+    // matching role: candidate slot and the couple of stage pairs (2q, 2q+1) in lexicographic order
+    cx.mc = cx.lane >> 4;
+    const int q = (cx.lane & 15) < 14 ? (cx.lane & 15) : 13;
+    cx.couple_valid = (cx.lane & 15) < 14;
 #pragma unroll
     for (int h = 0; h < 2; h++) {
         int t = 2 * q + h, a = 0;
@@ -178,11 +187,157 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
             t -= 7 - a;
             a++;
         }
-        j1[h] = a;
-        j2[h] = a + 1 + t;
+        cx.j1[h] = a;
+        cx.j2[h] = a + 1 + t;
     }
     __syncthreads();
+    return cx;
+}
 
+// Evaluates the four candidates whose rows are in the wavefront's LDS slice at OFF_PB (stage-major
+// bytes, already visible to all lanes); dev[c] = device at position `lane` of candidate c.
+// On return total[c] (Eq. 1) and datap[c] (Eq. 2 + max) are held by every lane. ghat_out, if not
+// null, receives the coarsened graphs of candidates cand0 .. cand0+3 that are < P.
+__device__ __forceinline__ void eval_quad(const wave_ctx &cx, const double *__restrict__ W_dp,
+                                          const double *__restrict__ rank_val, const int (&dev)[CANDS],
+                                          double (&total)[CANDS], double (&datap)[CANDS],
+                                          double *__restrict__ ghat_out, size_t cand0, size_t P)
+{
+    unsigned char *wl = cx.wl;
+    const uint16_t *R = cx.R;
+    const int lane = cx.lane;
+    // ---- a4: bottleneck matchings of this lane's two stage pairs, as ranks ----
+    uint32_t gfull;
+    {
+        const unsigned char *pb = wl + OFF_PB + cx.mc * 64;
+        uint2 rowdev[2], coldev[2];
+        uint32_t coloff[2][8];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            rowdev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * cx.j1[h]);   // devices of stage j1, slots 0..7
+            coldev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * cx.j2[h]);   // devices of stage j2
+#pragma unroll
+            for (int c = 0; c < 8; c++) coloff[h][c] = byte_of(coldev[h], c);
+        }
+        uint32_t G[256];
+        // rows are gathered one layer ahead of their use; the scheduling barriers keep the
+        // register footprint to two rows plus two layers of the table
+        uint32_t wnext[8];
+        {
+            const uint32_t rb0 = byte_of(rowdev[0], 0) * RSTRIDE, rb1 = byte_of(rowdev[1], 0) * RSTRIDE;
+#pragma unroll
+            for (int c = 0; c < 8; c++)
+                wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
+        }
+#pragma unroll
+        for (int r = 0; r < 8; r++) {
+            // row r of both blocks: w[c] = (rank of pair-0 entry (r,c)) | (rank of pair-1 entry) << 16
+            uint32_t w[8];
+#pragma unroll
+            for (int c = 0; c < 8; c++) w[c] = wnext[c];
+            if (r < 7) {
+                const uint32_t rb0 = byte_of(rowdev[0], r + 1) * RSTRIDE, rb1 = byte_of(rowdev[1], r + 1) * RSTRIDE;
+#pragma unroll
+                for (int c = 0; c < 8; c++)
+                    wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
+            }
+#pragma unroll
+            for (int i = 0; i < BINOM8[r + 1]; i++) {
+                const int S = LAYER.s[r + 1][i];
+                uint32_t acc = 0;
+                bool first = true;
+#pragma unroll
+                for (int c = 0; c < 8; c++) {
+                    if (!(S & (1 << c))) continue;
+                    const uint32_t m = (r == 0) ? w[c] : pk_max(G[S ^ (1 << c)], w[c]);
+                    acc = first ? m : pk_min(acc, m);
+                    first = false;
+                }
+                G[S] = acc;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        gfull = G[255];
+    }
+    // ---- winning ranks -> fp64 weights -> coarsened graphs in LDS ----
+    {
+        const double e0 = rank_val[gfull & 0xFFFFu], e1 = rank_val[gfull >> 16];
+        if (cx.couple_valid) {   // entry [candidate pair][u][v][candidate & 1]
+            double *gh = reinterpret_cast<double *>(wl + OFF_GHAT + (cx.mc >> 1) * 1024) + (cx.mc & 1);
+            gh[(cx.j1[0] * 8 + cx.j2[0]) * 2] = e0;
+            gh[(cx.j2[0] * 8 + cx.j1[0]) * 2] = e0;
+            gh[(cx.j1[1] * 8 + cx.j2[1]) * 2] = e1;
+            gh[(cx.j2[1] * 8 + cx.j1[1]) * 2] = e1;
+        }
+    }
+    WAVE_LDS_SYNC();
+
+    // ---- per candidate pair: a5 Held-Karp, a2/a3 DataP, a6 total ----
+#pragma nounroll
+    for (int pr = 0; pr < CANDS / 2; pr++) {
+        // DataP gathers first: their latency hides behind Held-Karp
+        double wv[2][8];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int d = pr == 0 ? dev[h] : dev[2 + h];
+            const uint2 mates = *reinterpret_cast<const uint2 *>(wl + OFF_PB + (2 * pr + h) * 64 + (lane & ~7));
+            const double *wrow = W_dp + d * NDEV;
+#pragma unroll
+            for (int k = 0; k < 8; k++) wv[h][k] = wrow[byte_of(mates, k)];   // own slot: the zero diagonal
+        }
+        const uint32_t ghat_off = OFF_GHAT + pr * 1024;
+        if (ghat_out != nullptr) {
+            const double2 g2 = *reinterpret_cast<const double2 *>(wl + ghat_off + lane * 16);
+            if (cand0 + 2 * pr < P) ghat_out[(cand0 + 2 * pr) * 64 + lane] = g2.x;
+            if (cand0 + 2 * pr + 1 < P) ghat_out[(cand0 + 2 * pr + 1) * 64 + lane] = g2.y;
+        }
+        // layer 1: tab[{v}][v] = 0 at entry v of the odd buffer
+        if (lane < 8) *reinterpret_cast<double2 *>(wl + OFF_BUF1 + lane * 16) = make_double2(0.0, 0.0);
+        WAVE_LDS_SYNC();
+        hk_layer<2>(wl, cx.hktab, ghat_off, lane);
+        hk_layer<3>(wl, cx.hktab, ghat_off, lane);
+        hk_layer<4>(wl, cx.hktab, ghat_off, lane);
+        hk_layer<5>(wl, cx.hktab, ghat_off, lane);
+        hk_layer<6>(wl, cx.hktab, ghat_off, lane);
+        hk_layer<7>(wl, cx.hktab, ghat_off, lane);
+        // the 8 items of the last layer sit in lanes 0..7 (others hold +inf): PP = min over them
+        double2 pp = hk_layer<8>(wl, cx.hktab, ghat_off, lane);
+#pragma unroll
+        for (int o = 1; o <= 4; o <<= 1) {
+            pp.x = fmin(pp.x, __shfl_xor(pp.x, o));
+            pp.y = fmin(pp.y, __shfl_xor(pp.y, o));
+        }
+        pp.x = __shfl(pp.x, 0);
+        pp.y = __shfl(pp.y, 0);
+        double res[2], dpv[2];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            double sum = 0.0;
+#pragma unroll
+            for (int k = 0; k < 8; k++) sum = __dadd_rn(sum, wv[h][k]);
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) sum = fmax(sum, __shfl_xor(sum, o));
+            dpv[h] = sum;
+            res[h] = __dadd_rn(sum, h == 0 ? pp.x : pp.y);
+        }
+        if (pr == 0) {
+            total[0] = res[0]; total[1] = res[1]; datap[0] = dpv[0]; datap[1] = dpv[1];
+        } else {
+            total[2] = res[0]; total[3] = res[1]; datap[2] = dpv[0]; datap[3] = dpv[1];
+        }
+        WAVE_LDS_SYNC();   // the next pair reuses the buffers
+    }
+}
+
+__global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
+k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank_tab,
+              const double *__restrict__ rank_val, const uint32_t *__restrict__ step_tab,
+              const int32_t *__restrict__ perm, size_t P, double *__restrict__ cost,
+              double *__restrict__ ghat_out, double *__restrict__ datap_out)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const wave_ctx cx = wave_setup(smem, rank_tab, step_tab);
+    const int lane = cx.lane, wave = threadIdx.x >> 6;
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
     const size_t nquads = (P + CANDS - 1) / CANDS;
     for (size_t quad = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; quad < nquads; quad += nwaves) {
@@ -193,128 +348,172 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
             size_t cand = quad * CANDS + c;
             if (cand >= P) cand = P - 1;   // ragged tail: recompute the last row, never stored
             dev[c] = perm[cand * NDEV + lane];
-            wl[OFF_PB + c * 64 + lane] = (unsigned char)dev[c];
+            cx.wl[OFF_PB + c * 64 + lane] = (unsigned char)dev[c];
         }
         WAVE_LDS_SYNC();
-
-        // ---- a4: bottleneck matchings of this lane's two stage pairs, as ranks ----
-        uint32_t gfull;
-        {
-            const unsigned char *pb = wl + OFF_PB + mc * 64;
-            uint2 rowdev[2], coldev[2];
-            uint32_t coloff[2][8];
-#pragma unroll
-            for (int h = 0; h < 2; h++) {
-                rowdev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * j1[h]);   // devices of stage j1, slots 0..7
-                coldev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * j2[h]);   // devices of stage j2
-#pragma unroll
-                for (int c = 0; c < 8; c++) coloff[h][c] = byte_of(coldev[h], c);
+        double total[CANDS], datap[CANDS];
+        eval_quad(cx, W_dp, rank_val, dev, total, datap, ghat_out, quad * CANDS, P);
+        if (lane < CANDS) {
+            const size_t cand = quad * CANDS + lane;
+            const double t = lane == 0 ? total[0] : lane == 1 ? total[1] : lane == 2 ? total[2] : total[3];
+            const double d = lane == 0 ? datap[0] : lane == 1 ? datap[1] : lane == 2 ? datap[2] : datap[3];
+            if (cand < P) {
+                if (cost != nullptr) cost[cand] = t;
+                if (datap_out != nullptr) datap_out[cand] = d;
             }
-            uint32_t G[256];
-            // rows are gathered one layer ahead of their use; the scheduling barriers keep the
-            // register footprint to two rows plus two layers of the table
-            uint32_t wnext[8];
-            {
-                const uint32_t rb0 = byte_of(rowdev[0], 0) * RSTRIDE, rb1 = byte_of(rowdev[1], 0) * RSTRIDE;
-#pragma unroll
-                for (int c = 0; c < 8; c++)
-                    wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
-            }
-#pragma unroll
-            for (int r = 0; r < 8; r++) {
-                // row r of both blocks: w[c] = (rank of pair-0 entry (r,c)) | (rank of pair-1 entry) << 16
-                uint32_t w[8];
-#pragma unroll
-                for (int c = 0; c < 8; c++) w[c] = wnext[c];
-                if (r < 7) {
-                    const uint32_t rb0 = byte_of(rowdev[0], r + 1) * RSTRIDE, rb1 = byte_of(rowdev[1], r + 1) * RSTRIDE;
-#pragma unroll
-                    for (int c = 0; c < 8; c++)
-                        wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
-                }
-#pragma unroll
-                for (int i = 0; i < BINOM8[r + 1]; i++) {
-                    const int S = LAYER.s[r + 1][i];
-                    uint32_t acc = 0;
-                    bool first = true;
-#pragma unroll
-                    for (int c = 0; c < 8; c++) {
-                        if (!(S & (1 << c))) continue;
-                        const uint32_t m = (r == 0) ? w[c] : pk_max(G[S ^ (1 << c)], w[c]);
-                        acc = first ? m : pk_min(acc, m);
-                        first = false;
-                    }
-                    G[S] = acc;
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            gfull = G[255];
         }
-        // ---- winning ranks -> fp64 weights -> coarsened graphs in LDS ----
-        {
-            const double e0 = rank_val[gfull & 0xFFFFu], e1 = rank_val[gfull >> 16];
-            if (couple_valid) {   // entry [candidate pair][u][v][candidate & 1]
-                double *gh = reinterpret_cast<double *>(wl + OFF_GHAT + (mc >> 1) * 1024) + (mc & 1);
-                gh[(j1[0] * 8 + j2[0]) * 2] = e0;
-                gh[(j2[0] * 8 + j1[0]) * 2] = e0;
-                gh[(j1[1] * 8 + j2[1]) * 2] = e1;
-                gh[(j2[1] * 8 + j1[1]) * 2] = e1;
-            }
+    }
+}
+
+// ---- Sec. 3.4 local search with the paper's four-candidate neighbourhood, all rounds in one launch
+// Each wavefront carries its four candidates through every round: propose a swap (fastest link inside
+// each of the round's two stages, the four end-point swaps ranked by the paper's Gain), evaluate the
+// swapped allocation with eval_quad, keep it iff strictly cheaper. The fastest link is found on the
+// ranks (same order and same ties as the weights); the Gain sums use the fp64 weights in slot order.
+__device__ __forceinline__ void pair8_decode(int e, int &i, int &k)
+{
+    int a = 0;
+    while (e >= 7 - a) {
+        e -= 7 - a;
+        a++;
+    }
+    i = a;
+    k = a + 1 + e;
+}
+
+__global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
+k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_pp,
+                  const uint16_t *__restrict__ rank_tab, const double *__restrict__ rank_val,
+                  const uint32_t *__restrict__ step_tab, int32_t *__restrict__ perm, size_t P, int moves,
+                  double *__restrict__ cost, int64_t *__restrict__ applied)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const wave_ctx cx = wave_setup(smem, rank_tab, step_tab);
+    const int lane = cx.lane, wave = threadIdx.x >> 6;
+    unsigned char *wl = cx.wl;
+    const int grp = lane >> 4, sub = lane & 15;   // proposal role: 16 lanes per candidate
+    const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
+    const size_t nquads = (P + CANDS - 1) / CANDS;
+    for (size_t quad = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; quad < nquads; quad += nwaves) {
+        int cur[CANDS];          // current allocation: device at position `lane`
+        double cur_cost[CANDS], unused[CANDS];
+#pragma unroll
+        for (int c = 0; c < CANDS; c++) {
+            size_t cand = quad * CANDS + c;
+            if (cand >= P) cand = P - 1;
+            cur[c] = perm[cand * NDEV + lane];
+            wl[OFF_PB + c * 64 + lane] = (unsigned char)cur[c];
+            wl[OFF_PBCUR + c * 64 + lane] = (unsigned char)cur[c];
         }
         WAVE_LDS_SYNC();
-
-        // ---- per candidate pair: a5 Held-Karp, a2/a3 DataP, a6 total ----
+        eval_quad(cx, W_dp, rank_val, cur, cur_cost, unused, nullptr, quad * CANDS, P);
 #pragma nounroll
-        for (int pr = 0; pr < CANDS / 2; pr++) {
-            const size_t cand0 = quad * CANDS + 2 * pr;
-            // DataP gathers first: their latency hides behind Held-Karp
-            double wv[2][8];
-#pragma unroll
-            for (int h = 0; h < 2; h++) {
-                const int d = pr == 0 ? dev[h] : dev[2 + h];
-                const uint2 mates = *reinterpret_cast<const uint2 *>(wl + OFF_PB + (2 * pr + h) * 64 + (lane & ~7));
-                const double *wrow = W_dp + d * NDEV;
-#pragma unroll
-                for (int k = 0; k < 8; k++) wv[h][k] = wrow[byte_of(mates, k)];   // own slot: the zero diagonal
+        for (int r = 0; r < moves; r++) {
+            // ---- proposal for candidate `grp` by its 16 lanes ----
+            int j, jp;
+            {
+                int t = r % 28, a = 0;
+                while (t >= 7 - a) {
+                    t -= 7 - a;
+                    a++;
+                }
+                j = a;
+                jp = a + 1 + t;
             }
-            const uint32_t ghat_off = OFF_GHAT + pr * 1024;
-            if (ghat_out != nullptr) {
-                const double2 g2 = *reinterpret_cast<const double2 *>(wl + ghat_off + lane * 16);
-                if (cand0 < P) ghat_out[cand0 * 64 + lane] = g2.x;
-                if (cand0 + 1 < P) ghat_out[(cand0 + 1) * 64 + lane] = g2.y;
-            }
-            // layer 1: tab[{v}][v] = 0 at entry v of the odd buffer
-            if (lane < 8) *reinterpret_cast<double2 *>(wl + OFF_BUF1 + lane * 16) = make_double2(0.0, 0.0);
-            WAVE_LDS_SYNC();
-            hk_layer<2>(wl, hktab, ghat_off, lane);
-            hk_layer<3>(wl, hktab, ghat_off, lane);
-            hk_layer<4>(wl, hktab, ghat_off, lane);
-            hk_layer<5>(wl, hktab, ghat_off, lane);
-            hk_layer<6>(wl, hktab, ghat_off, lane);
-            hk_layer<7>(wl, hktab, ghat_off, lane);
-            // the 8 items of the last layer sit in lanes 0..7 (others hold +inf): PP = min over them
-            double2 pp = hk_layer<8>(wl, hktab, ghat_off, lane);
+            const unsigned char *pc = wl + OFF_PBCUR + grp * 64;
+            int slot[2][2];
 #pragma unroll
-            for (int o = 1; o <= 4; o <<= 1) {
-                pp.x = fmin(pp.x, __shfl_xor(pp.x, o));
-                pp.y = fmin(pp.y, __shfl_xor(pp.y, o));
-            }
-            pp.x = __shfl(pp.x, 0);
-            pp.y = __shfl(pp.y, 0);
+            for (int s = 0; s < 2; s++) {
+                const unsigned char *C = pc + 8 * (s == 0 ? j : jp);
+                uint32_t key = 0xFFFFFFFFu;   // (rank << 8) | pair index: first minimiser wins
 #pragma unroll
-            for (int h = 0; h < 2; h++) {
+                for (int e0 = 0; e0 < 32; e0 += 16) {
+                    const int e = e0 + sub;
+                    if (e < 28) {
+                        int i, k;
+                        pair8_decode(e, i, k);
+                        const uint32_t kk = ((uint32_t)cx.R[(int)C[i] * RSTRIDE + C[k]] << 8) | (uint32_t)e;
+                        key = kk < key ? kk : key;
+                    }
+                }
+#pragma unroll
+                for (int o = 1; o <= 8; o <<= 1) {
+                    const uint32_t ok = __shfl_xor(key, o);
+                    key = ok < key ? ok : key;
+                }
+                pair8_decode((int)(key & 0xFFu), slot[s][0], slot[s][1]);
+            }
+            const int Cj = 8 * j, Cjp = 8 * jp;
+            // lanes 0,1 of the group: mean over C_j' of w[x][.] for x = d1, d2; lanes 2,3: mean over C_j of w[y][.]
+            double mean = 0.0;
+            {
+                const int side = (sub >> 1) & 1;
+                const int dv = pc[(side == 0 ? Cj : Cjp) + slot[side][sub & 1]];
+                const unsigned char *other = pc + (side == 0 ? Cjp : Cj);
                 double sum = 0.0;
+                if (sub < 4) {
 #pragma unroll
-                for (int k = 0; k < 8; k++) sum = __dadd_rn(sum, wv[h][k]);
+                    for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, W_pp[dv * NDEV + other[i]]);
+                }
+                mean = __ddiv_rn(sum, 8.0);
+            }
+            const double link0 = W_pp[(int)pc[Cj + slot[0][0]] * NDEV + pc[Cj + slot[0][1]]];
+            const double link1 = W_pp[(int)pc[Cjp + slot[1][0]] * NDEV + pc[Cjp + slot[1][1]]];
+            const int base = lane & ~15;
+            const double mx[2] = {__shfl(mean, base + 0), __shfl(mean, base + 1)};
+            const double my[2] = {__shfl(mean, base + 2), __shfl(mean, base + 3)};
+            double bestg = 0.0;
+            int bk = -1;
 #pragma unroll
-                for (int o = 32; o >= 1; o >>= 1) sum = fmax(sum, __shfl_xor(sum, o));
-                const size_t cand = cand0 + h;
-                if (lane == 0 && cand < P) {
-                    if (cost != nullptr) cost[cand] = __dadd_rn(sum, h == 0 ? pp.x : pp.y);
-                    if (datap_out != nullptr) datap_out[cand] = sum;
+            for (int k = 0; k < 4; k++) {
+                double g = mx[k >> 1];
+                g = __dadd_rn(g, -link0);
+                g = __dadd_rn(g, my[k & 1]);
+                g = __dadd_rn(g, -link1);
+                if (bk < 0 || g > bestg) {
+                    bestg = g;
+                    bk = k;
                 }
             }
-            WAVE_LDS_SYNC();   // the next pair reuses the buffers
+            const int pa = Cj + slot[0][bk >> 1], pb_ = Cjp + slot[1][bk & 1];   // positions, pa < pb_
+            // ---- trial rows: every lane needs each candidate's swap ----
+            int trial[CANDS], ta[CANDS], tb[CANDS];
+#pragma unroll
+            for (int c = 0; c < CANDS; c++) {
+                ta[c] = __shfl(pa, c * 16);
+                tb[c] = __shfl(pb_, c * 16);
+                const int src = lane == ta[c] ? tb[c] : (lane == tb[c] ? ta[c] : lane);
+                trial[c] = wl[OFF_PBCUR + c * 64 + src];
+            }
+            WAVE_LDS_SYNC();
+#pragma unroll
+            for (int c = 0; c < CANDS; c++) wl[OFF_PB + c * 64 + lane] = (unsigned char)trial[c];
+            WAVE_LDS_SYNC();
+            double tcost[CANDS];
+            eval_quad(cx, W_dp, rank_val, trial, tcost, unused, nullptr, quad * CANDS, P);
+            // ---- accept iff strictly cheaper ----
+#pragma unroll
+            for (int c = 0; c < CANDS; c++) {
+                const bool take = tcost[c] < cur_cost[c];   // wave-uniform
+                if (take) {
+                    cur[c] = trial[c];
+                    cur_cost[c] = tcost[c];
+                    wl[OFF_PBCUR + c * 64 + lane] = (unsigned char)trial[c];
+                }
+                const size_t cand = quad * CANDS + c;
+                if (applied != nullptr && lane == 0 && cand < P)
+                    applied[cand * (size_t)moves + r] =
+                        take ? (long long)ta[c] * NDEV - (long long)ta[c] * (ta[c] + 1) / 2 + (tb[c] - ta[c] - 1) : -1ll;
+            }
+            WAVE_LDS_SYNC();
+        }
+#pragma unroll
+        for (int c = 0; c < CANDS; c++) {
+            const size_t cand = quad * CANDS + c;
+            if (cand < P) {
+                perm[cand * NDEV + lane] = cur[c];
+                if (lane == 0) cost[cand] = cur_cost[c];
+            }
         }
     }
 }
@@ -485,6 +684,8 @@ int dtfm_fast64_prepare(dtfm_problem *pr)
     DTFM_HIP(hipMemcpy(pr->f64_steps, tab.data(), tab.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
     hipDeviceProp_t prop;
     DTFM_HIP(hipGetDeviceProperties(&prop, pr->device));
     pr->f64_grid = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
@@ -508,6 +709,19 @@ int dtfm_fast64_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
     hipLaunchKernelGGL(k_eval_fast64, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
                        pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, cost, ghat, datap);
+    DTFM_HIP(hipGetLastError());
+    return DTFM_OK;
+}
+
+int dtfm_fast64_ls_gain4_enqueue(const dtfm_problem *pr, int32_t *perm, size_t rows, int moves, double *cost,
+                                 int64_t *applied, hipStream_t st)
+{
+    if (rows == 0) return DTFM_OK;
+    size_t quads = (rows + CANDS - 1) / CANDS;
+    size_t blocks = (quads + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
+    hipLaunchKernelGGL(k_ls_gain4_fast64, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
+                       pr->W_pp, pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, moves, cost, applied);
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
 }

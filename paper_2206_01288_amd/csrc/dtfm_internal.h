@@ -79,6 +79,10 @@ void dtfm_fast64_release(dtfm_problem *pr);
 int dtfm_fast64_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows, double *cost, double *ghat,
                         double *datap, hipStream_t st);
 
+// all `moves` rounds of the GAIN4 local search in one launch; perm in/out, cost out, applied may be null
+int dtfm_fast64_ls_gain4_enqueue(const dtfm_problem *pr, int32_t *perm, size_t rows, int moves, double *cost,
+                                 int64_t *applied, hipStream_t st);
+
 // ---- search (dtfm_search.hip) -----------------------------------------------------------------
 struct dtfm_ls_bufs {
     double *cur;        // P: current cost of each candidate

@@ -248,6 +248,8 @@ int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm
                     int neighbourhood, double *cost, int64_t *applied, hipStream_t st)
 {
     if (P == 0) return DTFM_OK;
+    if (pr->fast64 && neighbourhood == DTFM_GAIN4)
+        return dtfm_fast64_ls_gain4_enqueue(pr, perm, P, moves, cost, applied, st);
     const int N = pr->N;
     const long long M = (long long)N * (N - 1) / 2;
     int rc = dtfm_eval_enqueue(pr, b.ev, perm, P, b.cur, st);
