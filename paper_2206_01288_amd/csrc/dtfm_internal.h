@@ -103,6 +103,7 @@ struct dtfm_ga_bufs {
     int32_t *next;      // P * N
     double *next_cost;  // P
     int32_t *src;       // P: origin index of each survivor
+    int32_t *rank;      // P + lambda: rank of each key under (cost, origin)
     dtfm_ls_bufs ls;
 };
 dtfm_ga_bufs dtfm_ga_carve(const dtfm_problem *pr, dtfm_arena &ar, const dtfm_ga_params &prm);

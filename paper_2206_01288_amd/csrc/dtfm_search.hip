@@ -425,28 +425,52 @@ __global__ void k_make_offspring(uint32_t k0, uint32_t k1, uint32_t g, const int
 }
 
 // Replacement: rank of element i among parents (origin 0..P-1) and offspring (origin P..P+L-1)
-// under the order (cost, origin); the P lowest survive, placed at their rank.
-__global__ void k_rank(const double *__restrict__ cost, const double *__restrict__ off_cost, int P, int L,
-                       double *__restrict__ next_cost, int32_t *__restrict__ src,
-                       double *__restrict__ trace_slot)
+// under the order (cost, origin); the P lowest survive, placed at their rank. The count over the
+// P+L keys is split: block (x, y) counts, for 256 elements i, the keys of chunk y (staged in LDS)
+// that precede them, and adds the partial count to rank[i].
+#define DTFM_RANK_CHUNK 1024
+__global__ void k_rank_count(const double *__restrict__ cost, const double *__restrict__ off_cost, int P, int L,
+                             int32_t *__restrict__ rank)
+{
+    __shared__ double s_key[DTFM_RANK_CHUNK];
+    const int n = P + L;
+    const int j0 = blockIdx.y * DTFM_RANK_CHUNK;
+    for (int t = threadIdx.x; t < DTFM_RANK_CHUNK; t += blockDim.x) {
+        int j = j0 + t;
+        s_key[t] = j < P ? cost[j] : (j < n ? off_cost[j - P] : INFINITY);
+    }
+    __syncthreads();
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const double ci = i < P ? cost[i] : off_cost[i - P];
+    const int jn = n - j0 < DTFM_RANK_CHUNK ? n - j0 : DTFM_RANK_CHUNK;
+    int cnt = 0;
+    for (int t = 0; t < jn; t++) {
+        const double cj = s_key[t];
+        cnt += (cj < ci || (cj == ci && j0 + t < i)) ? 1 : 0;
+    }
+    if (cnt) atomicAdd(&rank[i], cnt);
+}
+
+__global__ void k_rank_place(const double *__restrict__ cost, const double *__restrict__ off_cost, int P, int L,
+                             const int32_t *__restrict__ rank, double *__restrict__ next_cost,
+                             int32_t *__restrict__ src, double *__restrict__ trace_slot)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= P + L) return;
-    double ci = i < P ? cost[i] : off_cost[i - P];
-    int rank = 0;
-    for (int j = 0; j < P; j++) {
-        double cj = cost[j];
-        rank += (cj < ci || (cj == ci && j < i)) ? 1 : 0;
+    const int r = rank[i];
+    if (r < P) {
+        const double ci = i < P ? cost[i] : off_cost[i - P];
+        next_cost[r] = ci;
+        src[r] = i;
+        if (r == 0) *trace_slot = ci;
     }
-    for (int j = 0; j < L; j++) {
-        double cj = off_cost[j];
-        rank += (cj < ci || (cj == ci && P + j < i)) ? 1 : 0;
-    }
-    if (rank < P) {
-        next_cost[rank] = ci;
-        src[rank] = i;
-        if (rank == 0) *trace_slot = ci;
-    }
+}
+
+__global__ void k_fill_i32(int32_t *__restrict__ dst, int32_t v, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = v;
 }
 
 __global__ void k_gather_rows(const int32_t *__restrict__ pop, const int32_t *__restrict__ off, int P, int N,
@@ -467,6 +491,7 @@ dtfm_ga_bufs dtfm_ga_carve(const dtfm_problem *pr, dtfm_arena &ar, const dtfm_ga
     b.next = ar.take<int32_t>(P * N);
     b.next_cost = ar.take<double>(P);
     b.src = ar.take<int32_t>(P);
+    b.rank = ar.take<int32_t>(P + L);
     b.ls = dtfm_ls_carve(pr, ar, P > L ? P : L, prm.neighbourhood);
     return b;
 }
@@ -490,7 +515,13 @@ int dtfm_ga_enqueue(const dtfm_problem *pr, const dtfm_ga_bufs &b, uint64_t seed
         DTFM_HIP(hipGetLastError());
         rc = dtfm_ls_enqueue(pr, b.ls, b.off, L, prm.ls_moves, prm.neighbourhood, b.off_cost, nullptr, st);
         if (rc != DTFM_OK) return rc;
-        hipLaunchKernelGGL(k_rank, dim3((P + L + 255) / 256), dim3(256), 0, st, cost, b.off_cost, P, L,
+        const int nk = P + L;
+        hipLaunchKernelGGL(k_fill_i32, dim3((nk + 255) / 256), dim3(256), 0, st, b.rank, 0, (size_t)nk);
+        DTFM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(k_rank_count, dim3((nk + 255) / 256, (nk + DTFM_RANK_CHUNK - 1) / DTFM_RANK_CHUNK), dim3(256), 0,
+                           st, cost, b.off_cost, P, L, b.rank);
+        DTFM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(k_rank_place, dim3((nk + 255) / 256), dim3(256), 0, st, cost, b.off_cost, P, L, b.rank,
                            b.next_cost, b.src, best_trace + g);
         DTFM_HIP(hipGetLastError());
         hipLaunchKernelGGL(k_gather_rows, dim3(P), dim3(DTFM_WAVE), 0, st, population, b.off, P, N, b.src, b.next);
