@@ -28,7 +28,7 @@
 
 namespace {
 
-constexpr int NDEV = 64, CANDS = 4;   // candidates per wavefront pass
+constexpr int NDEV = 64, CANDS = 4;   // most candidates per wavefront pass (kernels are built for 4 and 2)
 // Row stride of the rank table in LDS, in 16-bit entries. 66 instead of 64 skews consecutive rows by
 // one 4-byte bank, so that lanes reading the same column of different rows hit different banks.
 constexpr int RSTRIDE = 66;
@@ -156,6 +156,7 @@ struct wave_ctx {
 };
 
 // Loads the workgroup's tables into LDS and derives the lane roles. Ends with a workgroup barrier.
+template <int NC>
 __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16_t *rank_tab, const uint32_t *step_tab)
 {
     wave_ctx cx;
@@ -177,9 +178,10 @@ __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16
         *reinterpret_cast<double *>(cx.wl + OFF_GHAT + (cx.lane >> 4) * 1024 + (cx.lane & 7) * 9 * 16 +
                                     ((cx.lane >> 3) & 1) * 8) = 0.0;
     // matching role: candidate slot and the couple of stage pairs (2q, 2q+1) in lexicographic order
-    cx.mc = cx.lane >> 4;
+    // (with NC = 2 the upper half of the wavefront repeats the lower half's work and writes nothing)
+    cx.mc = (cx.lane >> 4) % NC;
     const int q = (cx.lane & 15) < 14 ? (cx.lane & 15) : 13;
-    cx.couple_valid = (cx.lane & 15) < 14;
+    cx.couple_valid = (cx.lane & 15) < 14 && cx.lane < NC * 16;
 #pragma unroll
     for (int h = 0; h < 2; h++) {
         int t = 2 * q + h, a = 0;
@@ -194,10 +196,11 @@ __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16
     return cx;
 }
 
-// Evaluates the four candidates whose rows are in the wavefront's LDS slice at OFF_PB (stage-major
+// Evaluates the NC (4 or 2) candidates whose rows are in the wavefront's LDS slice at OFF_PB (stage-major
 // bytes, already visible to all lanes); dev[c] = device at position `lane` of candidate c.
 // On return total[c] (Eq. 1) and datap[c] (Eq. 2 + max) are held by every lane. ghat_out, if not
 // null, receives the coarsened graphs of candidates cand0 .. cand0+3 that are < P.
+template <int NC>
 __device__ __forceinline__ void eval_quad(const wave_ctx &cx, const double *__restrict__ W_dp,
                                           const double *__restrict__ rank_val, const int (&dev)[CANDS],
                                           double (&total)[CANDS], double (&datap)[CANDS],
@@ -274,7 +277,7 @@ __device__ __forceinline__ void eval_quad(const wave_ctx &cx, const double *__re
 
     // ---- per candidate pair: a5 Held-Karp, a2/a3 DataP, a6 total ----
 #pragma nounroll
-    for (int pr = 0; pr < CANDS / 2; pr++) {
+    for (int pr = 0; pr < NC / 2; pr++) {
         // DataP gathers first: their latency hides behind Held-Karp
         double wv[2][8];
 #pragma unroll
@@ -322,6 +325,7 @@ __device__ __forceinline__ void eval_quad(const wave_ctx &cx, const double *__re
         }
         if (pr == 0) {
             total[0] = res[0]; total[1] = res[1]; datap[0] = dpv[0]; datap[1] = dpv[1];
+            if (NC == 2) { total[2] = total[3] = datap[2] = datap[3] = 0.0; }
         } else {
             total[2] = res[0]; total[3] = res[1]; datap[2] = dpv[0]; datap[3] = dpv[1];
         }
@@ -329,6 +333,7 @@ __device__ __forceinline__ void eval_quad(const wave_ctx &cx, const double *__re
     }
 }
 
+template <int NC>
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
 k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank_tab,
               const double *__restrict__ rank_val, const uint32_t *__restrict__ step_tab,
@@ -336,25 +341,25 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
               double *__restrict__ ghat_out, double *__restrict__ datap_out)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const wave_ctx cx = wave_setup(smem, rank_tab, step_tab);
+    const wave_ctx cx = wave_setup<NC>(smem, rank_tab, step_tab);
     const int lane = cx.lane, wave = threadIdx.x >> 6;
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
-    const size_t nquads = (P + CANDS - 1) / CANDS;
+    const size_t nquads = (P + NC - 1) / NC;
     for (size_t quad = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; quad < nquads; quad += nwaves) {
-        // ---- a1: four candidate rows; position = lane: stage = lane / 8, slot = lane % 8 ----
-        int dev[CANDS];
+        // ---- a1: NC candidate rows; position = lane: stage = lane / 8, slot = lane % 8 ----
+        int dev[CANDS] = {0, 0, 0, 0};
 #pragma unroll
-        for (int c = 0; c < CANDS; c++) {
-            size_t cand = quad * CANDS + c;
+        for (int c = 0; c < NC; c++) {
+            size_t cand = quad * NC + c;
             if (cand >= P) cand = P - 1;   // ragged tail: recompute the last row, never stored
             dev[c] = perm[cand * NDEV + lane];
             cx.wl[OFF_PB + c * 64 + lane] = (unsigned char)dev[c];
         }
         WAVE_LDS_SYNC();
         double total[CANDS], datap[CANDS];
-        eval_quad(cx, W_dp, rank_val, dev, total, datap, ghat_out, quad * CANDS, P);
-        if (lane < CANDS) {
-            const size_t cand = quad * CANDS + lane;
+        eval_quad<NC>(cx, W_dp, rank_val, dev, total, datap, ghat_out, quad * NC, P);
+        if (lane < NC) {
+            const size_t cand = quad * NC + lane;
             const double t = lane == 0 ? total[0] : lane == 1 ? total[1] : lane == 2 ? total[2] : total[3];
             const double d = lane == 0 ? datap[0] : lane == 1 ? datap[1] : lane == 2 ? datap[2] : datap[3];
             if (cand < P) {
@@ -381,6 +386,7 @@ __device__ __forceinline__ void pair8_decode(int e, int &i, int &k)
     k = a + 1 + e;
 }
 
+template <int NC>
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
 k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_pp,
                   const uint16_t *__restrict__ rank_tab, const double *__restrict__ rank_val,
@@ -388,25 +394,25 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
                   double *__restrict__ cost, int64_t *__restrict__ applied)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const wave_ctx cx = wave_setup(smem, rank_tab, step_tab);
+    const wave_ctx cx = wave_setup<NC>(smem, rank_tab, step_tab);
     const int lane = cx.lane, wave = threadIdx.x >> 6;
     unsigned char *wl = cx.wl;
-    const int grp = lane >> 4, sub = lane & 15;   // proposal role: 16 lanes per candidate
+    const int grp = (lane >> 4) % NC, sub = lane & 15;   // proposal role: 16 lanes per candidate
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
-    const size_t nquads = (P + CANDS - 1) / CANDS;
+    const size_t nquads = (P + NC - 1) / NC;
     for (size_t quad = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; quad < nquads; quad += nwaves) {
-        int cur[CANDS];          // current allocation: device at position `lane`
+        int cur[CANDS] = {0, 0, 0, 0};   // current allocation: device at position `lane`
         double cur_cost[CANDS], unused[CANDS];
 #pragma unroll
-        for (int c = 0; c < CANDS; c++) {
-            size_t cand = quad * CANDS + c;
+        for (int c = 0; c < NC; c++) {
+            size_t cand = quad * NC + c;
             if (cand >= P) cand = P - 1;
             cur[c] = perm[cand * NDEV + lane];
             wl[OFF_PB + c * 64 + lane] = (unsigned char)cur[c];
             wl[OFF_PBCUR + c * 64 + lane] = (unsigned char)cur[c];
         }
         WAVE_LDS_SYNC();
-        eval_quad(cx, W_dp, rank_val, cur, cur_cost, unused, nullptr, quad * CANDS, P);
+        eval_quad<NC>(cx, W_dp, rank_val, cur, cur_cost, unused, nullptr, quad * NC, P);
 #pragma nounroll
         for (int r = 0; r < moves; r++) {
             // ---- proposal for candidate `grp` by its 16 lanes ----
@@ -477,9 +483,9 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
             }
             const int pa = Cj + slot[0][bk >> 1], pb_ = Cjp + slot[1][bk & 1];   // positions, pa < pb_
             // ---- trial rows: every lane needs each candidate's swap ----
-            int trial[CANDS], ta[CANDS], tb[CANDS];
+            int trial[CANDS] = {0, 0, 0, 0}, ta[CANDS], tb[CANDS];
 #pragma unroll
-            for (int c = 0; c < CANDS; c++) {
+            for (int c = 0; c < NC; c++) {
                 ta[c] = __shfl(pa, c * 16);
                 tb[c] = __shfl(pb_, c * 16);
                 const int src = lane == ta[c] ? tb[c] : (lane == tb[c] ? ta[c] : lane);
@@ -487,20 +493,20 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
             }
             WAVE_LDS_SYNC();
 #pragma unroll
-            for (int c = 0; c < CANDS; c++) wl[OFF_PB + c * 64 + lane] = (unsigned char)trial[c];
+            for (int c = 0; c < NC; c++) wl[OFF_PB + c * 64 + lane] = (unsigned char)trial[c];
             WAVE_LDS_SYNC();
             double tcost[CANDS];
-            eval_quad(cx, W_dp, rank_val, trial, tcost, unused, nullptr, quad * CANDS, P);
+            eval_quad<NC>(cx, W_dp, rank_val, trial, tcost, unused, nullptr, quad * NC, P);
             // ---- accept iff strictly cheaper ----
 #pragma unroll
-            for (int c = 0; c < CANDS; c++) {
+            for (int c = 0; c < NC; c++) {
                 const bool take = tcost[c] < cur_cost[c];   // wave-uniform
                 if (take) {
                     cur[c] = trial[c];
                     cur_cost[c] = tcost[c];
                     wl[OFF_PBCUR + c * 64 + lane] = (unsigned char)trial[c];
                 }
-                const size_t cand = quad * CANDS + c;
+                const size_t cand = quad * NC + c;
                 if (applied != nullptr && lane == 0 && cand < P)
                     applied[cand * (size_t)moves + r] =
                         take ? (long long)ta[c] * NDEV - (long long)ta[c] * (ta[c] + 1) / 2 + (tb[c] - ta[c] - 1) : -1ll;
@@ -508,8 +514,8 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
             WAVE_LDS_SYNC();
         }
 #pragma unroll
-        for (int c = 0; c < CANDS; c++) {
-            const size_t cand = quad * CANDS + c;
+        for (int c = 0; c < NC; c++) {
+            const size_t cand = quad * NC + c;
             if (cand < P) {
                 perm[cand * NDEV + lane] = cur[c];
                 if (lane == 0) cost[cand] = cur_cost[c];
@@ -682,9 +688,13 @@ int dtfm_fast64_prepare(dtfm_problem *pr)
     const std::vector<uint32_t> &tab = hk_item_table();
     DTFM_HIP(hipMalloc((void **)&pr->f64_steps, tab.size() * sizeof(uint32_t)));
     DTFM_HIP(hipMemcpy(pr->f64_steps, tab.data(), tab.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
-    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64),
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64<4>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
-    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64),
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64<2>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<4>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<2>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
     hipDeviceProp_t prop;
     DTFM_HIP(hipGetDeviceProperties(&prop, pr->device));
@@ -700,15 +710,27 @@ void dtfm_fast64_release(dtfm_problem *pr)
     if (pr->f64_steps) (void)hipFree(pr->f64_steps);
 }
 
+// Four candidates per wavefront give the best throughput; when there are too few candidates to
+// give every wavefront slot of the chip a pass that way, two per wavefront halve the latency.
+static bool use_two(const dtfm_problem *pr, size_t rows)
+{
+    return (rows + 3) / 4 < 2 * (size_t)pr->f64_grid * WAVES_PER_BLOCK;
+}
+
 int dtfm_fast64_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows, double *cost, double *ghat,
                         double *datap, hipStream_t st)
 {
     if (rows == 0) return DTFM_OK;
-    size_t quads = (rows + CANDS - 1) / CANDS;
-    size_t blocks = (quads + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    const int nc = use_two(pr, rows) ? 2 : 4;
+    size_t passes = (rows + nc - 1) / nc;
+    size_t blocks = (passes + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    hipLaunchKernelGGL(k_eval_fast64, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
-                       pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, cost, ghat, datap);
+    if (nc == 2)
+        hipLaunchKernelGGL(k_eval_fast64<2>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
+                           pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, cost, ghat, datap);
+    else
+        hipLaunchKernelGGL(k_eval_fast64<4>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
+                           pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, cost, ghat, datap);
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
 }
@@ -717,11 +739,18 @@ int dtfm_fast64_ls_gain4_enqueue(const dtfm_problem *pr, int32_t *perm, size_t r
                                  int64_t *applied, hipStream_t st)
 {
     if (rows == 0) return DTFM_OK;
-    size_t quads = (rows + CANDS - 1) / CANDS;
-    size_t blocks = (quads + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    const int nc = use_two(pr, rows) ? 2 : 4;
+    size_t passes = (rows + nc - 1) / nc;
+    size_t blocks = (passes + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    hipLaunchKernelGGL(k_ls_gain4_fast64, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
-                       pr->W_pp, pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, moves, cost, applied);
+    if (nc == 2)
+        hipLaunchKernelGGL(k_ls_gain4_fast64<2>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st,
+                           pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, moves, cost,
+                           applied);
+    else
+        hipLaunchKernelGGL(k_ls_gain4_fast64<4>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st,
+                           pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, moves, cost,
+                           applied);
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
 }

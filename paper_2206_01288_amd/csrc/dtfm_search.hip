@@ -444,8 +444,12 @@ __global__ void k_rank_count(const double *__restrict__ cost, const double *__re
     if (i >= n) return;
     const double ci = i < P ? cost[i] : off_cost[i - P];
     const int jn = n - j0 < DTFM_RANK_CHUNK ? n - j0 : DTFM_RANK_CHUNK;
+    // keys beyond the end of the chunk are +inf and never precede anything, so the loop can run over
+    // the whole (fixed-size) chunk and be unrolled
+    (void)jn;
     int cnt = 0;
-    for (int t = 0; t < jn; t++) {
+#pragma unroll 16
+    for (int t = 0; t < DTFM_RANK_CHUNK; t++) {
         const double cj = s_key[t];
         cnt += (cj < ci || (cj == ci && j0 + t < i)) ? 1 : 0;
     }

@@ -59,6 +59,20 @@ def test_config2_full_population(name, P):
         assert np.all(c == c[0])
 
 
+def test_config2_large_population_four_candidates_per_wavefront():
+    # populations of 16384 and more take the four-candidates-per-wavefront variant of the fused kernel
+    w = workloads.config("C2")
+    o, g = both(w)
+    perms = workloads.random_population(20003, 64, seed=11)
+    dperm = dev(perms)
+    c = host(dtfm.eval_population(g, dperm))
+    assert_costs_equal(c, o.eval_population(perms))
+    ghat, datap = dtfm.coarsened_graph(g, dperm)
+    ghat, datap = host(ghat), host(datap)
+    for p in (0, 1, 2, 3, 9999, 20000, 20001, 20002):
+        assert np.array_equal(ghat[p], o.coarsen(perms[p])) and datap[p] == o.datap(perms[p])
+
+
 def test_config4_full_population_sampled():
     w = workloads.config("C4")
     o, g = both(w)

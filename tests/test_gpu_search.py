@@ -68,6 +68,21 @@ def test_gain4_config2():
     assert (applied >= 0).any()
 
 
+def test_gain4_large_population_four_candidates_per_wavefront():
+    w = workloads.config("C2")
+    o, g = both(w)
+    perms = workloads.random_population(16500, 64, seed=12)
+    d = dev(perms)
+    cost, applied = dtfm.local_search(g, d, 3, dtfm.GAIN4, want_applied=True)
+    sel = np.r_[0:40, 8000:8040, 16460:16500]
+    rp, rc, ra = o.local_search(perms[sel], 3, oracle.GAIN4)
+    assert np.array_equal(host(d)[sel], rp) and np.array_equal(host(applied)[sel], ra)
+    assert_costs_equal(host(cost)[sel], rc)
+    # every row: still a permutation, cost equals a fresh evaluation of the final row
+    assert dtfm.validate_population(g, d) == 0
+    assert torch.equal(dtfm.eval_population(g, d), cost)
+
+
 def test_gain4_paper_table_ties():
     w = workloads.config("C2b")
     _ls_parity(w, workloads.random_population(32, 64, seed=6), 30, dtfm.GAIN4)
