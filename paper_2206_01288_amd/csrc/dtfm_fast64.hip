@@ -69,10 +69,14 @@ constexpr int LDS_RANK_BYTES = ((NDEV * RSTRIDE * 2 + 15) / 16) * 16;   // 8.25 
 constexpr int LDS_HKTAB_BYTES = HK_TAB_WORDS4 * 64 * 16;           // 29 KiB
 constexpr int OFF_BUF0 = 0;                                        // double2 [320]: even layers
 constexpr int OFF_BUF1 = OFF_BUF0 + HK_BUF_ENTRIES * 16;           // double2 [320]: odd layers
-constexpr int OFF_GHAT = OFF_BUF1 + HK_BUF_ENTRIES * 16;           // double2 [2 candidate pairs][8][8]
-constexpr int OFF_PB = OFF_GHAT + 2 * 1024;                        // u8 [4 candidates][64] perm, stage-major
+// Coarsened graphs, one 2 KiB block per candidate pair: double2 [u][16]: column s of row u holds
+// ghat[u][s % 8] (both candidates), so a lane of pass-lane s whose item ends in v = s % 8 always reads
+// its own column: the 16 lanes of a 128-bit read pass never share a bank group.
+constexpr int GHAT_PAIR_BYTES = 8 * 16 * 16;
+constexpr int OFF_GHAT = OFF_BUF1 + HK_BUF_ENTRIES * 16;
+constexpr int OFF_PB = OFF_GHAT + 2 * GHAT_PAIR_BYTES;             // u8 [4 candidates][64] perm, stage-major
 constexpr int OFF_PBCUR = OFF_PB + CANDS * 64;                     // u8 [4][64]: current rows (local search)
-constexpr int WAVE_LDS_BYTES = OFF_PBCUR + CANDS * 64;             // 12800
+constexpr int WAVE_LDS_BYTES = OFF_PBCUR + CANDS * 64;             // 14848
 constexpr int WAVES_PER_BLOCK = 8;
 constexpr int LDS_TOTAL = LDS_RANK_BYTES + LDS_HKTAB_BYTES + WAVES_PER_BLOCK * WAVE_LDS_BYTES;
 
@@ -110,35 +114,41 @@ __device__ __forceinline__ double2 hk_layer(unsigned char *wl, const unsigned ch
                                             int lane)
 {
     constexpr int PREV = (K & 1) ? OFF_BUF0 : OFF_BUF1, CUR = (K & 1) ? OFF_BUF1 : OFF_BUF0;
-    double2 best = make_double2(INFINITY, INFINITY);
+    constexpr int STEPS = hk_steps(K), W4 = hk_words4(K);
+    // all item words of the layer first, then all reads and arithmetic, then all writes: with no
+    // store between the loads of different steps the compiler may overlap their LDS latencies
+    uint32_t word[STEPS][4 * W4];
 #pragma unroll
-    for (int s = 0; s < hk_steps(K); s++) {
-        uint32_t word[8];
+    for (int s = 0; s < STEPS; s++)
 #pragma unroll
-        for (int i = 0; i < hk_words4(K); i++) {
+        for (int i = 0; i < W4; i++) {
             // volatile: keep this one dense 128-bit read per lane (the compiler would otherwise narrow
             // it to the words actually used, which at a 16-byte lane stride conflicts heavily)
-            const u32x4 t = *(const volatile lds_u32x4 *)(
-                hktab + ((hk_tab_first(K) + s * hk_words4(K) + i) * 64 + lane) * 16);
-            word[4 * i + 0] = t.x;
-            word[4 * i + 1] = t.y;
-            word[4 * i + 2] = t.z;
-            word[4 * i + 3] = t.w;
+            const u32x4 t = *(const volatile lds_u32x4 *)(hktab + ((hk_tab_first(K) + s * W4 + i) * 64 + lane) * 16);
+            word[s][4 * i + 0] = t.x;
+            word[s][4 * i + 1] = t.y;
+            word[s][4 * i + 2] = t.z;
+            word[s][4 * i + 3] = t.w;
         }
-        best = make_double2(INFINITY, INFINITY);
+    double2 best[STEPS];
+#pragma unroll
+    for (int s = 0; s < STEPS; s++) {
+        best[s] = make_double2(INFINITY, INFINITY);
 #pragma unroll
         for (int t = 1; t < K; t++) {
-            const double2 x = *reinterpret_cast<const double2 *>(wl + PREV + (word[t] & 0xFFFFu));
-            const double2 e = *reinterpret_cast<const double2 *>(wl + ghat_off + (word[t] >> 16));
-            best.x = fmin(best.x, __dadd_rn(x.x, e.x));
-            best.y = fmin(best.y, __dadd_rn(x.y, e.y));
+            const double2 x = *reinterpret_cast<const double2 *>(wl + PREV + (word[s][t] & 0xFFFFu));
+            const double2 e = *reinterpret_cast<const double2 *>(wl + ghat_off + (word[s][t] >> 16));
+            best[s].x = fmin(best[s].x, __dadd_rn(x.x, e.x));
+            best[s].y = fmin(best[s].y, __dadd_rn(x.y, e.y));
         }
-        if (word[0] >> 31) *reinterpret_cast<double2 *>(wl + CUR + (word[0] & 0xFFFFu)) = best;
-        else best = make_double2(INFINITY, INFINITY);
-        __builtin_amdgcn_sched_barrier(0);   // keep one step's loads in flight, not the whole layer's
+    }
+#pragma unroll
+    for (int s = 0; s < STEPS; s++) {
+        if (word[s][0] >> 31) *reinterpret_cast<double2 *>(wl + CUR + (word[s][0] & 0xFFFFu)) = best[s];
+        else best[s] = make_double2(INFINITY, INFINITY);
     }
     WAVE_LDS_SYNC();
-    return best;
+    return best[STEPS - 1];
 }
 
 // byte k (0..7) of a 64-bit value held as two dwords
@@ -173,10 +183,10 @@ __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16
     // Held-Karp item table -> LDS
     for (int i = threadIdx.x; i < LDS_HKTAB_BYTES / 16; i += blockDim.x)
         reinterpret_cast<uint4 *>(smem + LDS_RANK_BYTES)[i] = reinterpret_cast<const uint4 *>(step_tab)[i];
-    // zero diagonals of the four coarsened graphs (never overwritten): entry [pair][j][j][cand & 1]
+    // zero diagonals of the four coarsened graphs (never overwritten): [pair][j][column j][cand & 1]
     if (cx.lane < CANDS * 8)
-        *reinterpret_cast<double *>(cx.wl + OFF_GHAT + (cx.lane >> 4) * 1024 + (cx.lane & 7) * 9 * 16 +
-                                    ((cx.lane >> 3) & 1) * 8) = 0.0;
+        *reinterpret_cast<double *>(cx.wl + OFF_GHAT + (cx.lane >> 4) * GHAT_PAIR_BYTES +
+                                    ((cx.lane & 7) * 16 + (cx.lane & 7)) * 16 + ((cx.lane >> 3) & 1) * 8) = 0.0;
     // matching role: candidate slot and the couple of stage pairs (2q, 2q+1) in lexicographic order
     // (with NC = 2 the upper half of the wavefront repeats the lower half's work and writes nothing)
     cx.mc = (cx.lane >> 4) % NC;
@@ -265,12 +275,17 @@ __device__ __forceinline__ void eval_quad(const wave_ctx &cx, const double *__re
     // ---- winning ranks -> fp64 weights -> coarsened graphs in LDS ----
     {
         const double e0 = rank_val[gfull & 0xFFFFu], e1 = rank_val[gfull >> 16];
-        if (cx.couple_valid) {   // entry [candidate pair][u][v][candidate & 1]
-            double *gh = reinterpret_cast<double *>(wl + OFF_GHAT + (cx.mc >> 1) * 1024) + (cx.mc & 1);
-            gh[(cx.j1[0] * 8 + cx.j2[0]) * 2] = e0;
-            gh[(cx.j2[0] * 8 + cx.j1[0]) * 2] = e0;
-            gh[(cx.j1[1] * 8 + cx.j2[1]) * 2] = e1;
-            gh[(cx.j2[1] * 8 + cx.j1[1]) * 2] = e1;
+        if (cx.couple_valid) {   // entries [candidate pair][u][columns v and v + 8][candidate & 1]
+            double *gh = reinterpret_cast<double *>(wl + OFF_GHAT + (cx.mc >> 1) * GHAT_PAIR_BYTES) + (cx.mc & 1);
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const double e = h == 0 ? e0 : e1;
+                const int a = cx.j1[h], b = cx.j2[h];
+                gh[(a * 16 + b) * 2] = e;
+                gh[(a * 16 + b + 8) * 2] = e;
+                gh[(b * 16 + a) * 2] = e;
+                gh[(b * 16 + a + 8) * 2] = e;
+            }
         }
     }
     WAVE_LDS_SYNC();
@@ -288,14 +303,14 @@ __device__ __forceinline__ void eval_quad(const wave_ctx &cx, const double *__re
 #pragma unroll
             for (int k = 0; k < 8; k++) wv[h][k] = wrow[byte_of(mates, k)];   // own slot: the zero diagonal
         }
-        const uint32_t ghat_off = OFF_GHAT + pr * 1024;
+        const uint32_t ghat_off = OFF_GHAT + pr * GHAT_PAIR_BYTES;
         if (ghat_out != nullptr) {
-            const double2 g2 = *reinterpret_cast<const double2 *>(wl + ghat_off + lane * 16);
+            const double2 g2 = *reinterpret_cast<const double2 *>(wl + ghat_off + ((lane >> 3) * 16 + (lane & 7)) * 16);
             if (cand0 + 2 * pr < P) ghat_out[(cand0 + 2 * pr) * 64 + lane] = g2.x;
             if (cand0 + 2 * pr + 1 < P) ghat_out[(cand0 + 2 * pr + 1) * 64 + lane] = g2.y;
         }
-        // layer 1: tab[{v}][v] = 0 at entry v of the odd buffer
-        if (lane < 8) *reinterpret_cast<double2 *>(wl + OFF_BUF1 + lane * 16) = make_double2(0.0, 0.0);
+        // layer 1: tab[{v}][v] = 0, kept twice (entries v and v + 8 of the odd buffer)
+        if (lane < 16) *reinterpret_cast<double2 *>(wl + OFF_BUF1 + lane * 16) = make_double2(0.0, 0.0);
         WAVE_LDS_SYNC();
         hk_layer<2>(wl, cx.hktab, ghat_off, lane);
         hk_layer<3>(wl, cx.hktab, ghat_off, lane);
@@ -548,38 +563,30 @@ __global__ void k_rank_weights(const double *__restrict__ W_pp, int N, uint16_t 
 }
 
 // ---- Held-Karp item table (problem independent, built once per process) ------------------------
-// Layer k has C(8,k) k items (S, v). Each is given a (step, lane) position; its entry lives at
-// index step*64 + lane of the layer's buffer, so writes are dense. The free choices - which item
-// sits at which position and in which order it visits its predecessors - are settled by a
-// deterministic local search that minimises LDS bank conflicts of the two 128-bit reads per
-// transition: a 128-bit read is served 16 lanes at a time, and within such a group two lanes that
-// read different entries with equal (index % 16) cost an extra cycle.
-struct hk_item {
-    uint8_t S, v, ord[7];
-    bool valid;
+// A 128-bit LDS read is served 16 lanes at a time and is fastest when those 16 lanes hit 16 different
+// bank groups (address / 16 mod 16) - lanes that share an address are only free when adjacent. The
+// items are therefore laid out by a cyclic structure that makes this true by construction:
+//  * item (S, v) with S = v + ({0} u D) (mod 8) belongs to class D, a (k-1)-subset of {1..7}; the 8
+//    items of a class are the rotations v = 0..7 and occupy 8 consecutive lanes (lane % 8 = v);
+//  * a pass of 16 lanes holds two classes (halves h = 0, 1); the item's entry index in its layer's
+//    buffer is pass*16 + h*8 + v, so writes are dense and an entry's bank group is h*8 + v;
+//  * every class visits its predecessors in an order (d_1 .. d_{k-1}) of D: at step t all 8 lanes read
+//    u = v + d_t, i.e. the 8 rotations of ONE source class D' = (D \ d_t) - d_t of the previous layer:
+//    8 different bank groups, all in the half h(D') where that class was placed;
+//  * the read of a pass is conflict free when its two classes read from opposite halves; class
+//    placement and visiting orders are chosen by a small deterministic search to make that so;
+//  * ghat[u][v] is read from the lane's own column (see GHAT_PAIR_BYTES): never a conflict.
+struct hk_class {
+    uint8_t D;        // difference set as a bit mask over {1..7} (bit d set = d in D)
+    uint8_t ord[7];   // visiting order of D's elements
 };
 
-int hk_group_cost(const hk_item *it, int k, const int (*prev_idx)[8])
+inline uint8_t hk_source_class(uint8_t D, int d)   // (D \ d) - d (mod 8), as a mask over {1..7}
 {
-    int total = 0;
-    for (int t = 0; t < k - 1; t++) {
-        int cnt_a[16] = {0}, cnt_g[16] = {0}, worst_a = 0, worst_g = 0;
-        bool seen_a[HK_BUF_ENTRIES] = {false}, seen_g[64] = {false};
-        for (int i = 0; i < 16; i++) {
-            if (!it[i].valid) continue;
-            int u = it[i].ord[t], a = prev_idx[it[i].S ^ (1 << it[i].v)][u], g = u * 8 + it[i].v;
-            if (!seen_a[a]) {
-                seen_a[a] = true;
-                if (++cnt_a[a & 15] > worst_a) worst_a = cnt_a[a & 15];
-            }
-            if (!seen_g[g]) {
-                seen_g[g] = true;
-                if (++cnt_g[g & 15] > worst_g) worst_g = cnt_g[g & 15];
-            }
-        }
-        total += worst_a + worst_g;
-    }
-    return total;
+    uint8_t out = 0;
+    for (int e = 1; e < 8; e++)
+        if (e != d && (D & (1 << e))) out |= (uint8_t)(1 << ((e - d + 8) & 7));
+    return out;
 }
 
 const std::vector<uint32_t> &hk_item_table()
@@ -588,83 +595,106 @@ const std::vector<uint32_t> &hk_item_table()
     static std::once_flag once;
     std::call_once(once, [] {
         tab.assign((size_t)HK_TAB_WORDS4 * 64 * 4, 0u);
-        static int idx[2][256][8];   // entry index of (S, v) in its layer's buffer, by layer parity
-        for (int v = 0; v < 8; v++) idx[1][1 << v][v] = v;   // layer 1
+        // half[D] (0/1) and pass[D] of every class of the previous layer, indexed by mask; -1: none
+        int prev_half[256], prev_pass[256], cur_half[256], cur_pass[256];
+        for (int i = 0; i < 256; i++) prev_half[i] = prev_pass[i] = -1;
         uint64_t rng = 0x2545F4914F6CDD1Dull;
         auto next = [&rng](uint32_t n) {
             rng = rng * 6364136223846793005ull + 1442695040888963407ull;
             return (uint32_t)((rng >> 33) % n);
         };
         for (int k = 2; k <= 8; k++) {
-            const int (*prev_idx)[8] = idx[(k - 1) & 1];
-            const int npos = hk_steps(k) * 64, ngrp = npos / 16;
-            std::vector<hk_item> pos(npos, hk_item{});
-            int n = 0;
-            for (int S = 1; S < 256; S++)
-                if (__builtin_popcount(S) == k)
-                    for (int v = 0; v < 8; v++)
-                        if (S & (1 << v)) {
-                            hk_item &m = pos[n++];
-                            m.S = (uint8_t)S;
-                            m.v = (uint8_t)v;
-                            m.valid = true;
-                            int t = 0;
-                            for (int u = 0; u < 8; u++)
-                                if (u != v && (S & (1 << u))) m.ord[t++] = (uint8_t)u;
-                        }
-            // layer 8 keeps its 8 items in lanes 0..7 (the kernel reduces over them)
-            if (k < 8) {
-                // spread the items over all 16-lane groups before searching
-                std::vector<hk_item> spread(npos, hk_item{});
-                for (int i = 0; i < n; i++) spread[(i % ngrp) * 16 + (i / ngrp)] = pos[i];
-                if (n <= ngrp * 16 && (n + ngrp - 1) / ngrp <= 16) pos = spread;
-            }
-            std::vector<int> cost(ngrp);
-            for (int g = 0; g < ngrp; g++) cost[g] = hk_group_cost(&pos[g * 16], k, prev_idx);
-            const int iters = k < 8 ? 40000 : 2000;
-            for (int it = 0; it < iters; it++) {
-                const bool allow_worse = it < iters / 2 && next(16) == 0;
-                int p = (int)next(npos);
-                if (next(2) == 0 || k == 8) {
-                    hk_item &m = pos[p];
-                    if (!m.valid || k < 3) continue;
-                    int a = (int)next(k - 1), b = (int)next(k - 1);
-                    if (a == b) continue;
-                    std::swap(m.ord[a], m.ord[b]);
-                    int c = hk_group_cost(&pos[(p / 16) * 16], k, prev_idx);
-                    if (c <= cost[p / 16] || (allow_worse && c == cost[p / 16] + 1)) cost[p / 16] = c;
-                    else std::swap(m.ord[a], m.ord[b]);
-                } else {
-                    int q = (int)next(npos);
-                    if (p / 16 == q / 16) continue;
-                    std::swap(pos[p], pos[q]);
-                    int cp = hk_group_cost(&pos[(p / 16) * 16], k, prev_idx);
-                    int cq = hk_group_cost(&pos[(q / 16) * 16], k, prev_idx);
-                    int d = cp + cq - cost[p / 16] - cost[q / 16];
-                    if (d <= 0 || (allow_worse && d == 1)) {
-                        cost[p / 16] = cp;
-                        cost[q / 16] = cq;
+            std::vector<hk_class> cls;
+            for (int D = 0; D < 256; D += 2)
+                if (__builtin_popcount(D) == k - 1) {
+                    hk_class c = {};
+                    c.D = (uint8_t)D;
+                    int t = 0;
+                    for (int d = 1; d < 8; d++)
+                        if (D & (1 << d)) c.ord[t++] = (uint8_t)d;
+                    cls.push_back(c);
+                }
+            const int nc = (int)cls.size(), np = (nc + 1) / 2;
+            // position i of `cls` = (pass i / 2, half i % 2). Cost: number of (pass, step) whose two
+            // classes read from the same half of the previous layer (layer 1 is kept in both halves).
+            auto pass_cost = [&](int p) {
+                if (2 * p + 1 >= nc || k == 2) return 0;
+                int c = 0;
+                for (int t = 0; t < k - 1; t++) {
+                    int ha = prev_half[hk_source_class(cls[2 * p].D, cls[2 * p].ord[t])];
+                    int hb = prev_half[hk_source_class(cls[2 * p + 1].D, cls[2 * p + 1].ord[t])];
+                    c += ha == hb;
+                }
+                return c;
+            };
+            std::vector<int> cost(np);
+            int total = 0;
+            for (int p = 0; p < np; p++) total += cost[p] = pass_cost(p);
+            for (int it = 0; it < 60000 && total > 0; it++) {
+                int a = (int)next(nc);
+                if (next(2) == 0 && k > 2) {
+                    int x = (int)next(k - 1), y = (int)next(k - 1);
+                    if (x == y) continue;
+                    std::swap(cls[a].ord[x], cls[a].ord[y]);
+                    int c = pass_cost(a / 2);
+                    if (c <= cost[a / 2]) {
+                        total += c - cost[a / 2];
+                        cost[a / 2] = c;
                     } else
-                        std::swap(pos[p], pos[q]);
+                        std::swap(cls[a].ord[x], cls[a].ord[y]);
+                } else {
+                    int b = (int)next(nc);
+                    if (a / 2 == b / 2) continue;
+                    std::swap(cls[a], cls[b]);
+                    int ca = pass_cost(a / 2), cb = pass_cost(b / 2);
+                    if (ca + cb <= cost[a / 2] + cost[b / 2]) {
+                        total += ca + cb - cost[a / 2] - cost[b / 2];
+                        cost[a / 2] = ca;
+                        cost[b / 2] = cb;
+                    } else
+                        std::swap(cls[a], cls[b]);
                 }
             }
-            // emit the layer's table words and record where its entries live
-            for (int s = 0; s < hk_steps(k); s++)
-                for (int lane = 0; lane < 64; lane++) {
-                    const hk_item &m = pos[s * 64 + lane];
-                    if (!m.valid) continue;
-                    idx[k & 1][m.S][m.v] = s * 64 + lane;
+            for (int i = 0; i < 256; i++) cur_half[i] = cur_pass[i] = -1;
+            for (int i = 0; i < nc; i++) {
+                cur_pass[cls[i].D] = i / 2;
+                cur_half[cls[i].D] = i % 2;
+            }
+            // emit: item (S, v) of class i sits at step (i/2)/4, lane ((i/2)%4)*16 + (i%2)*8 + v
+            for (int i = 0; i < nc; i++)
+                for (int v = 0; v < 8; v++) {
+                    const int pass = i / 2, half = i % 2, s = pass / 4, lane = (pass % 4) * 16 + half * 8 + v;
                     uint32_t word[8] = {0};
-                    word[0] = (uint32_t)((s * 64 + lane) * 16) | 0x80000000u;
+                    word[0] = (uint32_t)((pass * 16 + half * 8 + v) * 16) | 0x80000000u;
                     for (int t = 0; t < k - 1; t++) {
-                        int u = m.ord[t];
-                        word[1 + t] = (uint32_t)(prev_idx[m.S ^ (1 << m.v)][u] * 16) | ((uint32_t)((u * 8 + m.v) * 16) << 16);
+                        const int d = cls[i].ord[t], u = (v + d) & 7;
+                        int src;   // entry index of (S \ v, u) in the previous layer's buffer
+                        if (k == 2)
+                            src = half * 8 + u;   // layer 1 is stored in both halves
+                        else {
+                            const uint8_t Ds = hk_source_class(cls[i].D, d);
+                            src = prev_pass[Ds] * 16 + prev_half[Ds] * 8 + u;
+                        }
+                        word[1 + t] = (uint32_t)(src * 16) | ((uint32_t)((u * 16 + half * 8 + v) * 16) << 16);
                     }
                     for (int w = 0; w < hk_words4(k) * 4; w++) {
                         size_t word4 = (size_t)hk_tab_first(k) + (size_t)s * hk_words4(k) + w / 4;
                         tab[(word4 * 64 + lane) * 4 + w % 4] = word[w];
                     }
                 }
+            // lanes without an item still execute the reads: point them at their own bank group
+            for (int s = 0; s < hk_steps(k); s++)
+                for (int lane = 0; lane < 64; lane++) {
+                    size_t word4 = (size_t)hk_tab_first(k) + (size_t)s * hk_words4(k);
+                    if (tab[(word4 * 64 + lane) * 4] >> 31) continue;
+                    for (int w = 1; w < hk_words4(k) * 4; w++)
+                        tab[((word4 + w / 4) * 64 + lane) * 4 + w % 4] =
+                            (uint32_t)((lane & 15) * 16) | ((uint32_t)((lane & 15) * 16) << 16);
+                }
+            for (int i = 0; i < 256; i++) {
+                prev_half[i] = cur_half[i];
+                prev_pass[i] = cur_pass[i];
+            }
         }
     });
     return tab;
