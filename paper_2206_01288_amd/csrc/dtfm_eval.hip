@@ -208,6 +208,91 @@ __global__ void k_held_karp(const double *__restrict__ ghat, const double *__res
     }
 }
 
+// a5/a6 for D_pp above the LDS limit: the table [S][16] lives in HBM and is walked source-side.
+// tab[T][v] depends only on the row of S = T \ v: tab[T][v] = min_{u in S} fl(tab[S][u] + Ghat[u][v]).
+// So a group of 16 lanes takes one source set S, reads its row (128 contiguous bytes; lane u holds
+// tab[S][u], or +inf when u is not in S), rotates the row through the group with DPP so that every
+// lane v meets every u, keeps min_u (tab[S][u] + Ghat[u][v]) and, for v not in S, stores it as
+// tab[S + v][v]: every entry is written exactly once and every row is read exactly once, layer by
+// layer (workgroup barrier between layers). Per candidate 8 MiB of rows are read and 4 MiB of
+// entries written, instead of one 8-byte read per relaxation.
+template <int R>
+__device__ __forceinline__ int dpp_ror_i32(int x)
+{
+    return __builtin_amdgcn_update_dpp(0, x, 0x120 + R, 0xf, 0xf, false);   // row_ror:R within 16 lanes
+}
+template <int R>
+__device__ __forceinline__ double dpp_ror_f64(double x)
+{
+    union {
+        double d;
+        int i[2];
+    } a, b;
+    a.d = x;
+    b.i[0] = dpp_ror_i32<R>(a.i[0]);
+    b.i[1] = dpp_ror_i32<R>(a.i[1]);
+    return b.d;
+}
+
+template <int R>
+struct hk_push_rot {
+    // Gc[R-1] = Ghat[u][v] for the lane u that rotation R brings to lane v
+    static __device__ __forceinline__ void setup(const double *G, int v, double *Gc)
+    {
+        const int u = dpp_ror_i32<R>(v);
+        Gc[R - 1] = G[u * 16 + v];
+        hk_push_rot<R - 1>::setup(G, v, Gc);
+    }
+    static __device__ __forceinline__ double relax(double x, const double *Gc, double y)
+    {
+        y = hk_push_rot<R - 1>::relax(x, Gc, y);
+        return fmin(y, __dadd_rn(dpp_ror_f64<R>(x), Gc[R - 1]));
+    }
+};
+template <>
+struct hk_push_rot<0> {
+    static __device__ __forceinline__ void setup(const double *, int, double *) {}
+    static __device__ __forceinline__ double relax(double, const double *, double y) { return y; }
+};
+
+__global__ void __launch_bounds__(1024)
+k_held_karp_push(const double *__restrict__ ghat, const double *__restrict__ datap, int n,
+                 const uint32_t *__restrict__ subsets, dtfm_layer_off lo, double *__restrict__ tab_global,
+                 double *__restrict__ cost, size_t P)
+{
+    __shared__ double G[16 * 16];
+    double *tab = tab_global + (size_t)blockIdx.x * ((size_t)16 << n);
+    const int v = threadIdx.x & 15, grp = threadIdx.x >> 4, ngrp = blockDim.x >> 4;
+    const uint32_t full = (1u << n) - 1u;
+    for (size_t p = blockIdx.x; p < P; p += gridDim.x) {
+        for (int e = threadIdx.x; e < 256; e += blockDim.x) {
+            const int a = e >> 4, b = e & 15;
+            G[e] = (a < n && b < n) ? ghat[p * n * n + a * n + b] : INFINITY;
+        }
+        if ((int)threadIdx.x < n) tab[((size_t)1 << threadIdx.x) * 16 + threadIdx.x] = 0.0;
+        __syncthreads();
+        double Gc[15];
+        hk_push_rot<15>::setup(G, v, Gc);
+        for (int k = 1; k < n; k++) {
+            const int first = lo.off[k], cnt = lo.off[k + 1] - first;
+            for (int i = grp; i < cnt; i += ngrp) {
+                const uint32_t S = subsets[first + i];
+                const bool in = (S >> v) & 1u;
+                const double x = in ? tab[(size_t)S * 16 + v] : INFINITY;
+                const double y = hk_push_rot<15>::relax(x, Gc, INFINITY);
+                if (!in && v < n) tab[(size_t)(S | (1u << v)) * 16 + v] = y;
+            }
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            double m = INFINITY;
+            for (int u = 0; u < n; u++) m = fmin(m, tab[(size_t)full * 16 + u]);
+            cost[p] = __dadd_rn(datap[p], m);
+        }
+        __syncthreads();
+    }
+}
+
 dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows)
 {
     dtfm_eval_bufs b;
@@ -217,7 +302,7 @@ dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t ro
     b.hk_tab = nullptr;
     if (pr->D_pp > DTFM_HK_LDS_MAX_DPP) {
         size_t grid = rows < DTFM_HK_GLOBAL_GRID ? rows : DTFM_HK_GLOBAL_GRID;
-        b.hk_tab = ar.take<double>(grid * (n << n));
+        b.hk_tab = ar.take<double>(grid * ((size_t)16 << n));
     }
     return b;
 }
@@ -254,8 +339,8 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
                            pr->hk_subsets, pr->hk_off, (double *)nullptr, cost, rows);
     } else {
         size_t grid = rows < DTFM_HK_GLOBAL_GRID ? rows : DTFM_HK_GLOBAL_GRID;
-        hipLaunchKernelGGL(k_held_karp<false>, dim3((unsigned)grid), dim3(1024), (size_t)n * n * sizeof(double),
-                           st, b.ghat, b.datap, n, pr->hk_subsets, pr->hk_off, b.hk_tab, cost, rows);
+        hipLaunchKernelGGL(k_held_karp_push, dim3((unsigned)grid), dim3(1024), 0, st, b.ghat, b.datap, n,
+                           pr->hk_subsets, pr->hk_off, b.hk_tab, cost, rows);
     }
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
