@@ -428,30 +428,22 @@ __global__ void k_make_offspring(uint32_t k0, uint32_t k1, uint32_t g, const int
 // under the order (cost, origin); the P lowest survive, placed at their rank. The count over the
 // P+L keys is split: block (x, y) counts, for 256 elements i, the keys of chunk y (staged in LDS)
 // that precede them, and adds the partial count to rank[i].
-#define DTFM_RANK_CHUNK 1024
+#define DTFM_RANK_CHUNK 256
 __global__ void k_rank_count(const double *__restrict__ cost, const double *__restrict__ off_cost, int P, int L,
                              int32_t *__restrict__ rank)
 {
-    __shared__ double s_key[DTFM_RANK_CHUNK];
     const int n = P + L;
     const int j0 = blockIdx.y * DTFM_RANK_CHUNK;
-    for (int t = threadIdx.x; t < DTFM_RANK_CHUNK; t += blockDim.x) {
-        int j = j0 + t;
-        s_key[t] = j < P ? cost[j] : (j < n ? off_cost[j - P] : INFINITY);
-    }
-    __syncthreads();
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const double ci = i < P ? cost[i] : off_cost[i - P];
-    const int jn = n - j0 < DTFM_RANK_CHUNK ? n - j0 : DTFM_RANK_CHUNK;
-    // keys beyond the end of the chunk are +inf and never precede anything, so the loop can run over
-    // the whole (fixed-size) chunk and be unrolled
-    (void)jn;
+    const int j1 = j0 + DTFM_RANK_CHUNK < n ? j0 + DTFM_RANK_CHUNK : n;
     int cnt = 0;
-#pragma unroll 16
-    for (int t = 0; t < DTFM_RANK_CHUNK; t++) {
-        const double cj = s_key[t];
-        cnt += (cj < ci || (cj == ci && j0 + t < i)) ? 1 : 0;
+    // the key index j is the same for every lane: the keys come through the scalar cache
+#pragma unroll 8
+    for (int j = j0; j < j1; j++) {
+        const double cj = j < P ? cost[j] : off_cost[j - P];
+        cnt += (cj < ci || (cj == ci && j < i)) ? 1 : 0;
     }
     if (cnt) atomicAdd(&rank[i], cnt);
 }
