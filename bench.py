@@ -46,9 +46,9 @@ import workloads  # noqa: E402
 # (fp64 add/min/max issue at full rate), twice that for packed 16-bit ops.
 VALU_LANE_OPS_PER_S = 256 * 4 * 16 * 2.4e9
 # HBM bytes per candidate of the evaluation kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/k_eval_fast64_C2_P1048576.md (269.7 MB + 8.4 MB per 1,048,576 candidates,
+# summarised in profiles/k_eval_fast64_C2_P1048576.md (271.8 MB + 10.5 MB per 1,048,576 candidates,
 # each counter scaled by its reading for a 1 GiB device copy). Algorithmic: 4N + 8 = 264 B.
-MEASURED_HBM_BYTES_PER_CANDIDATE = 265.2
+MEASURED_HBM_BYTES_PER_CANDIDATE = 269.2
 
 
 def algorithmic_ops(N, D_dp, D_pp):
