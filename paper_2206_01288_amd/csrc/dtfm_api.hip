@@ -125,12 +125,27 @@ extern "C" int dtfm_create_problem(const double *latency, const double *bandwidt
     lat_dev = nullptr;
     CREATE_HIP(hipFree(bw_dev));
     bw_dev = nullptr;
-#undef CREATE_HIP
     if (dtfm_fast64_applicable(pr)) {
         rc = dtfm_fast64_prepare(pr);
         if (rc != DTFM_OK) return fail(rc);
         pr->fast64 = true;
+    } else {
+        // dense ranks of the pipeline weights for the matching kernel: the device-computed W_pp
+        // is read back, sorted and deduplicated once (cold path)
+        std::vector<double> w((size_t)N * N), vals;
+        CREATE_HIP(hipMemcpy(w.data(), pr->W_pp, mat, hipMemcpyDeviceToHost));
+        vals = w;
+        std::sort(vals.begin(), vals.end());
+        vals.erase(std::unique(vals.begin(), vals.end()), vals.end());
+        std::vector<uint32_t> rk(w.size());
+        for (size_t i = 0; i < w.size(); i++)
+            rk[i] = (uint32_t)(std::lower_bound(vals.begin(), vals.end(), w[i]) - vals.begin());
+        CREATE_HIP(hipMalloc((void **)&pr->W_rank, rk.size() * sizeof(uint32_t)));
+        CREATE_HIP(hipMalloc((void **)&pr->rank_val, vals.size() * sizeof(double)));
+        CREATE_HIP(hipMemcpy(pr->W_rank, rk.data(), rk.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+        CREATE_HIP(hipMemcpy(pr->rank_val, vals.data(), vals.size() * sizeof(double), hipMemcpyHostToDevice));
     }
+#undef CREATE_HIP
     *out = pr;
     return DTFM_OK;
 }
@@ -142,6 +157,8 @@ extern "C" void dtfm_destroy_problem(dtfm_problem *pr)
     if (pr->W_dp) (void)hipFree(pr->W_dp);
     if (pr->W_pp) (void)hipFree(pr->W_pp);
     if (pr->hk_subsets) (void)hipFree(pr->hk_subsets);
+    if (pr->W_rank) (void)hipFree(pr->W_rank);
+    if (pr->rank_val) (void)hipFree(pr->rank_val);
     if (pr->scratch) (void)hipFree(pr->scratch);
     dtfm_fast64_release(pr);
     delete pr;

@@ -79,22 +79,25 @@ __global__ void k_datap(const double *__restrict__ W_dp, const int32_t *__restri
 }
 
 // ------------------------------------------------------------------------------------------------
-// a4: bottleneck assignment for one (candidate, stage pair) per wavefront, lane c = column c
-// (device at slot c of the second stage). Rows (slots of the first stage) are inserted one at a
-// time; for each, the alternating path to a free column that minimises its largest edge is found
-// by a Dijkstra-style search in which `dist[c]` is the smallest achievable largest-edge of an
-// alternating path from the new row to column c. The optimum of Eq. 3 is the largest of these
-// path values over all insertions: a perfect matching within threshold T exists iff every
-// insertion finds a path within T (Berge), and the matching kept so far never uses an edge above
-// the running maximum. The value is one of the block's entries, so no rounding is involved.
-__device__ __forceinline__ double wave_min_f64(double v)
-{
-    for (int o = 32; o >= 1; o >>= 1) v = fmin(v, __shfl_xor(v, o));
-    return v;
-}
+// a4: bottleneck assignment for one (candidate, stage pair) per wavefront, lane c = column c (device
+// at slot c of the second stage). The optimum of Eq. 3 is one of the block's entries and depends
+// only on their order, so the search runs on `Wr`, the dense ranks of W_pp (equal weights share a
+// rank), and the result is mapped back through `rank_val`: no rounding is involved.
+// Lane c keeps its column of the block, E[r] = Wr[C_j1[r]][C_j2[c]], in registers; every row index
+// used below is wavefront-uniform, so E is read by register-relative moves and the search touches
+// no memory. Rows are inserted one at a time. For row r0 the alternating-path search grows a set of
+// reached rows; dist[c] is the smallest edge from a reached row to column c, and every unvisited
+// column with dist <= theta is reachable within the threshold theta. theta starts at the optimum T
+// of the rows inserted so far and is raised, only when the search is stuck, to the smallest dist of
+// an unvisited column: a perfect matching of rows 0..r0 within theta exists iff an alternating path
+// from r0 to a free column exists within theta (Berge), so the final theta is the new optimum.
+typedef uint32_t dtfm_u32x16 __attribute__((ext_vector_type(16)));
 
-__global__ void k_match(const double *__restrict__ W_pp, const int32_t *__restrict__ perm, int N,
-                        int D_dp, int D_pp, int npairs, size_t total, double *__restrict__ ghat)
+template <int NB>  // number of 16-row register blocks: D_dp <= 16 * NB
+__global__ void __launch_bounds__(256)
+k_match(const uint32_t *__restrict__ Wr, const double *__restrict__ rank_val,
+        const int32_t *__restrict__ perm, int N, int D_dp, int D_pp, int npairs, size_t total,
+        double *__restrict__ ghat)
 {
     const int lane = threadIdx.x & (DTFM_WAVE - 1);
     size_t item = (size_t)blockIdx.x * (blockDim.x / DTFM_WAVE) + threadIdx.x / DTFM_WAVE;
@@ -111,53 +114,102 @@ __global__ void k_match(const double *__restrict__ W_pp, const int32_t *__restri
     const int32_t *row = perm + p * N;
     const int32_t *Ca = row + j1 * D_dp;
     const bool active = lane < D_dp;
-    const int coldev = active ? row[j2 * D_dp + lane] : 0;
+    const uint32_t *col = Wr + (active ? row[j2 * D_dp + lane] : 0);
 
-    int match_row = -1;  // row currently matched to this lane's column
-    double T = 0.0;      // weights are >= 0
+    dtfm_u32x16 E0, E1, E2, E3;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+        E0[r] = r < D_dp ? col[(size_t)Ca[r] * N] : 0xffffffffu;
+        if (NB > 1) E1[r] = r + 16 < D_dp ? col[(size_t)Ca[r + 16] * N] : 0xffffffffu;
+        if (NB > 2) E2[r] = r + 32 < D_dp ? col[(size_t)Ca[r + 32] * N] : 0xffffffffu;
+        if (NB > 3) E3[r] = r + 48 < D_dp ? col[(size_t)Ca[r + 48] * N] : 0xffffffffu;
+    }
+    // E[r] for a wavefront-uniform r. The empty asm statements keep the four register-relative
+    // reads apart (merged into one 64-entry access they would go through scratch memory).
+    auto entry = [&](int r) -> uint32_t {
+        const int lo = r & 15, hi = r >> 4;
+        uint32_t w = E0[lo];
+        asm volatile("" : "+v"(w));
+        if (NB > 1) {
+            uint32_t x = E1[lo];
+            asm volatile("" : "+v"(x));
+            w = hi == 1 ? x : w;
+        }
+        if (NB > 2) {
+            uint32_t x = E2[lo];
+            asm volatile("" : "+v"(x));
+            w = hi == 2 ? x : w;
+        }
+        if (NB > 3) {
+            uint32_t x = E3[lo];
+            asm volatile("" : "+v"(x));
+            w = hi == 3 ? x : w;
+        }
+        return w;
+    };
+
+    const uint64_t allcols = D_dp >= 64 ? ~0ull : ((1ull << D_dp) - 1ull);
+    uint64_t freecols = allcols;  // columns not matched yet
+    int match_row = 0;            // row matched to this lane's column (meaningful when not free)
+    uint32_t T = 0;
     for (int r0 = 0; r0 < D_dp; r0++) {
-        double dist = active ? W_pp[(size_t)Ca[r0] * N + coldev] : INFINITY;
-        int prev = -1;       // previous column on the best path to this column, -1: straight from r0
-        bool visited = !active;
-        double dmin = INFINITY;
-        int cmin = 0;
-        // at most r0 matched columns are visited before a free one; the bound also ends the search
-        // on malformed input (non-finite weights), leaving T = inf
-        for (int step = 0; step <= r0; step++) {
-            double key = visited ? INFINITY : dist;
-            dmin = wave_min_f64(key);
-            unsigned long long hit = __ballot(!visited && key == dmin);
-            if (hit == 0ull) {
-                dmin = INFINITY;
+        uint32_t dist = entry(r0);
+        int prev = -1;  // column whose matched row gave `dist`; -1: the inserted row itself
+        uint64_t visited = 0;
+        uint32_t theta = T;
+        int cfin = -1;
+        // every pass visits at least one new column, ends the search, or follows a raise of theta
+        // that makes the next pass do so: at most 2 (r0 + 1) passes
+        for (int pass = 0; pass < 2 * 16 * NB + 2; pass++) {
+            uint64_t reach = __ballot(dist <= theta) & ~visited & allcols;
+            if (reach == 0ull) {
+                uint32_t k = (((visited >> lane) & 1ull) != 0ull || !active) ? 0xffffffffu : dist;
+                for (int o = 32; o >= 1; o >>= 1) {
+                    uint32_t q = (uint32_t)__shfl_xor((int)k, o);
+                    k = q < k ? q : k;
+                }
+                theta = (uint32_t)__builtin_amdgcn_readfirstlane((int)k);
+                continue;
+            }
+            uint64_t hit = reach & freecols;
+            if (hit != 0ull) {
+                cfin = __builtin_ctzll(hit);
                 break;
             }
-            cmin = __ffsll((long long)hit) - 1;
-            if (lane == cmin) visited = true;
-            int mr = __shfl(match_row, cmin);
-            if (mr < 0) break;  // free column reached
-            double w = active ? W_pp[(size_t)Ca[mr] * N + coldev] : INFINITY;
-            double nd = fmax(dmin, w);
-            if (!visited && nd < dist) {
-                dist = nd;
-                prev = cmin;
+            visited |= reach;
+            const bool open = ((visited >> lane) & 1ull) == 0ull;  // a visited column keeps its path
+            while (reach != 0ull) {  // the rows matched to the newly reached columns join the search
+                const int c = __builtin_ctzll(reach);
+                reach &= reach - 1ull;
+                const int mr = __builtin_amdgcn_readlane(match_row, c);
+                const uint32_t w = entry(mr);
+                if (open && w < dist) {
+                    dist = w;
+                    prev = c;
+                }
             }
         }
-        T = fmax(T, dmin);
+        if (cfin < 0) {  // cannot happen for a finite block; leaves +inf rather than a wrong value
+            T = 0xffffffffu;
+            break;
+        }
+        T = theta;
         // flip the path: column c takes the row of its predecessor column; the first column takes r0
-        int c = cmin;
+        int c = cfin;
         for (int step = 0; step <= r0; step++) {  // a path has at most r0 + 1 columns
-            int pc = __shfl(prev, c);
-            int prow = __shfl(match_row, pc < 0 ? 0 : pc);
-            int newrow = (pc < 0) ? r0 : prow;
-            if (lane == c) match_row = newrow;
+            const int pc = __builtin_amdgcn_readlane(prev, c);
+            const int prow = __builtin_amdgcn_readlane(match_row, pc < 0 ? 0 : pc);
+            if (lane == c) match_row = pc < 0 ? r0 : prow;
             if (pc < 0) break;
             c = pc;
         }
+        freecols &= ~(1ull << cfin);
     }
     if (lane == 0) {
+        const double v = T == 0xffffffffu ? INFINITY : rank_val[T];
         double *G = ghat + p * D_pp * D_pp;
-        G[j1 * D_pp + j2] = T;
-        G[j2 * D_pp + j1] = T;
+        G[j1 * D_pp + j2] = v;
+        G[j2 * D_pp + j1] = v;
     }
 }
 
@@ -324,8 +376,9 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
         size_t total = rows * (size_t)pr->npairs;
         const int waves_per_block = 4;
         size_t blocks = (total + waves_per_block - 1) / waves_per_block;
-        hipLaunchKernelGGL(k_match, dim3((unsigned)blocks), dim3(waves_per_block * DTFM_WAVE), 0, st,
-                           pr->W_pp, perm, N, pr->D_dp, n, pr->npairs, total, b.ghat);
+        auto kern = pr->D_dp <= 16 ? k_match<1> : pr->D_dp <= 32 ? k_match<2> : pr->D_dp <= 48 ? k_match<3> : k_match<4>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(waves_per_block * DTFM_WAVE), 0, st,
+                           pr->W_rank, pr->rank_val, perm, N, pr->D_dp, n, pr->npairs, total, b.ghat);
         DTFM_HIP(hipGetLastError());
     }
     if (cost == nullptr) return DTFM_OK;
