@@ -260,14 +260,18 @@ __global__ void k_held_karp(const double *__restrict__ ghat, const double *__res
     }
 }
 
-// a5/a6 for D_pp above the LDS limit: the table [S][16] lives in HBM and is walked source-side.
+// a5/a6 for D_pp above the LDS limit: the table is walked source-side, in blocks that live in LDS.
 // tab[T][v] depends only on the row of S = T \ v: tab[T][v] = min_{u in S} fl(tab[S][u] + Ghat[u][v]).
-// So a group of 16 lanes takes one source set S, reads its row (128 contiguous bytes; lane u holds
-// tab[S][u], or +inf when u is not in S), rotates the row through the group with DPP so that every
-// lane v meets every u, keeps min_u (tab[S][u] + Ghat[u][v]) and, for v not in S, stores it as
-// tab[S + v][v]: every entry is written exactly once and every row is read exactly once, layer by
-// layer (workgroup barrier between layers). Per candidate 8 MiB of rows are read and 4 MiB of
-// entries written, instead of one 8-byte read per relaxation.
+// So a group of 16 lanes takes one source set S, reads its row (lane u holds tab[S][u], or +inf when
+// u is not in S), rotates the row through the group with DPP so that every lane v meets every u,
+// keeps min_u (tab[S][u] + Ghat[u][v]) and, for v not in S, stores it as tab[S + v][v]: every entry
+// is written exactly once and every row is read exactly once.
+// A set S is split into its high part H (stages >= NL) and its low part L (stages < NL). All 2^NL
+// rows that share H form a block [L][16] in LDS; the blocks are processed in increasing H (every
+// subset of H before H), and inside a block the rows go in layers of |L| with a workgroup barrier
+// between layers. A push to a low stage v stays in the block. A push to a high stage v belongs to
+// the later block H + v: it goes to the workgroup's exchange area X[H + v][v][L] in HBM and is
+// loaded, contiguously, when that block starts. Only these n - NL of every 16 entries cross HBM.
 template <int R>
 __device__ __forceinline__ int dpp_ror_i32(int x)
 {
@@ -307,41 +311,87 @@ struct hk_push_rot<0> {
     static __device__ __forceinline__ double relax(double, const double *, double y) { return y; }
 };
 
-__global__ void __launch_bounds__(1024)
-k_held_karp_push(const double *__restrict__ ghat, const double *__restrict__ datap, int n,
-                 const uint32_t *__restrict__ subsets, dtfm_layer_off lo, double *__restrict__ tab_global,
-                 double *__restrict__ cost, size_t P)
+// C(b, i) for b <= 10
+__device__ const unsigned char dtfm_binom10[11][11] = {
+    {1, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0},   {1, 1, 0, 0, 0, 0, 0, 0, 0, 0, 0},    {1, 2, 1, 0, 0, 0, 0, 0, 0, 0, 0},
+    {1, 3, 3, 1, 0, 0, 0, 0, 0, 0, 0},   {1, 4, 6, 4, 1, 0, 0, 0, 0, 0, 0},    {1, 5, 10, 10, 5, 1, 0, 0, 0, 0, 0},
+    {1, 6, 15, 20, 15, 6, 1, 0, 0, 0, 0}, {1, 7, 21, 35, 35, 21, 7, 1, 0, 0, 0}, {1, 8, 28, 56, 70, 56, 28, 8, 1, 0, 0},
+    {1, 9, 36, 84, 126, 126, 84, 36, 9, 1, 0}, {1, 10, 45, 120, 210, 252, 210, 120, 45, 10, 1}};
+
+template <int NL>  // low stages per block; the workgroup has 2^NL threads
+__global__ void __launch_bounds__(1 << NL)
+k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ datap, int n,
+                    double *__restrict__ xchg, double *__restrict__ cost, size_t P)
 {
-    __shared__ double G[16 * 16];
-    double *tab = tab_global + (size_t)blockIdx.x * ((size_t)16 << n);
-    const int v = threadIdx.x & 15, grp = threadIdx.x >> 4, ngrp = blockDim.x >> 4;
-    const uint32_t full = (1u << n) - 1u;
+    constexpr int ROWS = 1 << NL, THREADS = 1 << NL, GROUPS = THREADS / 16;
+    extern __shared__ double smem[];
+    double *tab = smem;                                           // [ROWS][16]
+    double *G = smem + ROWS * 16;                                 // [16][16], +inf outside n x n
+    uint16_t *lsub = reinterpret_cast<uint16_t *>(G + 256);       // low parts ordered by popcount
+    __shared__ int loff[NL + 2];                                  // first index of each popcount in lsub
+    const int nh = n - NL;
+    double *X = xchg + (size_t)blockIdx.x * (((size_t)nh << nh) << NL);   // [H][high stage][L]
+    const int v = threadIdx.x & 15, grp = threadIdx.x >> 4;
+
+    {   // position of L = threadIdx.x in the (popcount, value) order: combinatorial number system
+        const int L = threadIdx.x, k = __popc(L);
+        int first = 0;
+        for (int j = 0; j < k; j++) first += dtfm_binom10[NL][j];
+        int rank = 0, i = 0;
+        for (int m = L; m; m &= m - 1) {
+            i++;
+            rank += dtfm_binom10[__ffs(m) - 1][i];
+        }
+        lsub[first + rank] = (uint16_t)L;
+        if (L == 0)
+            for (int j = 0, acc = 0; j <= NL + 1; j++) {
+                loff[j] = acc;
+                if (j <= NL) acc += dtfm_binom10[NL][j];
+            }
+    }
     for (size_t p = blockIdx.x; p < P; p += gridDim.x) {
-        for (int e = threadIdx.x; e < 256; e += blockDim.x) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < 256; e += THREADS) {
             const int a = e >> 4, b = e & 15;
             G[e] = (a < n && b < n) ? ghat[p * n * n + a * n + b] : INFINITY;
         }
-        if ((int)threadIdx.x < n) tab[((size_t)1 << threadIdx.x) * 16 + threadIdx.x] = 0.0;
+        if ((int)threadIdx.x < NL) tab[((size_t)1 << threadIdx.x) * 16 + threadIdx.x] = 0.0;   // block H = 0
         __syncthreads();
         double Gc[15];
         hk_push_rot<15>::setup(G, v, Gc);
-        for (int k = 1; k < n; k++) {
-            const int first = lo.off[k], cnt = lo.off[k + 1] - first;
-            for (int i = grp; i < cnt; i += ngrp) {
-                const uint32_t S = subsets[first + i];
-                const bool in = (S >> v) & 1u;
-                const double x = in ? tab[(size_t)S * 16 + v] : INFINITY;
-                const double y = hk_push_rot<15>::relax(x, Gc, INFINITY);
-                if (!in && v < n) tab[(size_t)(S | (1u << v)) * 16 + v] = y;
-            }
+        for (uint32_t H = 0; H < (1u << nh); H++) {
+            // entries that end in a high stage: pushed by the blocks H - h (a single high stage alone
+            // is a path of one node)
+            for (int hi = 0; hi < nh; hi++)
+                if ((H >> hi) & 1u) {
+                    const int L = threadIdx.x;
+                    tab[L * 16 + NL + hi] =
+                        (H == (1u << hi) && L == 0) ? 0.0 : X[(((size_t)H * nh + hi) << NL) + L];
+                }
             __syncthreads();
+            for (int k = 0; k <= NL; k++) {
+                const int first = loff[k], cnt = loff[k + 1] - first;
+                for (int i = grp; i < cnt; i += GROUPS) {
+                    const uint32_t L = lsub[first + i];
+                    const uint32_t S = (H << NL) | L;
+                    const bool in = (S >> v) & 1u;
+                    const double x = in ? tab[L * 16 + v] : INFINITY;
+                    const double y = hk_push_rot<15>::relax(x, Gc, INFINITY);
+                    if (!in && v < n && S != 0u) {
+                        if (v < NL)
+                            tab[(L | (1u << v)) * 16 + v] = y;
+                        else
+                            X[(((size_t)(H | (1u << (v - NL))) * nh + (v - NL)) << NL) + L] = y;
+                    }
+                }
+                __syncthreads();
+            }
         }
-        if (threadIdx.x == 0) {
+        if (threadIdx.x == 0) {   // the block of H = all high stages is still in LDS; its last row is the full set
             double m = INFINITY;
-            for (int u = 0; u < n; u++) m = fmin(m, tab[(size_t)full * 16 + u]);
+            for (int u = 0; u < n; u++) m = fmin(m, tab[(ROWS - 1) * 16 + u]);
             cost[p] = __dadd_rn(datap[p], m);
         }
-        __syncthreads();
     }
 }
 
@@ -354,7 +404,8 @@ dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t ro
     b.hk_tab = nullptr;
     if (pr->D_pp > DTFM_HK_LDS_MAX_DPP) {
         size_t grid = rows < DTFM_HK_GLOBAL_GRID ? rows : DTFM_HK_GLOBAL_GRID;
-        b.hk_tab = ar.take<double>(grid * ((size_t)16 << n));
+        size_t nh = n - DTFM_HK_BLOCK_LOW;
+        b.hk_tab = ar.take<double>(grid * ((nh << nh) << DTFM_HK_BLOCK_LOW));
     }
     return b;
 }
@@ -392,8 +443,12 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
                            pr->hk_subsets, pr->hk_off, (double *)nullptr, cost, rows);
     } else {
         size_t grid = rows < DTFM_HK_GLOBAL_GRID ? rows : DTFM_HK_GLOBAL_GRID;
-        hipLaunchKernelGGL(k_held_karp_push, dim3((unsigned)grid), dim3(1024), 0, st, b.ghat, b.datap, n,
-                           pr->hk_subsets, pr->hk_off, b.hk_tab, cost, rows);
+        constexpr int NL = DTFM_HK_BLOCK_LOW;
+        size_t lds = ((size_t)(16 << NL) + 256) * sizeof(double) + ((size_t)sizeof(uint16_t) << NL);
+        DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_held_karp_blocked<NL>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(k_held_karp_blocked<NL>, dim3((unsigned)grid), dim3(1 << NL), lds, st, b.ghat,
+                           b.datap, n, b.hk_tab, cost, rows);
     }
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;

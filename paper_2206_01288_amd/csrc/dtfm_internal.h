@@ -12,8 +12,11 @@
 // Largest D_pp whose Held-Karp table (2^D_pp x D_pp fp64) is kept in LDS by the general kernel:
 // 2^10 * 10 * 8 B = 80 KiB of the CU's 160 KiB.
 #define DTFM_HK_LDS_MAX_DPP 10
-// Workgroups (= concurrently live tables) of the Held-Karp kernel when the table lives in HBM.
-#define DTFM_HK_GLOBAL_GRID 512
+// Above that limit the table is processed in LDS blocks over the DTFM_HK_BLOCK_LOW lowest stages
+// (2^10 rows x 16 fp64 = 128 KiB: one workgroup per CU); DTFM_HK_GLOBAL_GRID workgroups, each with
+// its own exchange area in HBM for the entries that pass from block to block.
+#define DTFM_HK_BLOCK_LOW 10
+#define DTFM_HK_GLOBAL_GRID 256
 
 struct dtfm_layer_off {
     int off[DTFM_MAX_DPP + 2];  // off[k] = first index of the subsets of popcount k; off[n+1] = end
@@ -64,7 +67,7 @@ int dtfm_hip_fail(hipError_t e, const char *what);
 struct dtfm_eval_bufs {
     double *datap;   // rows
     double *ghat;    // rows * D_pp * D_pp
-    double *hk_tab;  // DTFM_HK_GLOBAL_GRID tables, or null when the table fits LDS
+    double *hk_tab;  // DTFM_HK_GLOBAL_GRID exchange areas, or null when the table fits LDS
 };
 dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows);
 // enqueues a2..a6 for `rows` candidates; cost may be null (then only datap/ghat are produced)

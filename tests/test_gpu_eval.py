@@ -100,12 +100,13 @@ def test_config5_population_sampled():
 
 
 @pytest.mark.parametrize("D_dp,D_pp", [(1, 1), (1, 5), (5, 1), (2, 2), (3, 4), (7, 3), (4, 9), (3, 10),
-                                        (2, 11), (5, 12), (33, 2), (64, 3), (16, 8), (8, 16)])
+                                        (2, 11), (5, 12), (3, 13), (2, 14), (2, 15), (17, 2), (20, 3), (33, 2),
+                                        (40, 2), (64, 3), (16, 8), (8, 16)])
 def test_odd_and_degenerate_shapes(D_dp, D_pp):
     N = D_dp * D_pp
     w = custom(N, D_dp, D_pp, seed=N + 1)
     o, g = both(w)
-    for P in (1, 67):
+    for P in (1, 67) + ((300,) if D_pp == 13 else ()):   # 300: more candidates than workgroups
         perms = workloads.random_population(P, N, seed=P)
         assert_costs_equal(host(dtfm.eval_population(g, dev(perms))), o.eval_population(perms))
 
