@@ -262,54 +262,24 @@ __global__ void k_held_karp(const double *__restrict__ ghat, const double *__res
 
 // a5/a6 for D_pp above the LDS limit: the table is walked source-side, in blocks that live in LDS.
 // tab[T][v] depends only on the row of S = T \ v: tab[T][v] = min_{u in S} fl(tab[S][u] + Ghat[u][v]).
-// So a group of 16 lanes takes one source set S, reads its row (lane u holds tab[S][u], or +inf when
-// u is not in S), rotates the row through the group with DPP so that every lane v meets every u,
-// keeps min_u (tab[S][u] + Ghat[u][v]) and, for v not in S, stores it as tab[S + v][v]: every entry
-// is written exactly once and every row is read exactly once.
+// Rows have 16 slots; the slot of a stage that is not in the set holds +inf. A group of 16 lanes
+// takes one source set S; all its lanes read the whole row (128-bit LDS reads of one address per
+// group, served as broadcasts), lane v keeps min_u (tab[S][u] + Ghat[u][v]) with its column of
+// Ghat in registers and, for v not in S, stores it as tab[S + v][v]: every entry is written
+// exactly once and every row is read exactly once.
 // A set S is split into its high part H (stages >= NL) and its low part L (stages < NL). All 2^NL
 // rows that share H form a block [L][16] in LDS; the blocks are processed in increasing H (every
 // subset of H before H), and inside a block the rows go in layers of |L| with a workgroup barrier
 // between layers. A push to a low stage v stays in the block. A push to a high stage v belongs to
 // the later block H + v: it goes to the workgroup's exchange area X[H + v][v][L] in HBM and is
 // loaded, contiguously, when that block starts. Only these n - NL of every 16 entries cross HBM.
-template <int R>
-__device__ __forceinline__ int dpp_ror_i32(int x)
-{
-    return __builtin_amdgcn_update_dpp(0, x, 0x120 + R, 0xf, 0xf, false);   // row_ror:R within 16 lanes
-}
-template <int R>
-__device__ __forceinline__ double dpp_ror_f64(double x)
-{
-    union {
-        double d;
-        int i[2];
-    } a, b;
-    a.d = x;
-    b.i[0] = dpp_ror_i32<R>(a.i[0]);
-    b.i[1] = dpp_ror_i32<R>(a.i[1]);
-    return b.d;
-}
-
-template <int R>
-struct hk_push_rot {
-    // Gc[R-1] = Ghat[u][v] for the lane u that rotation R brings to lane v
-    static __device__ __forceinline__ void setup(const double *G, int v, double *Gc)
-    {
-        const int u = dpp_ror_i32<R>(v);
-        Gc[R - 1] = G[u * 16 + v];
-        hk_push_rot<R - 1>::setup(G, v, Gc);
-    }
-    static __device__ __forceinline__ double relax(double x, const double *Gc, double y)
-    {
-        y = hk_push_rot<R - 1>::relax(x, Gc, y);
-        return fmin(y, __dadd_rn(dpp_ror_f64<R>(x), Gc[R - 1]));
-    }
-};
-template <>
-struct hk_push_rot<0> {
-    static __device__ __forceinline__ void setup(const double *, int, double *) {}
-    static __device__ __forceinline__ double relax(double, const double *, double y) { return y; }
-};
+// Workgroup barrier that orders LDS accesses only: global stores in flight are not waited for.
+#define DTFM_LDS_BARRIER()                                                  \
+    do {                                                                    \
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");     \
+        __builtin_amdgcn_s_barrier();                                       \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");     \
+    } while (0)
 
 // C(b, i) for b <= 10
 __device__ const unsigned char dtfm_binom10[11][11] = {
@@ -323,12 +293,15 @@ __global__ void __launch_bounds__(1 << NL)
 k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ datap, int n,
                     double *__restrict__ xchg, double *__restrict__ cost, size_t P)
 {
-    constexpr int ROWS = 1 << NL, THREADS = 1 << NL, GROUPS = THREADS / 16;
+    // rows are RS = 18 doubles apart (144 B = 36 banks): the same slot of 16 consecutive rows falls
+    // into 16 different bank pairs, and the 128-bit row reads stay aligned
+    constexpr int ROWS = 1 << NL, THREADS = 1 << NL, GROUPS = THREADS / 16, RS = DTFM_HK_ROW_STRIDE;
     extern __shared__ double smem[];
-    double *tab = smem;                                           // [ROWS][16]
-    double *G = smem + ROWS * 16;                                 // [16][16], +inf outside n x n
+    double *tab = smem;                                           // [ROWS][RS], 16 slots used
+    double *G = smem + ROWS * RS;                                 // [16][16], +inf outside n x n
     uint16_t *lsub = reinterpret_cast<uint16_t *>(G + 256);       // low parts ordered by popcount
     __shared__ int loff[NL + 2];                                  // first index of each popcount in lsub
+    constexpr int NHMAX = 16 - NL;
     const int nh = n - NL;
     double *X = xchg + (size_t)blockIdx.x * (((size_t)nh << nh) << NL);   // [H][high stage][L]
     const int v = threadIdx.x & 15, grp = threadIdx.x >> 4;
@@ -355,41 +328,66 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
             const int a = e >> 4, b = e & 15;
             G[e] = (a < n && b < n) ? ghat[p * n * n + a * n + b] : INFINITY;
         }
-        if ((int)threadIdx.x < NL) tab[((size_t)1 << threadIdx.x) * 16 + threadIdx.x] = 0.0;   // block H = 0
+#pragma unroll
+        for (int e = 0; e < RS; e++) tab[e * THREADS + threadIdx.x] = INFINITY;   // empty slots read as +inf
         __syncthreads();
-        double Gc[15];
-        hk_push_rot<15>::setup(G, v, Gc);
+        if ((int)threadIdx.x < NL) tab[((size_t)1 << threadIdx.x) * RS + threadIdx.x] = 0.0;   // block H = 0
+        __syncthreads();
+        double Gc[16];   // column v of Ghat
+#pragma unroll
+        for (int u = 0; u < 16; u++) Gc[u] = G[u * 16 + v];
+        // entries of block Hq that end in a high stage: pushed by the blocks Hq - h (a single high
+        // stage alone is a path of one node); +inf for the high stages outside Hq
+        const int Lt = threadIdx.x;
+        auto fetch = [&](uint32_t Hq, double (&xv)[NHMAX]) {
+#pragma unroll
+            for (int hi = 0; hi < NHMAX; hi++) {
+                double val = INFINITY;
+                if (hi < nh && ((Hq >> hi) & 1u))
+                    val = (Hq == (1u << hi) && Lt == 0) ? 0.0 : X[(((size_t)Hq * nh + hi) << NL) + Lt];
+                xv[hi] = val;
+            }
+        };
         for (uint32_t H = 0; H < (1u << nh); H++) {
-            // entries that end in a high stage: pushed by the blocks H - h (a single high stage alone
-            // is a path of one node)
-            for (int hi = 0; hi < nh; hi++)
-                if ((H >> hi) & 1u) {
-                    const int L = threadIdx.x;
-                    tab[L * 16 + NL + hi] =
-                        (H == (1u << hi) && L == 0) ? 0.0 : X[(((size_t)H * nh + hi) << NL) + L];
-                }
+            if (H != 0u) {   // the previous block is done (barrier after its last layer)
+#pragma unroll
+                for (int e = 0; e < RS; e++) tab[e * THREADS + threadIdx.x] = INFINITY;
+            }
+            // orders the fill before the stores below and completes every exchange store issued so far
             __syncthreads();
+            double xv[NHMAX];
+            fetch(H, xv);
+#pragma unroll
+            for (int hi = 0; hi < NHMAX; hi++)
+                if (hi < nh) tab[Lt * RS + NL + hi] = xv[hi];
+            DTFM_LDS_BARRIER();
             for (int k = 0; k <= NL; k++) {
                 const int first = loff[k], cnt = loff[k + 1] - first;
                 for (int i = grp; i < cnt; i += GROUPS) {
                     const uint32_t L = lsub[first + i];
                     const uint32_t S = (H << NL) | L;
                     const bool in = (S >> v) & 1u;
-                    const double x = in ? tab[L * 16 + v] : INFINITY;
-                    const double y = hk_push_rot<15>::relax(x, Gc, INFINITY);
+                    const double2 *row = reinterpret_cast<const double2 *>(tab + L * RS);
+                    double y = INFINITY;
+#pragma unroll
+                    for (int h = 0; h < 8; h++) {
+                        const double2 x = row[h];
+                        y = fmin(y, __dadd_rn(x.x, Gc[2 * h]));
+                        y = fmin(y, __dadd_rn(x.y, Gc[2 * h + 1]));
+                    }
                     if (!in && v < n && S != 0u) {
                         if (v < NL)
-                            tab[(L | (1u << v)) * 16 + v] = y;
+                            tab[(L | (1u << v)) * RS + v] = y;
                         else
                             X[(((size_t)(H | (1u << (v - NL))) * nh + (v - NL)) << NL) + L] = y;
                     }
                 }
-                __syncthreads();
+                DTFM_LDS_BARRIER();
             }
         }
         if (threadIdx.x == 0) {   // the block of H = all high stages is still in LDS; its last row is the full set
             double m = INFINITY;
-            for (int u = 0; u < n; u++) m = fmin(m, tab[(ROWS - 1) * 16 + u]);
+            for (int u = 0; u < n; u++) m = fmin(m, tab[(ROWS - 1) * RS + u]);
             cost[p] = __dadd_rn(datap[p], m);
         }
     }
@@ -444,7 +442,7 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
     } else {
         size_t grid = rows < DTFM_HK_GLOBAL_GRID ? rows : DTFM_HK_GLOBAL_GRID;
         constexpr int NL = DTFM_HK_BLOCK_LOW;
-        size_t lds = ((size_t)(16 << NL) + 256) * sizeof(double) + ((size_t)sizeof(uint16_t) << NL);
+        size_t lds = ((size_t)(DTFM_HK_ROW_STRIDE << NL) + 256) * sizeof(double) + ((size_t)sizeof(uint16_t) << NL);
         DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_held_karp_blocked<NL>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(k_held_karp_blocked<NL>, dim3((unsigned)grid), dim3(1 << NL), lds, st, b.ghat,

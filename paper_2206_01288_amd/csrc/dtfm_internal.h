@@ -13,9 +13,10 @@
 // 2^10 * 10 * 8 B = 80 KiB of the CU's 160 KiB.
 #define DTFM_HK_LDS_MAX_DPP 10
 // Above that limit the table is processed in LDS blocks over the DTFM_HK_BLOCK_LOW lowest stages
-// (2^10 rows x 16 fp64 = 128 KiB: one workgroup per CU); DTFM_HK_GLOBAL_GRID workgroups, each with
+// (2^10 rows x 18 fp64 = 144 KiB: one workgroup per CU); DTFM_HK_GLOBAL_GRID workgroups, each with
 // its own exchange area in HBM for the entries that pass from block to block.
 #define DTFM_HK_BLOCK_LOW 10
+#define DTFM_HK_ROW_STRIDE 18   // doubles between rows of a block (16 slots + padding against bank conflicts)
 #define DTFM_HK_GLOBAL_GRID 256
 
 struct dtfm_layer_off {
