@@ -273,14 +273,6 @@ __global__ void k_held_karp(const double *__restrict__ ghat, const double *__res
 // between layers. A push to a low stage v stays in the block. A push to a high stage v belongs to
 // the later block H + v: it goes to the workgroup's exchange area X[H + v][v][L] in HBM and is
 // loaded, contiguously, when that block starts. Only these n - NL of every 16 entries cross HBM.
-// Workgroup barrier that orders LDS accesses only: global stores in flight are not waited for.
-#define DTFM_LDS_BARRIER()                                                  \
-    do {                                                                    \
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");     \
-        __builtin_amdgcn_s_barrier();                                       \
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");     \
-    } while (0)
-
 // C(b, i) for b <= 10
 __device__ const unsigned char dtfm_binom10[11][11] = {
     {1, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0},   {1, 1, 0, 0, 0, 0, 0, 0, 0, 0, 0},    {1, 2, 1, 0, 0, 0, 0, 0, 0, 0, 0},

@@ -19,6 +19,15 @@
 #define DTFM_HK_ROW_STRIDE 18   // doubles between rows of a block (16 slots + padding against bank conflicts)
 #define DTFM_HK_GLOBAL_GRID 256
 
+// Workgroup barrier that orders LDS accesses only: global memory operations in flight are not
+// waited for.
+#define DTFM_LDS_BARRIER()                                                  \
+    do {                                                                    \
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");     \
+        __builtin_amdgcn_s_barrier();                                       \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");     \
+    } while (0)
+
 struct dtfm_layer_off {
     int off[DTFM_MAX_DPP + 2];  // off[k] = first index of the subsets of popcount k; off[n+1] = end
 };
