@@ -64,6 +64,10 @@ def lib():
         L.orc_comm_cost.argtypes = [dp, dp, c_int, c_int, c_int, ip, c_int]
         L.orc_comm_cost.restype = c_double
         L.orc_eval_population.argtypes = [dp, dp, c_int, c_int, c_int, ip, c_int, dp]
+        L.orc_hk_path.argtypes = [dp, c_int, ip]
+        L.orc_lexmin_matching.argtypes = [dp, c_int, c_double, ip]
+        L.orc_lexmin_matching.restype = c_int
+        L.orc_get_assignment.argtypes = [dp, c_int, c_int, c_int, ip, ip, ip]
         L.orc_gain4_propose.argtypes = [dp, c_int, c_int, c_int, ip, c_int, ip, ip, dp]
         L.orc_local_search.argtypes = [dp, dp, c_int, c_int, c_int, ip, c_int, c_int, c_int, dp, lp]
         L.orc_philox4x32_10.argtypes = [POINTER(c_uint32), POINTER(c_uint32), POINTER(c_uint32)]
@@ -131,6 +135,15 @@ class Problem:
                                   cost.ctypes.data_as(POINTER(c_double)))
         return cost
 
+    def get_assignment(self, perm):
+        """(stage order [D_pp], pipelines sigma [D_dp, D_pp]) of one candidate, canonical choices."""
+        perm, pp = _i(perm)
+        order = np.empty(self.D_pp, dtype=np.int32)
+        sigma = np.empty((self.D_dp, self.D_pp), dtype=np.int32)
+        lib().orc_get_assignment(self._w()[1], self.N, self.D_dp, self.D_pp, pp,
+                                 order.ctypes.data_as(POINTER(c_int)), sigma.ctypes.data_as(POINTER(c_int)))
+        return order, sigma
+
     def gain4_propose(self, perm, r):
         perm, pp = _i(perm)
         a, b = c_int(), c_int()
@@ -182,6 +195,21 @@ def open_tsp(G, brute=False) -> float:
     G, pg = _d(G)
     n = G.shape[0]
     return lib().orc_open_tsp_brute(pg, n) if brute else lib().orc_open_tsp_held_karp(pg, n)
+
+
+def hk_path(G) -> np.ndarray:
+    G, pg = _d(G)
+    order = np.empty(G.shape[0], dtype=np.int32)
+    lib().orc_hk_path(pg, G.shape[0], order.ctypes.data_as(POINTER(c_int)))
+    return order
+
+
+def lexmin_matching(w, t):
+    """Lexicographically smallest perfect matching within entries <= t, or None."""
+    w, pw = _d(w)
+    mate = np.empty(w.shape[0], dtype=np.int32)
+    ok = lib().orc_lexmin_matching(pw, w.shape[0], float(t), mate.ctypes.data_as(POINTER(c_int)))
+    return mate if ok else None
 
 
 def datap_stage(W_dp, C) -> float:

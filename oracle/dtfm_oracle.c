@@ -27,6 +27,10 @@
  *   orc_local_search GAIN4      gain formula pinned by hand computation; the choice of stage
  *                               pair per round and acceptance rule are this build's reading:
  *                               parity unpinned beyond invariants
+ *   orc_get_assignment          the tie-breaking rules are this build's choice (the paper names
+ *                               none): pinned as implementing those rules by enumeration of all
+ *                               tours and all matchings on tiny cases, by the closed form on a
+ *                               homogeneous network, and by re-deriving the cost from the output
  *   orc_philox4x32_10           pinned: published known-answer vectors
  *   orc_evolve                  invariants only (valid permutations, elitism, determinism);
  *                               the GA operators are this build's reading: parity unpinned
@@ -267,6 +271,126 @@ void orc_eval_population(const double *W_dp, const double *W_pp, int N, int D_dp
 {
     for (int p = 0; p < P; p++)
         cost[p] = orc_comm_cost(W_dp, W_pp, N, D_dp, D_pp, perm + (size_t)p * N, 0);
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* The assignment behind the cost (Sec. 2, "Pipeline parallel"; Sec. 3.3): the order in which the
+ * stage groups C_j form the pipeline, and the D_dp pipelines P_i = { sigma_{i,j} } obtained by
+ * chaining one optimal matching (Eq. 3) per adjacent pair of that order: matched devices handle
+ * the same micro-batch.
+ *
+ * Neither the optimal order nor an optimal matching is unique; the paper names no choice. This
+ * build's canonical choices:
+ *   order     Held-Karp back-tracking. The path ends in the lowest-numbered node v that attains
+ *             min_v best[all][v]; the node before v in a path over S is the lowest-numbered u in
+ *             S \ v with best[S \ v][u] + Ghat[u][v] == best[S][v] (equality of the rounded
+ *             values). order[] lists the nodes from the path's first to its last.
+ *   matching  for adjacent nodes A = order[k], B = order[k+1] with optimum T = Ghat[A][B]: among
+ *             the perfect matchings that use only pairs with W_pp <= T, the one whose vector
+ *             (slot in B matched to slot 0 of A, to slot 1 of A, ...) is lexicographically
+ *             smallest.
+ *   pipeline  P_i starts at slot i of stage order[0] and follows the matchings.                  */
+
+/* order[0..n): the canonical optimal open-loop tour over Ghat (see above). */
+void orc_hk_path(const double *Ghat, int n, int *order)
+{
+    if (n == 1) { order[0] = 0; return; }
+    size_t full = ((size_t)1 << n) - 1;
+    double *best = (double *)malloc(sizeof(double) * (full + 1) * n);
+    for (size_t S = 1; S <= full; S++) {
+        for (int v = 0; v < n; v++) {
+            if (!(S & ((size_t)1 << v))) continue;
+            size_t rest = S ^ ((size_t)1 << v);
+            if (rest == 0) { best[S * n + v] = 0.0; continue; }
+            double m = INFINITY;
+            for (int u = 0; u < n; u++) {
+                if (!(rest & ((size_t)1 << u))) continue;
+                double c = best[rest * n + u] + Ghat[u * n + v];
+                if (c < m) m = c;
+            }
+            best[S * n + v] = m;
+        }
+    }
+    int v = 0;
+    for (int x = 1; x < n; x++)
+        if (best[full * n + x] < best[full * n + v]) v = x;   /* lowest index among the minimisers */
+    size_t S = full;
+    for (int pos = n - 1; pos >= 0; pos--) {
+        order[pos] = v;
+        size_t rest = S ^ ((size_t)1 << v);
+        if (rest == 0) break;
+        int pred = -1;
+        for (int u = 0; u < n && pred < 0; u++)
+            if ((rest & ((size_t)1 << u)) && best[rest * n + u] + Ghat[u * n + v] == best[S * n + v]) pred = u;
+        S = rest;
+        v = pred;
+    }
+    free(best);
+}
+
+/* 1 iff rows first_row..n-1 can all be matched, within entries <= t, to columns not in col_used. */
+static int rest_feasible(const double *w, int n, double t, int first_row, const int *col_used)
+{
+    int *col_row = (int *)malloc(sizeof(int) * n);
+    int *seen = (int *)malloc(sizeof(int) * n);
+    int ok = 1;
+    for (int c = 0; c < n; c++) col_row[c] = -1;
+    for (int r = first_row; r < n && ok; r++) {
+        for (int c = 0; c < n; c++) seen[c] = col_used[c];   /* a used column is never entered */
+        ok = try_row(w, n, t, r, seen, col_row);
+    }
+    free(col_row);
+    free(seen);
+    return ok;
+}
+
+/* mate[r] = column matched to row r in the lexicographically smallest perfect matching within
+ * the entries <= t of the n x n block w. Returns 0 (mate undefined) if there is none. Row by row,
+ * the smallest column that still leaves the remaining rows a perfect matching is taken. */
+int orc_lexmin_matching(const double *w, int n, double t, int *mate)
+{
+    int *used = (int *)calloc((size_t)n, sizeof(int));
+    int ok = 1;
+    for (int r = 0; r < n && ok; r++) {
+        ok = 0;
+        for (int c = 0; c < n && !ok; c++) {
+            if (used[c] || !(w[r * n + c] <= t)) continue;
+            used[c] = 1;
+            if (rest_feasible(w, n, t, r + 1, used)) { mate[r] = c; ok = 1; }
+            else used[c] = 0;
+        }
+    }
+    free(used);
+    return ok;
+}
+
+/* order[D_pp]: stage index at each pipeline position; sigma[i * D_pp + k]: device of pipeline i
+ * at position k (it belongs to stage order[k]). */
+void orc_get_assignment(const double *W_pp, int N, int D_dp, int D_pp, const int *perm, int *order,
+                        int *sigma)
+{
+    double *Ghat = (double *)malloc(sizeof(double) * D_pp * D_pp);
+    double *blk = (double *)malloc(sizeof(double) * D_dp * D_dp);
+    int *mate = (int *)malloc(sizeof(int) * D_dp);
+    int *slot = (int *)malloc(sizeof(int) * D_dp);   /* slot of pipeline i in the current stage */
+    orc_coarsen(W_pp, N, perm, D_dp, D_pp, 0, Ghat);
+    orc_hk_path(Ghat, D_pp, order);
+    for (int i = 0; i < D_dp; i++) {
+        slot[i] = i;
+        sigma[i * D_pp + 0] = perm[order[0] * D_dp + i];
+    }
+    for (int k = 0; k + 1 < D_pp; k++) {
+        int A = order[k], B = order[k + 1];
+        for (int r = 0; r < D_dp; r++)
+            for (int c = 0; c < D_dp; c++)
+                blk[r * D_dp + c] = W_pp[perm[A * D_dp + r] * N + perm[B * D_dp + c]];
+        orc_lexmin_matching(blk, D_dp, Ghat[A * D_pp + B], mate);
+        for (int i = 0; i < D_dp; i++) {
+            slot[i] = mate[slot[i]];
+            sigma[i * D_pp + k + 1] = perm[B * D_dp + slot[i]];
+        }
+    }
+    free(Ghat); free(blk); free(mate); free(slot);
 }
 
 /* ------------------------------------------------------------------------------------------ */
