@@ -80,6 +80,25 @@ int dtfm_eval_population(dtfm_problem *prob, const int32_t *perm, int P, double 
 int dtfm_coarsened_graph(dtfm_problem *prob, const int32_t *perm, int P, double *ghat,
                          double *datap, void *hip_stream);
 
+/* The assignment behind the cost of each candidate (Sec. 2, "Pipeline parallel": the pipelines
+ * P_i = { sigma_{i,j} }; Sec. 3.3: devices matched between adjacent stage groups handle the same
+ * micro-batch and the groups are ordered by the open-loop tour of Eq. 4). Neither optimum is unique
+ * and the paper names no choice; the canonical ones taken here:
+ *  - order: Held-Karp back-tracking. The tour ends in the lowest-numbered group attaining the
+ *    minimum; the group before v in a tour over the set S is the lowest-numbered u in S \ v whose
+ *    rounded value tab[S \ v][u] + Ghat[u][v] equals tab[S][v];
+ *  - matching of adjacent groups (A, B) with Eq. 3 optimum T: the lexicographically smallest vector
+ *    (slot of B matched to slot 0 of A, to slot 1 of A, ...) among the perfect matchings that use
+ *    only device pairs with W_pp <= T;
+ *  - pipeline i starts at slot i of the first group of the order and follows the matchings.
+ * perm: device, P*N int32, read only. stage_order: device, P*D_pp int32, out: stage index at each
+ * pipeline position, first to last. sigma: device, P*D_dp*D_pp int32, out: [p][i][k] = device of
+ * pipeline i at position k (a member of stage stage_order[p][k]). Summing over k the largest
+ * W_pp[sigma[i][k]][sigma[i][k+1]] over i, left to right, and adding DataP gives the bits of
+ * dtfm_eval_population. Enqueues only. Errors: NULL, ARG (P < 0), HIP. */
+int dtfm_get_assignment(dtfm_problem *prob, const int32_t *perm, int P, int32_t *stage_order,
+                        int32_t *sigma, void *hip_stream);
+
 /* Validity of Sec. 2 ("a valid assignment needs to be unique"): counts the rows of perm that are
  * not permutations of 0..N-1 into *bad_rows (device, one int32, overwritten). */
 int dtfm_validate_population(dtfm_problem *prob, const int32_t *perm, int P, int32_t *bad_rows,

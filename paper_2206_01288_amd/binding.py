@@ -16,7 +16,7 @@ GAIN4 = 1
 # every entry point include/dtfm.h declares
 DECLARED_SYMBOLS = [
     "dtfm_create_problem", "dtfm_destroy_problem", "dtfm_get_weights", "dtfm_eval_population",
-    "dtfm_coarsened_graph", "dtfm_validate_population", "dtfm_local_search", "dtfm_evolve",
+    "dtfm_coarsened_graph", "dtfm_get_assignment", "dtfm_validate_population", "dtfm_local_search", "dtfm_evolve",
     "dtfm_philox_blocks", "dtfm_status_string", "dtfm_last_hip_error",
 ]
 
@@ -56,6 +56,7 @@ def load_library():
     L.dtfm_get_weights.argtypes = [c_void_p, dp, dp]
     L.dtfm_eval_population.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p]
     L.dtfm_coarsened_graph.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p]
+    L.dtfm_get_assignment.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p]
     L.dtfm_validate_population.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p]
     L.dtfm_local_search.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p]
     L.dtfm_evolve.argtypes = [c_void_p, c_uint64, c_int, POINTER(GAParams), c_void_p, c_void_p, c_void_p, c_void_p]
@@ -164,6 +165,18 @@ def coarsened_graph(prob: Problem, perm, stream=None):
     _check(L.dtfm_coarsened_graph(prob.handle, _dev_ptr(perm, torch.int32, P * prob.N, "perm"), P,
                                   _dev_ptr(ghat, torch.float64), _dev_ptr(datap, torch.float64), _stream(stream)))
     return ghat, datap
+
+
+def get_assignment(prob: Problem, perm, stream=None):
+    """Returns (stage_order [P, D_pp], sigma [P, D_dp, D_pp]) int32 device tensors."""
+    import torch
+    L = load_library()
+    P = perm.shape[0]
+    order = torch.empty((P, prob.D_pp), dtype=torch.int32, device=perm.device)
+    sigma = torch.empty((P, prob.D_dp, prob.D_pp), dtype=torch.int32, device=perm.device)
+    _check(L.dtfm_get_assignment(prob.handle, _dev_ptr(perm, torch.int32, P * prob.N, "perm"), P,
+                                 _dev_ptr(order, torch.int32), _dev_ptr(sigma, torch.int32), _stream(stream)))
+    return order, sigma
 
 
 def validate_population(prob: Problem, perm, stream=None) -> int:

@@ -213,6 +213,23 @@ extern "C" int dtfm_coarsened_graph(dtfm_problem *pr, const int32_t *perm, int P
     return DTFM_OK;
 }
 
+extern "C" int dtfm_get_assignment(dtfm_problem *pr, const int32_t *perm, int P, int32_t *stage_order,
+                                   int32_t *sigma, void *hip_stream)
+{
+    if (pr == nullptr) return DTFM_ERR_NULL;
+    if (P < 0) return DTFM_ERR_ARG;
+    if (P == 0) return DTFM_OK;
+    if (perm == nullptr || stage_order == nullptr || sigma == nullptr) return DTFM_ERR_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    dtfm_arena measure = {nullptr, 0};
+    dtfm_assign_carve(pr, measure, (size_t)P);
+    int rc = ensure_scratch(pr, measure.off);
+    if (rc != DTFM_OK) return rc;
+    dtfm_arena ar = {pr->scratch, 0};
+    dtfm_assign_bufs b = dtfm_assign_carve(pr, ar, (size_t)P);
+    return dtfm_assign_enqueue(pr, b, perm, (size_t)P, stage_order, sigma, st);
+}
+
 extern "C" int dtfm_validate_population(dtfm_problem *pr, const int32_t *perm, int P, int32_t *bad_rows,
                                         void *hip_stream)
 {

@@ -86,6 +86,16 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
 int dtfm_weights_enqueue(const double *lat_dev, const double *bw_dev, int N, double shard,
                          double c_pp, double *W_dp, double *W_pp, hipStream_t st);
 
+// ---- assignment extraction (dtfm_assign.hip) ---------------------------------------------------
+struct dtfm_assign_bufs {
+    dtfm_eval_bufs ev;
+    double *tab;      // Held-Karp tables kept for back-tracking, one per concurrently live workgroup
+    int32_t *mates;   // rows * (D_pp - 1) * D_dp: matching of each adjacent pair of the order
+};
+dtfm_assign_bufs dtfm_assign_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows);
+int dtfm_assign_enqueue(const dtfm_problem *pr, const dtfm_assign_bufs &b, const int32_t *perm, size_t rows,
+                        int32_t *stage_order, int32_t *sigma, hipStream_t st);
+
 // ---- fused evaluation, 64-device shape (dtfm_fast64.hip) ---------------------------------------
 bool dtfm_fast64_applicable(const dtfm_problem *pr);
 int dtfm_fast64_prepare(dtfm_problem *pr);
