@@ -20,7 +20,14 @@
 namespace {
 
 constexpr int HKP_THREADS = 256;
-constexpr size_t HKP_GRID = 32;   // concurrently live tables (8 MiB each at D_pp = 16)
+// concurrently live Held-Karp tables: as many as fit 256 MiB of scratch (32 of 8 MiB at D_pp = 16),
+// at most 2048
+static size_t hkp_grid(int n, size_t rows)
+{
+    size_t g = ((size_t)256 << 20) / (((size_t)n << n) * sizeof(double));
+    if (g > 2048) g = 2048;
+    return rows < g ? rows : g;
+}
 
 __global__ void __launch_bounds__(HKP_THREADS)
 k_hk_path(const double *__restrict__ ghat, int n, const uint32_t *__restrict__ subsets, dtfm_layer_off lo,
@@ -198,7 +205,7 @@ dtfm_assign_bufs dtfm_assign_carve(const dtfm_problem *pr, dtfm_arena &ar, size_
     dtfm_assign_bufs b;
     const size_t n = pr->D_pp;
     b.ev = dtfm_eval_carve(pr, ar, rows);
-    const size_t grid = rows < HKP_GRID ? rows : HKP_GRID;
+    const size_t grid = hkp_grid(pr->D_pp, rows);
     b.tab = ar.take<double>(grid * (n << n));
     b.mates = ar.take<int32_t>(rows * (n > 1 ? n - 1 : 1) * (size_t)pr->D_dp);
     return b;
@@ -211,7 +218,7 @@ int dtfm_assign_enqueue(const dtfm_problem *pr, const dtfm_assign_bufs &b, const
     const int n = pr->D_pp, D = pr->D_dp, N = pr->N;
     int rc = dtfm_eval_enqueue(pr, b.ev, perm, rows, nullptr, st);   // coarsened graphs only
     if (rc != DTFM_OK) return rc;
-    const size_t grid = rows < HKP_GRID ? rows : HKP_GRID;
+    const size_t grid = hkp_grid(n, rows);
     hipLaunchKernelGGL(k_hk_path, dim3((unsigned)grid), dim3(HKP_THREADS), 0, st, b.ev.ghat, n, pr->hk_subsets,
                        pr->hk_off, b.tab, stage_order, rows);
     DTFM_HIP(hipGetLastError());

@@ -143,6 +143,14 @@ def test_evolve_config1():
     _evolve_parity(w, 4, 5, 9, lam=4, m_x=3, m_m=2, ls_moves=0)
 
 
+def test_evolve_steady_state_lambda_one():
+    # the paper's loop: one offspring per generation, inserted iff better than the worst
+    _evolve_parity(workloads.config("C1"), 11, 40, 7, lam=1, m_x=2, m_m=1, ls_moves=2, neighbourhood=dtfm.GAIN4)
+    _evolve_parity(workloads.config("C2"), 3, 30, 12, lam=1, ls_moves=4, neighbourhood=dtfm.GAIN4)
+    _evolve_parity(workloads.config("C2"), 4, 5, 6, lam=1, ls_moves=1, neighbourhood=dtfm.ALL_PAIRS)
+    _evolve_parity(workloads.config("C2"), 5, 10, 20, lam=3, ls_moves=2, neighbourhood=dtfm.GAIN4)
+
+
 def test_evolve_config2_shape():
     w = workloads.config("C2")
     trace = _evolve_parity(w, 1, 6, 48, ls_moves=8, neighbourhood=dtfm.GAIN4)

@@ -248,3 +248,29 @@ def test_evolve_generation_is_select_cross_mutate_search_replace():
     # one-generation run from pop0 equals generation 0 of the cold run
     pop1w, cost1w, _ = pr.evolve(seed=seed, generations=1, P=P, m_x=2, m_m=1, ls_moves=3, population=pop0)
     assert np.array_equal(pop1w, pop1) and np.array_equal(cost1w, cost1)
+
+
+def test_evolve_steady_state_is_insert_and_drop_worst():
+    # lambda = 1 is the paper's loop (Sec. 3.4): two random parents -> offspring -> local search ->
+    # "add o*, remove the worst if o* is better". Re-composed here from the oracle's parts with the
+    # replacement written as that sentence, generation by generation.
+    w, pr = _problem("C1")
+    P, seed, G = 7, 11, 25
+    kw = dict(lam=1, m_x=2, m_m=1, ls_moves=2, neighbourhood=oracle.GAIN4)
+    pop, cost, _ = pr.evolve(seed=seed, generations=0, P=P, **kw)
+    inserted = 0
+    for g in range(G):
+        child = oracle.make_offspring(seed, g, 0, pop, 2, 2, 1)[0]
+        child, ccost, _ = pr.local_search(child[None, :], 2, oracle.GAIN4)
+        # incumbents in (cost, position) order; the worst is the last of them
+        order = np.lexsort((np.arange(P), cost))
+        pop, cost = pop[order], cost[order]
+        if ccost[0] < cost[-1]:
+            at = int(np.searchsorted(cost, ccost[0], side="right"))     # behind incumbents of equal cost
+            pop = np.concatenate([pop[:at], child, pop[at:-1]])
+            cost = np.concatenate([cost[:at], ccost, cost[at:-1]])
+            inserted += 1
+        want_pop, want_cost, trace = pr.evolve(seed=seed, generations=g + 1, P=P, **kw)
+        assert np.array_equal(pop, want_pop) and np.array_equal(cost, want_cost)
+        assert trace[-1] == cost[0]
+    assert 0 < inserted < G      # both branches of the rule were exercised
