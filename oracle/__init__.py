@@ -20,6 +20,7 @@ _LIB = os.path.join(_HERE, "libdtfm_oracle.so")
 
 ALL_PAIRS = 0
 GAIN4 = 1
+KL = 2
 
 
 def build(force: bool = False) -> str:
@@ -69,6 +70,7 @@ def lib():
         L.orc_lexmin_matching.restype = c_int
         L.orc_get_assignment.argtypes = [dp, c_int, c_int, c_int, ip, ip, ip]
         L.orc_gain4_propose.argtypes = [dp, c_int, c_int, c_int, ip, c_int, ip, ip, dp]
+        L.orc_kl_propose.argtypes = [dp, c_int, c_int, c_int, ip, c_int, ip, ip, dp]
         L.orc_local_search.argtypes = [dp, dp, c_int, c_int, c_int, ip, c_int, c_int, c_int, dp, lp]
         L.orc_philox4x32_10.argtypes = [POINTER(c_uint32), POINTER(c_uint32), POINTER(c_uint32)]
         L.orc_draw_randint.argtypes = [c_uint64, c_uint32, c_uint32, c_uint32, c_uint32, c_uint32]
@@ -150,6 +152,15 @@ class Problem:
         gains = np.empty(4)
         lib().orc_gain4_propose(self._w()[1], self.N, self.D_dp, self.D_pp, pp, r,
                                 ctypes.byref(a), ctypes.byref(b), gains.ctypes.data_as(POINTER(c_double)))
+        return a.value, b.value, gains
+
+    def kl_propose(self, perm, r):
+        """(position a, position b, gain_KL of all D_dp x D_dp swaps) for round r."""
+        perm, pp = _i(perm)
+        a, b = c_int(), c_int()
+        gains = np.empty((self.D_dp, self.D_dp))
+        lib().orc_kl_propose(self._w()[1], self.N, self.D_dp, self.D_pp, pp, r,
+                             ctypes.byref(a), ctypes.byref(b), gains.ctypes.data_as(POINTER(c_double)))
         return a.value, b.value, gains
 
     def local_search(self, perms, rounds, neighbourhood):

@@ -31,6 +31,10 @@
  *                               none): pinned as implementing those rules by enumeration of all
  *                               tours and all matchings on tiny cases, by the closed form on a
  *                               homogeneous network, and by re-deriving the cost from the output
+ *   orc_local_search KL         gain_KL formula pinned by hand computation and by its textbook
+ *                               meaning (change of the cut weight between the two groups); the
+ *                               round schedule and acceptance rule are shared with GAIN4 and are
+ *                               this build's reading: parity unpinned beyond invariants
  *   orc_philox4x32_10           pinned: published known-answer vectors
  *   orc_evolve                  invariants only (valid permutations, elitism, determinism);
  *                               the GA operators are this build's reading: parity unpinned
@@ -42,6 +46,7 @@
 
 #define ORC_ALL_PAIRS 0
 #define ORC_GAIN4 1
+#define ORC_KL 2
 
 /* ------------------------------------------------------------------------------------------ */
 /* Sec. 2: communication graph G. Each edge carries the average of the two directions.         */
@@ -400,6 +405,10 @@ void orc_get_assignment(const double *W_pp, int N, int D_dp, int D_pp, const int
  * ALL_PAIRS: every position pair a < b, in lexicographic order, is a move; the move with the
  * lowest resulting cost is chosen, the first such on ties.
  *
+ * KL (the strategy the paper compares against, Sec. 3.4 "Existing Local Search Strategy"): same
+ * stage pair per round as GAIN4; the swap of largest gain_KL among all D_dp^2 swaps between the
+ * two stages is the round's single move (see orc_kl_propose).
+ *
  * GAIN4 (the paper's neighbourhood, Sec. 3.4 "Improving Local Search Strategy"): round r looks
  * at stage pair number r mod (D_pp (D_pp-1)/2) in lexicographic (j < j') order. (d1,d2) is the
  * fastest link inside C_j (smallest W_pp over slot pairs i < i', first on ties), (d1',d2') the
@@ -465,6 +474,53 @@ void orc_gain4_propose(const double *W_pp, int N, int D_dp, int D_pp, const int 
     *pos_b = jp * D_dp + sp[bk % 2];
 }
 
+/* The Kernighan-Lin gain the paper quotes as the existing strategy (Sec. 3.4, "Existing Local
+ * Search Strategy"), with w = W_pp, for swapping x (slot sx of C_j) with y (slot sy of C_j'):
+ *   gain_KL = sum_{d'' in C_j'} w[x][d''] - sum_{d'' in C_j - {x}} w[x][d'']
+ *           + sum_{d'' in C_j} w[y][d''] - sum_{d'' in C_j' - {y}} w[y][d''] - 2 w[x][y]
+ * Each sum runs in slot order from +0.0; the five terms are combined left to right. */
+static double gain_kl(const double *W_pp, int N, int D_dp, const int *Cj, const int *Cjp, int sx, int sy)
+{
+    int x = Cj[sx], y = Cjp[sy];
+    double s1 = 0.0, s2 = 0.0, s3 = 0.0, s4 = 0.0;
+    for (int i = 0; i < D_dp; i++) s1 += W_pp[x * N + Cjp[i]];
+    for (int i = 0; i < D_dp; i++) if (i != sx) s2 += W_pp[x * N + Cj[i]];
+    for (int i = 0; i < D_dp; i++) s3 += W_pp[y * N + Cj[i]];
+    for (int i = 0; i < D_dp; i++) if (i != sy) s4 += W_pp[y * N + Cjp[i]];
+    double g = s1 - s2;
+    g = g + s3;
+    g = g - s4;
+    g = g - 2.0 * W_pp[x * N + y];
+    return g;
+}
+
+/* KL neighbourhood, for the paper's ablation ("ours vs. Kernighan-Lin gain"): round r looks at the
+ * same stage pair as GAIN4 does and proposes, among all D_dp^2 swaps between the two stages, the
+ * one of largest gain_KL (the first in (slot of C_j, slot of C_j') order on ties). gains, if not
+ * NULL, receives all D_dp^2 values. */
+void orc_kl_propose(const double *W_pp, int N, int D_dp, int D_pp, const int *perm, int r,
+                    int *pos_a, int *pos_b, double *gains)
+{
+    int npairs = D_pp * (D_pp - 1) / 2;
+    int t = r % npairs, j = 0, jp = 1, cnt = 0;
+    for (int a = 0; a < D_pp; a++)
+        for (int b = a + 1; b < D_pp; b++) {
+            if (cnt == t) { j = a; jp = b; }
+            cnt++;
+        }
+    const int *Cj = perm + j * D_dp, *Cjp = perm + jp * D_dp;
+    double bestg = 0.0;
+    int bx = -1, by = -1;
+    for (int sx = 0; sx < D_dp; sx++)
+        for (int sy = 0; sy < D_dp; sy++) {
+            double g = gain_kl(W_pp, N, D_dp, Cj, Cjp, sx, sy);
+            if (gains) gains[sx * D_dp + sy] = g;
+            if (bx < 0 || g > bestg) { bestg = g; bx = sx; by = sy; }
+        }
+    *pos_a = j * D_dp + bx;
+    *pos_b = jp * D_dp + by;
+}
+
 /* move index <-> position pair for ALL_PAIRS: (0,1),(0,2),...,(0,N-1),(1,2),... */
 static long pair_index(int N, int a, int b)
 {
@@ -492,7 +548,8 @@ void orc_local_search(const double *W_dp, const double *W_pp, int N, int D_dp, i
                         if (c < bc) { bc = c; ba = a; bb = b; }
                     }
             } else {
-                orc_gain4_propose(W_pp, N, D_dp, D_pp, x, r, &ba, &bb, NULL);
+                if (neighbourhood == ORC_KL) orc_kl_propose(W_pp, N, D_dp, D_pp, x, r, &ba, &bb, NULL);
+                else orc_gain4_propose(W_pp, N, D_dp, D_pp, x, r, &ba, &bb, NULL);
                 int t = x[ba]; x[ba] = x[bb]; x[bb] = t;
                 bc = orc_comm_cost(W_dp, W_pp, N, D_dp, D_pp, x, 0);
                 t = x[ba]; x[ba] = x[bb]; x[bb] = t;

@@ -12,6 +12,7 @@ _LIB_PATH = os.path.join(_PKG, "libdtfm.so")
 
 ALL_PAIRS = 0
 GAIN4 = 1
+KL = 2
 
 # every entry point include/dtfm.h declares
 DECLARED_SYMBOLS = [

@@ -184,7 +184,74 @@ __global__ void k_gain4_propose(const double *__restrict__ W_pp, const int32_t *
     }
 }
 
-// GAIN4: accept the proposed swap iff its cost is strictly lower.
+// KL neighbourhood (Sec. 3.4 "Existing Local Search Strategy", the strategy the paper compares with):
+// one wavefront per candidate; round r looks at the same stage pair as the four-candidate
+// neighbourhood and proposes, among all D_dp^2 swaps between the two stages, the one of largest
+//   gain_KL = sum_{C_j'} w[x][.] - sum_{C_j - x} w[x][.] + sum_{C_j} w[y][.] - sum_{C_j' - y} w[y][.] - 2 w[x][y]
+// (w = W_pp; each sum in slot order from +0.0, the five terms combined left to right; the first
+// maximiser in (slot of C_j, slot of C_j') order wins). Writes the swapped allocation and the positions.
+__global__ void k_kl_propose(const double *__restrict__ W_pp, const int32_t *__restrict__ perm, int N,
+                             int D_dp, int D_pp, int r, int32_t *__restrict__ tmp_perm,
+                             int32_t *__restrict__ move_ab)
+{
+    __shared__ double S[4][DTFM_MAX_DDP];   // the four sums per slot: [0],[1] for x = C_j[slot]; [2],[3] for y = C_j'[slot]
+    const int lane = threadIdx.x;
+    size_t p = blockIdx.x;
+    int npairs = D_pp * (D_pp - 1) / 2;
+    int j, jp;
+    pair_decode(D_pp, r % npairs, j, jp);
+    const int32_t *row = perm + p * N;
+    const int32_t *Cj = row + j * D_dp, *Cjp = row + jp * D_dp;
+    if (lane < D_dp) {
+        const double *wx = W_pp + (size_t)Cj[lane] * N, *wy = W_pp + (size_t)Cjp[lane] * N;
+        double s1 = 0.0, s2 = 0.0, s3 = 0.0, s4 = 0.0;
+        for (int i = 0; i < D_dp; i++) s1 = __dadd_rn(s1, wx[Cjp[i]]);
+        for (int i = 0; i < D_dp; i++)
+            if (i != lane) s2 = __dadd_rn(s2, wx[Cj[i]]);
+        for (int i = 0; i < D_dp; i++) s3 = __dadd_rn(s3, wy[Cj[i]]);
+        for (int i = 0; i < D_dp; i++)
+            if (i != lane) s4 = __dadd_rn(s4, wy[Cjp[i]]);
+        S[0][lane] = s1;
+        S[1][lane] = s2;
+        S[2][lane] = s3;
+        S[3][lane] = s4;
+    }
+    __syncthreads();
+    double bestg = 0.0;
+    int be = -1;
+    for (int e = lane; e < D_dp * D_dp; e += DTFM_WAVE) {   // e = sx * D_dp + sy, increasing per lane
+        const int sx = e / D_dp, sy = e - sx * D_dp;
+        double g = __dadd_rn(S[0][sx], -S[1][sx]);
+        g = __dadd_rn(g, S[2][sy]);
+        g = __dadd_rn(g, -S[3][sy]);
+        g = __dadd_rn(g, -__dmul_rn(2.0, W_pp[(size_t)Cj[sx] * N + Cjp[sy]]));
+        if (be < 0 || g > bestg) {
+            bestg = g;
+            be = e;
+        }
+    }
+    for (int o = 32; o >= 1; o >>= 1) {
+        const double og = __shfl_xor(bestg, o);
+        const int oe = __shfl_xor(be, o);
+        if (oe >= 0 && (be < 0 || og > bestg || (og == bestg && oe < be))) {
+            bestg = og;
+            be = oe;
+        }
+    }
+    if (be < 0) be = 0;   // only on malformed (NaN) weights
+    const int a = j * D_dp + be / D_dp, b = jp * D_dp + be % D_dp;
+    int32_t *dst = tmp_perm + p * N;
+    for (int q = lane; q < N; q += DTFM_WAVE) {
+        int s = q == a ? b : (q == b ? a : q);
+        dst[q] = row[s];
+    }
+    if (lane == 0) {
+        move_ab[2 * p] = a;
+        move_ab[2 * p + 1] = b;
+    }
+}
+
+// GAIN4 and KL: accept the proposed swap iff its cost is strictly lower.
 __global__ void k_accept(int32_t *__restrict__ perm, int N, const double *__restrict__ tmp_cost,
                          double *__restrict__ cur, const int32_t *__restrict__ move_ab,
                          int64_t *__restrict__ applied, int moves, int r, size_t P)
@@ -278,8 +345,8 @@ int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm
                 DTFM_HIP(hipGetLastError());
             }
         } else {
-            hipLaunchKernelGGL(k_gain4_propose, dim3((unsigned)P), dim3(DTFM_WAVE), 0, st, pr->W_pp, perm, N,
-                               pr->D_dp, pr->D_pp, r, b.tmp_perm, b.move_ab);
+            hipLaunchKernelGGL(neighbourhood == DTFM_KL ? k_kl_propose : k_gain4_propose, dim3((unsigned)P),
+                               dim3(DTFM_WAVE), 0, st, pr->W_pp, perm, N, pr->D_dp, pr->D_pp, r, b.tmp_perm, b.move_ab);
             DTFM_HIP(hipGetLastError());
             rc = dtfm_eval_enqueue(pr, b.ev, b.tmp_perm, P, b.tmp_cost, st);
             if (rc != DTFM_OK) return rc;

@@ -101,6 +101,22 @@ def test_gain4_odd_shapes(D_dp, D_pp):
     _ls_parity(custom(N, D_dp, D_pp, seed=N), workloads.random_population(20, N, seed=4), 12, dtfm.GAIN4)
 
 
+@pytest.mark.parametrize("name,P,rounds", [("C1", 40, 14), ("C2", 64, 30), ("C2b", 24, 30), ("C3h", 8, 5)])
+def test_kl_neighbourhood_parity(name, P, rounds):
+    w = workloads.config(name)
+    _ls_parity(w, workloads.random_population(P, w.N, seed=8), rounds, dtfm.KL)
+
+
+@pytest.mark.parametrize("D_dp,D_pp", [(1, 2), (2, 2), (3, 5), (2, 7), (9, 2), (64, 2), (16, 16)])
+def test_kl_odd_shapes(D_dp, D_pp):
+    N = D_dp * D_pp
+    _ls_parity(custom(N, D_dp, D_pp, seed=N), workloads.random_population(5, N, seed=4), 4, dtfm.KL)
+
+
+def test_kl_in_evolve():
+    _evolve_parity(workloads.config("C2"), 2, 4, 24, ls_moves=5, neighbourhood=dtfm.KL)
+
+
 def test_zero_moves_is_plain_evaluation():
     w = workloads.config("C2")
     o, g = both(w)

@@ -160,6 +160,74 @@ def test_gain4_local_search_invariants():
         assert np.array_equal(q, out[p]) and c == cost[p]
 
 
+# ---------------------------------------------------------------- KL (the paper's comparison strategy)
+def test_kl_gain_is_the_drop_in_cut_weight():
+    # textbook meaning of the Kernighan-Lin gain: swapping x in A with y in B lowers the weight of the
+    # cut between A and B by exactly gain(x, y). Checked against cuts summed independently.
+    lat, bw = workloads.network_iid(15, seed=8)
+    pr = oracle.Problem(lat, bw, 9e7, 6e6, 5, 3)
+    W = pr.W_pp
+    rng = np.random.default_rng(1)
+    pairs = [(0, 1), (0, 2), (1, 2)]
+
+    def cut(A, B):
+        return sum(W[a, b] for a in A for b in B)
+    for r in range(9):
+        perm = rng.permutation(15).astype(np.int32)
+        j, jp = pairs[r % 3]
+        A, B = list(perm[5 * j:5 * j + 5]), list(perm[5 * jp:5 * jp + 5])
+        a, b, gains = pr.kl_propose(perm, r)
+        want = np.empty((5, 5))
+        for sx in range(5):
+            for sy in range(5):
+                A2, B2 = A.copy(), B.copy()
+                A2[sx], B2[sy] = B[sy], A[sx]
+                want[sx, sy] = cut(A, B) - cut(A2, B2)
+        assert np.allclose(gains, want, rtol=0, atol=1e-12 * cut(A, B))
+        sx, sy = divmod(int(np.argmax(gains)), 5)          # first maximiser in (slot, slot') order
+        assert (a, b) == (5 * j + sx, 5 * jp + sy)
+
+
+def test_kl_gain_hand_values_on_a_tiny_case():
+    # 4 devices, two stages of two; weights chosen by hand (W = 2 * latency when sizes are zero)
+    lat = np.array([[0, 1, 4, 6], [1, 0, 3, 5], [4, 3, 0, 2], [6, 5, 2, 0]], dtype=np.float64) / 2
+    pr = oracle.Problem(lat, np.ones((4, 4)), 0.0, 0.0, 2, 2)
+    assert np.array_equal(pr.W_pp, 2 * lat)
+    _, _, g = pr.kl_propose(np.arange(4, dtype=np.int32), 0)
+    # x=0,y=2: (4+6) - 1 + (4+3) - 2 - 2*4 = 6;  x=0,y=3: 10 - 1 + 11 - 2 - 12 = 6
+    # x=1,y=2: (3+5) - 1 + 7 - 2 - 6 = 6;         x=1,y=3: 8 - 1 + 11 - 2 - 10 = 6
+    assert np.array_equal(g, np.full((2, 2), 6.0))
+    lat[0, 2] = lat[2, 0] = 0.5                       # w[0][2] = 1
+    pr = oracle.Problem(lat, np.ones((4, 4)), 0.0, 0.0, 2, 2)
+    a, b, g = pr.kl_propose(np.arange(4, dtype=np.int32), 0)
+    # x=0,y=2: (1+6) - 1 + (1+3) - 2 - 2 = 6; x=0,y=3: 7 - 1 + 11 - 2 - 12 = 3; x=1,y=2: 8 - 1 + 4 - 2 - 6 = 3
+    assert np.array_equal(g, [[6.0, 3.0], [3.0, 6.0]]) and (a, b) == (0, 2)
+
+
+def test_kl_local_search_invariants():
+    w, pr = _problem("C2")
+    perms = workloads.random_population(8, 64, seed=6)
+    c0 = pr.eval_population(perms)
+    out, cost, applied = pr.local_search(perms, 30, oracle.KL)
+    assert np.all(np.sort(out, axis=1) == np.arange(64))
+    assert np.array_equal(cost, pr.eval_population(out))
+    assert np.all(cost <= c0)
+    moves = [(a, b) for a in range(64) for b in range(a + 1, 64)]
+    for p in range(8):
+        q, c = perms[p].copy(), c0[p]
+        for r in range(30):
+            a, b, _ = pr.kl_propose(q, r)
+            q2 = q.copy()
+            q2[a], q2[b] = q2[b], q2[a]
+            c2 = pr.comm_cost(q2)
+            if applied[p, r] >= 0:
+                assert moves[applied[p, r]] == (a, b) and c2 < c
+                q, c = q2, c2
+            else:
+                assert c2 >= c
+        assert np.array_equal(q, out[p]) and c == cost[p]
+
+
 # ---------------------------------------------------------------- Philox
 def test_philox_known_answers():
     n = 0
