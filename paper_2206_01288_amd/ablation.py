@@ -1,0 +1,74 @@
+"""Search ablations in the style of the paper's scheduler study (Sec. 4.3, Figure 4):
+
+    python -m paper_2206_01288_amd.ablation [--network C2b] [--budget 600000] [--seeds 0 1 2]
+
+Runs the evolutionary search on one GPU with the paper's four-candidate local search (GAIN4), with
+the Kernighan-Lin gain (KL), with no local search, and in steady-state mode (one offspring per
+generation, the paper's loop), every variant with the same budget of cost evaluations (or, with
+--offspring, the same number of offspring), and prints
+the best estimated cost (seconds) each reaches per seed, next to the mean cost of random
+allocations. The figure's own values are not printed in the paper; only the ordering can be compared.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+import workloads  # noqa: E402
+
+
+def main():
+    import torch
+    import paper_2206_01288_amd as dtfm
+
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--network", default="C2b")
+    ap.add_argument("--budget", type=int, default=600000, help="cost evaluations per run")
+    ap.add_argument("--offspring", type=int, default=0,
+                    help="if > 0: give every variant this many offspring instead of an equal evaluation budget")
+    ap.add_argument("--population", type=int, default=256)
+    ap.add_argument("--ls-moves", type=int, default=8)
+    ap.add_argument("--seeds", type=int, nargs="+", default=[0, 1, 2])
+    args = ap.parse_args()
+
+    w = workloads.config(args.network)
+    prob = dtfm.create_problem(w.latency, w.bandwidth, w.c_dp, w.c_pp, w.D_dp, w.D_pp)
+    P, m = args.population, args.ls_moves
+    rand = dtfm.eval_population(prob, torch.from_numpy(workloads.random_population(4096, w.N, seed=99)).cuda())
+    out = {"network": args.network, "budget_evaluations": args.budget if args.offspring <= 0 else None,
+           "offspring_per_run": args.offspring if args.offspring > 0 else None, "population": P, "ls_moves": m,
+           "random_allocation_mean_cost": float(rand.mean().item()), "random_allocation_best_of_4096": float(rand.min().item()),
+           "best_cost": {}}
+    variants = {
+        # name: (lambda, ls_moves, neighbourhood)
+        "gain4 (paper's local search)": (P, m, dtfm.GAIN4),
+        "kl gain": (P, m, dtfm.KL),
+        "no local search": (P, 0, dtfm.GAIN4),
+        "gain4, steady state (lambda=1)": (1, m, dtfm.GAIN4),
+    }
+    for name, (lam, moves, nb) in variants.items():
+        per_gen = lam * (1 + moves)
+        gens = max(1, (args.budget - P) // per_gen) if args.offspring <= 0 else max(1, args.offspring // lam)
+        res, secs = [], []
+        for seed in args.seeds:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            _, cost, trace = dtfm.evolve(prob, seed, gens, P, lam=lam, ls_moves=moves, neighbourhood=nb)
+            torch.cuda.synchronize()
+            secs.append(time.perf_counter() - t0)
+            res.append(float(trace[-1].item()))
+        out["best_cost"][name] = {"generations": gens, "per_seed": res, "mean": float(np.mean(res)),
+                                  "seconds_per_run": float(np.mean(secs))}
+        print("%-32s generations %7d  %.2f s/run  best cost per seed %s"
+              % (name, gens, np.mean(secs), " ".join("%.4f" % r for r in res)), flush=True)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
