@@ -69,6 +69,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--roofline-only", action="store_true",
                     help="only the population-evaluation launches plus one 1 GiB device copy (for rocprofv3 runs)")
+    ap.add_argument("--general-shapes", action="store_true",
+                    help="only population evaluations at configurations C4 and C5 (for rocprofv3 runs of the "
+                         "general-shape kernels)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (candidates are independent; see DESIGN.md "
@@ -82,6 +85,24 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dtfm.load_library()  # fails loudly when the HIP library is not built
+
+    if args.general_shapes:
+        res = {}
+        for name, Pg in (("C4", 1024), ("C5", 4096)):
+            wg = workloads.config(name)
+            pg = dtfm.create_problem(wg.latency, wg.bandwidth, wg.c_dp, wg.c_pp, wg.D_dp, wg.D_pp)
+            perms = torch.from_numpy(workloads.random_population(Pg, wg.N, seed=1)).cuda()
+            out = torch.empty(Pg, dtype=torch.float64, device="cuda")
+            dtfm.eval_population(pg, perms, out)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                dtfm.eval_population(pg, perms, out)
+            torch.cuda.synchronize()
+            res[name] = {"population": Pg, "ms_per_eval_population": (time.perf_counter() - t0) / 3 * 1e3}
+            dtfm.destroy_problem(pg)
+        print(json.dumps({"general_shapes": res}))
+        return
 
     w = workloads.config("C2")
     P, N = w.P, w.N
