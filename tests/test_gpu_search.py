@@ -187,3 +187,47 @@ def test_evolve_warm_start_and_determinism():
     assert np.array_equal(host(pop), rp) and np.array_equal(host(trace), rt)
     pop2, cost2, trace2 = dtfm.evolve(g, 5, 3, 24, ls_moves=4, population=dev(pop0))
     assert torch.equal(pop, pop2) and torch.equal(cost, cost2) and torch.equal(trace, trace2)
+
+
+# ---------------------------------------------------------------- the configurations at full size
+def test_config3_full_size_twenty_rounds():
+    # 4096 candidates x 20 rounds x 2016 moves on the GPU; what the oracle can do in seconds is compared
+    # on sampled candidates (candidates do not interact), the rest by properties that hold at any size
+    w = workloads.config("C3")
+    o, g = both(w)
+    perms = workloads.random_population(4096, 64, seed=1)
+    d = dev(perms)
+    c0 = host(dtfm.eval_population(g, d))
+    cost, applied = dtfm.local_search(g, d, 20, dtfm.ALL_PAIRS, want_applied=True)
+    out, cost, applied = host(d), host(cost), host(applied)
+    assert np.array_equal(np.sort(out, axis=1), np.tile(np.arange(64, dtype=np.int32), (4096, 1)))
+    assert np.array_equal(cost, host(dtfm.eval_population(g, dev(out))))
+    assert np.all(cost <= c0) and np.all(cost[(applied >= 0).any(axis=1)] < c0[(applied >= 0).any(axis=1)])
+    moves = np.array([(a, b) for a in range(64) for b in range(a + 1, 64)])
+    replay = perms.copy()
+    rows = np.arange(4096)
+    for r in range(20):
+        m = applied[:, r]
+        on = m >= 0
+        a, b = moves[m[on], 0], moves[m[on], 1]
+        replay[rows[on], a], replay[rows[on], b] = replay[rows[on], b].copy(), replay[rows[on], a].copy()
+    assert np.array_equal(replay, out)
+    for p in (17, 3001):
+        rp, rc, ra = o.local_search(perms[p:p + 1], 20, oracle.ALL_PAIRS)
+        assert np.array_equal(out[p], rp[0]) and np.array_equal(applied[p], ra[0])
+        assert_costs_equal(cost[p:p + 1], rc)
+
+
+def test_config5_full_size_generations():
+    # the search of configuration 5 at its population (fewer generations than its 100): properties on
+    # everything, oracle costs on sampled survivors
+    w = workloads.config("C5")
+    o, g = both(w)
+    pop, cost, trace = dtfm.evolve(g, 7, 4, 4096, ls_moves=8, neighbourhood=dtfm.GAIN4)
+    pop, cost, trace = host(pop), host(cost), host(trace)
+    assert np.array_equal(np.sort(pop, axis=1), np.tile(np.arange(1024, dtype=np.int32), (4096, 1)))
+    assert np.all(np.diff(cost) >= 0) and np.all(np.diff(trace) <= 0) and trace[-1] == cost[0]
+    idx = [0, 1500, 4095]
+    assert_costs_equal(cost[idx], o.eval_population(pop[idx]))
+    rand = o.eval_population(workloads.random_population(3, 1024, seed=1))
+    assert cost[0] < rand.min()
