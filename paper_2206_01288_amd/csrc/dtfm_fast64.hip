@@ -1,5 +1,6 @@
 // Fused population-evaluation kernel for the 64-device shape (N = 64, D_dp = 8, D_pp = 8): one
-// wavefront evaluates four candidates end to end (Eqs. 1-4).
+// wavefront evaluates eight candidates end to end (Eqs. 1-4); apart from the table gathers the whole
+// evaluation is register arithmetic.
 //
 //   Matching (Eq. 3)   The bottleneck value of a block depends only on the ORDER of its entries,
 //                      so the kernel works on 16-bit ranks of W_pp (rank table in LDS, built once
@@ -7,32 +8,34 @@
 //                      bit-identical to working on the doubles. Per stage pair a min-max dynamic
 //                      programme over column subsets, row by row:
 //                          g[S] = min_{c in S} max(g[S \ c], w[|S|-1][c]),   g[all] = optimum.
-//                      Lane = (candidate 0..3, couple of stage pairs 0..13): two pairs packed in
-//                      one 32-bit register, 16-bit packed max/min. Every lane walks the subsets in
-//                      the same order, so the whole table lives in registers with compile-time
-//                      indices: no table traffic, no index arithmetic, 2 ALU ops per transition.
-//   Held-Karp (Eq. 4)  two candidates at a time, their fp64 values side by side in 128-bit LDS
-//                      entries; one lane per (S, v) item, layers of equal |S| kept in two
-//                      alternating compact buffers. Which item a lane owns in each step, and the
-//                      byte offsets of the entries it reads, are fixed: they come from a table built
-//                      once (LDS-resident) whose slot assignment avoids LDS bank conflicts.
-//   DataP (Eq. 2)      lane = position; 8 gathers of W_dp (L2-resident 32 KiB table) summed in
-//                      slot order (the device's own slot adds the zero diagonal), wave max.
+//                      Lane = (candidate 0..3, couple of stage pairs 0..13), two passes for the eight
+//                      candidates: two pairs packed in one 32-bit register, 16-bit packed max/min.
+//                      Every lane walks the subsets in the same order, so the whole table lives in
+//                      registers with compile-time indices: no table traffic, no index arithmetic,
+//                      2 ALU ops per transition.
+//   Held-Karp (Eq. 4)  lane = (candidate 0..7, stage v 0..7). The stages are taken as the group
+//                      Z_2^3: item (S, v) with S = v xor ({0} u D) belongs to class D (a subset of
+//                      {1..7}), and lane v holds the items (class D, v) of ALL classes, one register
+//                      pair per class. The relaxation tab[S][v] = min_u tab[S \ v][u] + Ghat[u][v] with
+//                      u = v xor d reads class (D \ d) xor d at lane v xor d: a compile-time register
+//                      and a lane exchange within the 8 lanes of the candidate, done by data-parallel
+//                      primitive moves (xor 1, 2, 3: quad permutations; xor 7: mirror of the 8 lanes;
+//                      xor 4, 5, 6: mirror, then a quad permutation). No memory traffic at all.
+//   DataP (Eq. 2)      lane = (candidate, stage): the 8 x 8 entries of W_dp (LDS copy) of the stage's
+//                      devices summed in slot order (the device's own slot adds the zero diagonal),
+//                      max over the stage, then over the 8 lanes of the candidate.
 #include "dtfm_internal.h"
 
 #include <math.h>
 
-#include <mutex>
-#include <utility>
-#include <vector>
-
 namespace {
 
-constexpr int NDEV = 64, CANDS = 4;   // most candidates per wavefront pass (kernels are built for 4 and 2)
+constexpr int NDEV = 64;
 // Row stride of the rank table in LDS, in 16-bit entries. 66 instead of 64 skews consecutive rows by
 // one 4-byte bank, so that lanes reading the same column of different rows hit different banks.
 constexpr int RSTRIDE = 66;
 constexpr int BINOM8[9] = {1, 8, 28, 56, 70, 56, 28, 8, 1};
+constexpr int BINOM7[8] = {1, 7, 21, 35, 35, 21, 7, 1};
 
 // the subsets of {0..7} grouped by size: LAYER.s[k][i] = i-th subset with k elements, ascending
 struct layer_table {
@@ -53,36 +56,99 @@ constexpr layer_table make_layers()
 }
 constexpr layer_table LAYER = make_layers();
 
-constexpr int hk_steps(int k) { return (BINOM8[k] * k + 63) / 64; }    // 64-lane steps of layer k
-constexpr int hk_words4(int k) { return (k + 3) / 4; }                 // 128-bit table words per item
-constexpr int hk_tab_first(int k)                                       // first table word of layer k
+// Held-Karp classes: D as a bit mask over {1..7} (bit d set = d in D; bit 0 never set).
+// HKC.cls[j][i] = i-th class with j elements (ascending masks), HKC.idx[D] = its index i.
+struct hk_class_table {
+    unsigned char cls[8][35];
+    unsigned char idx[256];
+};
+constexpr hk_class_table make_hk_classes()
 {
-    int o = 0;
-    for (int i = 2; i < k; i++) o += hk_steps(i) * hk_words4(i);
-    return o;
+    hk_class_table t = {};
+    for (int j = 0; j <= 7; j++) {
+        int n = 0;
+        for (int D = 0; D < 256; D += 2) {
+            int pc = 0;
+            for (int b = 1; b < 8; b++) pc += (D >> b) & 1;
+            if (pc == j) {
+                t.cls[j][n] = (unsigned char)D;
+                t.idx[D] = (unsigned char)n;
+                n++;
+            }
+        }
+    }
+    return t;
 }
-constexpr int HK_TAB_WORDS4 = hk_tab_first(9);          // 29 (x 64 lanes x 16 B = 29696 B)
-constexpr int HK_BUF_ENTRIES = 5 * 64;                  // largest layer: 5 steps of 64 lanes
+constexpr hk_class_table HKC = make_hk_classes();
 
-// LDS: rank table and Held-Karp item table shared by the workgroup, then one slice per wavefront
-constexpr int LDS_RANK_BYTES = ((NDEV * RSTRIDE * 2 + 15) / 16) * 16;   // 8.25 KiB
-constexpr int LDS_HKTAB_BYTES = HK_TAB_WORDS4 * 64 * 16;           // 29 KiB
-constexpr int OFF_BUF0 = 0;                                        // double2 [320]: even layers
-constexpr int OFF_BUF1 = OFF_BUF0 + HK_BUF_ENTRIES * 16;           // double2 [320]: odd layers
-// Coarsened graphs, one 2 KiB block per candidate pair: double2 [u][16]: column s of row u holds
-// ghat[u][s % 8] (both candidates), so a lane of pass-lane s whose item ends in v = s % 8 always reads
-// its own column: the 16 lanes of a 128-bit read pass never share a bank group.
-constexpr int GHAT_PAIR_BYTES = 8 * 16 * 16;
-constexpr int OFF_GHAT = OFF_BUF1 + HK_BUF_ENTRIES * 16;
-constexpr int OFF_PB = OFF_GHAT + 2 * GHAT_PAIR_BYTES;             // u8 [4 candidates][64] perm, stage-major
-constexpr int OFF_PBCUR = OFF_PB + CANDS * 64;                     // u8 [4][64]: current rows (local search)
-constexpr int WAVE_LDS_BYTES = OFF_PBCUR + CANDS * 64;             // 14848
+// class reached from source class Ds by the relaxation through d (d not in Ds): (Ds xor d) u {d}
+constexpr int hk_dest_class(int Ds, int d)
+{
+    int out = 1 << d;
+    for (int e = 1; e < 8; e++)
+        if ((Ds >> e) & 1) out |= 1 << (e ^ d);
+    return out;
+}
+// source class of class D through d (d in D): (D \ d) xor d
+constexpr int hk_source_class(int D, int d)
+{
+    int out = 0;
+    for (int e = 1; e < 8; e++)
+        if (e != d && ((D >> e) & 1)) out |= 1 << (e ^ d);
+    return out;
+}
+// true when, walking the source classes of a layer in ascending index and d ascending within a source,
+// (source of D through d) is the first relaxation into D: it initialises D's register instead of
+// taking a min. (Two different d can have the same source class, e.g. D = {d, e} through d and e.)
+constexpr bool hk_first_into(int D, int d)
+{
+    const int mine = HKC.idx[hk_source_class(D, d)];
+    for (int e = 1; e < 8; e++) {
+        if (e == d || !((D >> e) & 1)) continue;
+        const int other = HKC.idx[hk_source_class(D, e)];
+        if (other < mine || (other == mine && e < d)) return false;
+    }
+    return true;
+}
+// The relaxation programme: HKP.step[J][s][d] for source class s of layer J - 1 and d = 1..7:
+// 0xFF when d is in the source class (no relaxation), else (index of the destination class in layer
+// J) | 0x80 when this relaxation is the first into its destination.
+struct hk_program {
+    unsigned char step[8][35][8];
+};
+constexpr hk_program make_hk_program()
+{
+    hk_program p = {};
+    for (int J = 1; J <= 7; J++)
+        for (int s = 0; s < BINOM7[J - 1]; s++)
+            for (int d = 1; d < 8; d++) {
+                const int Ds = HKC.cls[J - 1][s];
+                if ((Ds >> d) & 1) {
+                    p.step[J][s][d] = 0xFF;
+                    continue;
+                }
+                const int D = hk_dest_class(Ds, d);
+                p.step[J][s][d] = (unsigned char)(HKC.idx[D] | (hk_first_into(D, d) ? 0x80 : 0));
+            }
+    return p;
+}
+constexpr hk_program HKP = make_hk_program();
+
+// ---- LDS layout: three tables shared by the workgroup, then one slice per wavefront ----
+constexpr int MAXC = 8;                                                 // candidates per wavefront pass
+constexpr int LDS_RANK_BYTES = ((NDEV * RSTRIDE * 2 + 15) / 16) * 16;   // 8.25 KiB: u16 rank of W_pp
+constexpr int LDS_RVAL_BYTES = NDEV * NDEV * 8;                         // 32 KiB: rank -> weight
+constexpr int LDS_WDP_BYTES = NDEV * NDEV * 8;                          // 32 KiB: W_dp
+constexpr int OFF_PB = 0;                                // u8 [8 candidates][64]: rows under evaluation, stage-major
+constexpr int OFF_PBCUR = OFF_PB + MAXC * 64;            // u8 [8][64]: current rows (local search)
+// coarsened graphs, double [candidate][u][v] with rows padded to 9 and candidates to 73 entries
+constexpr int GH_ROW = 9, GH_CAND = 73;
+constexpr int OFF_GHAT = OFF_PBCUR + MAXC * 64;
+constexpr int WAVE_LDS_BYTES = ((OFF_GHAT + MAXC * GH_CAND * 8 + 15) / 16) * 16;
 constexpr int WAVES_PER_BLOCK = 8;
-constexpr int LDS_TOTAL = LDS_RANK_BYTES + LDS_HKTAB_BYTES + WAVES_PER_BLOCK * WAVE_LDS_BYTES;
+constexpr int LDS_TOTAL = LDS_RANK_BYTES + LDS_RVAL_BYTES + LDS_WDP_BYTES + WAVES_PER_BLOCK * WAVE_LDS_BYTES;
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) u32x4 lds_u32x4;   // explicitly LDS-qualified
 
 __device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b)
 {
@@ -105,93 +171,119 @@ __device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b)
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");  \
     } while (0)
 
-// One layer of Held-Karp for a pair of candidates: every lane owns (S, v) items with |S| = K.
-// Item table (128-bit words, lane-major): word 0 = byte offset of the item's own entry in this
-// layer's buffer | valid << 31; words 1..K-1 = one per predecessor u in S \ v:
-// (byte offset of tab[S \ v][u] in the previous layer's buffer) | (byte offset of ghat[u][v]) << 16.
-template <int K>
-__device__ __forceinline__ double2 hk_layer(unsigned char *wl, const unsigned char *hktab, uint32_t ghat_off,
-                                            int lane)
+// ---- lane exchanges inside the 8 lanes of a candidate (data-parallel primitive moves) ----
+constexpr int DPP_XOR1 = 0xB1;          // quad permutation [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;          // quad permutation [2,3,0,1]
+constexpr int DPP_XOR3 = 0x1B;          // quad permutation [3,2,1,0]
+constexpr int DPP_HALF_MIRROR = 0x141;  // lane i of every 8 takes lane 7 - i: xor 7
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double x)
 {
-    constexpr int PREV = (K & 1) ? OFF_BUF0 : OFF_BUF1, CUR = (K & 1) ? OFF_BUF1 : OFF_BUF0;
-    constexpr int STEPS = hk_steps(K), W4 = hk_words4(K);
-    // all item words of the layer first, then all reads and arithmetic, then all writes: with no
-    // store between the loads of different steps the compiler may overlap their LDS latencies
-    uint32_t word[STEPS][4 * W4];
+    const uint64_t b = __builtin_bit_cast(uint64_t, x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(double, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+// value of x at lane (lane xor d), d = 1, 2, 3, 7
+__device__ __forceinline__ double lane_xor_direct(double x, int d)
+{
+    switch (d) {
+    case 1: return dpp_move<DPP_XOR1>(x);
+    case 2: return dpp_move<DPP_XOR2>(x);
+    case 3: return dpp_move<DPP_XOR3>(x);
+    default: return dpp_move<DPP_HALF_MIRROR>(x);
+    }
+}
+
+// One layer of Held-Karp: classes with J elements from the classes with J - 1. Source-major order, so
+// that the mirrored copy of a source serves all its relaxations through d = 4, 5, 6.
+template <int J>
+__device__ __forceinline__ void hk_layer(const double (&prev)[35], double (&cur)[35], const double (&G)[8])
+{
 #pragma unroll
-    for (int s = 0; s < STEPS; s++)
+    for (int s = 0; s < BINOM7[J - 1]; s++) {
+        const double x = prev[s];
+        double xm = 0.0;
+        if (HKP.step[J][s][4] != 0xFF || HKP.step[J][s][5] != 0xFF || HKP.step[J][s][6] != 0xFF)
+            xm = dpp_move<DPP_HALF_MIRROR>(x);
 #pragma unroll
-        for (int i = 0; i < W4; i++) {
-            // volatile: keep this one dense 128-bit read per lane (the compiler would otherwise narrow
-            // it to the words actually used, which at a 16-byte lane stride conflicts heavily)
-            const u32x4 t = *(const volatile lds_u32x4 *)(hktab + ((hk_tab_first(K) + s * W4 + i) * 64 + lane) * 16);
-            word[s][4 * i + 0] = t.x;
-            word[s][4 * i + 1] = t.y;
-            word[s][4 * i + 2] = t.z;
-            word[s][4 * i + 3] = t.w;
-        }
-    double2 best[STEPS];
-#pragma unroll
-    for (int s = 0; s < STEPS; s++) {
-        best[s] = make_double2(INFINITY, INFINITY);
-#pragma unroll
-        for (int t = 1; t < K; t++) {
-            const double2 x = *reinterpret_cast<const double2 *>(wl + PREV + (word[s][t] & 0xFFFFu));
-            const double2 e = *reinterpret_cast<const double2 *>(wl + ghat_off + (word[s][t] >> 16));
-            best[s].x = fmin(best[s].x, __dadd_rn(x.x, e.x));
-            best[s].y = fmin(best[s].y, __dadd_rn(x.y, e.y));
+        for (int d = 1; d < 8; d++) {
+            const int step = HKP.step[J][s][d];
+            if (step == 0xFF) continue;
+            const int i = step & 0x7F;
+            // tab[S \ v][u] at u = v xor d, then + Ghat[u][v]
+            const double moved = (d >= 4 && d <= 6) ? lane_xor_direct(xm, d ^ 7) : lane_xor_direct(x, d);
+            const double t = __dadd_rn(moved, G[d]);
+            cur[i] = (step & 0x80) ? t : fmin(cur[i], t);
         }
     }
+}
+
+// Eq. 4 for the candidate of this lane's 8-lane group; G[d] = Ghat[v][v xor d] of the lane's stage v.
+// Every lane of the group returns the optimum.
+__device__ __forceinline__ double hk_registers(const double (&G)[8])
+{
+    double a[35], b[35];
+    // one stage: 0; two stages {v, v xor d}: 0 + Ghat
 #pragma unroll
-    for (int s = 0; s < STEPS; s++) {
-        if (word[s][0] >> 31) *reinterpret_cast<double2 *>(wl + CUR + (word[s][0] & 0xFFFFu)) = best[s];
-        else best[s] = make_double2(INFINITY, INFINITY);
-    }
-    WAVE_LDS_SYNC();
-    return best[STEPS - 1];
+    for (int d = 1; d < 8; d++) b[HKC.idx[1 << d]] = G[d];
+    hk_layer<2>(b, a, G);
+    hk_layer<3>(a, b, G);
+    hk_layer<4>(b, a, G);
+    hk_layer<5>(a, b, G);
+    hk_layer<6>(b, a, G);
+    hk_layer<7>(a, b, G);
+    double pp = b[0];   // all eight stages, ending in v: min over v
+    pp = fmin(pp, dpp_move<DPP_XOR1>(pp));
+    pp = fmin(pp, dpp_move<DPP_XOR2>(pp));
+    pp = fmin(pp, dpp_move<DPP_HALF_MIRROR>(pp));
+    return pp;
 }
 
 // byte k (0..7) of a 64-bit value held as two dwords
 __device__ __forceinline__ uint32_t byte_of(uint2 v, int k) { return ((k < 4 ? v.x : v.y) >> (8 * (k & 3))) & 0xFFu; }
 
-// Per-wavefront context: LDS pointers and the lane's fixed role in the matching programme.
+// Per-wavefront context: LDS pointers and the lane's fixed roles.
 struct wave_ctx {
-    unsigned char *wl;            // this wavefront's LDS slice
-    const uint16_t *R;            // rank table (LDS)
-    const unsigned char *hktab;   // Held-Karp item table (LDS)
+    unsigned char *wl;       // this wavefront's LDS slice
+    const uint16_t *R;       // rank table (LDS)
+    const double *rank_val;  // rank -> weight (LDS)
+    const double *Wdp;       // W_dp (LDS)
     int lane;
-    int mc;                       // candidate slot 0..3 whose matchings this lane computes
-    bool couple_valid;            // lanes 14, 15 of each 16 repeat couple 13 and write nothing
-    int j1[2], j2[2];             // the lane's two stage pairs (j1 < j2)
+    int mslot;               // matching role: candidate slot 0..3 within a matching pass
+    bool couple_valid;       // lanes 14, 15 of each 16 repeat couple 13 and write nothing
+    int j1[2], j2[2];        // the lane's two stage pairs (j1 < j2)
+    int hc, hv;              // Held-Karp / DataP role: candidate slot, stage
 };
 
 // Loads the workgroup's tables into LDS and derives the lane roles. Ends with a workgroup barrier.
 template <int NC>
-__device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16_t *rank_tab, const uint32_t *step_tab)
+__device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16_t *rank_tab,
+                                               const double *rank_val, const double *W_dp)
 {
     wave_ctx cx;
     cx.lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     cx.R = reinterpret_cast<const uint16_t *>(smem);
-    cx.hktab = smem + LDS_RANK_BYTES;
-    cx.wl = smem + LDS_RANK_BYTES + LDS_HKTAB_BYTES + wave * WAVE_LDS_BYTES;
+    cx.rank_val = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES);
+    cx.Wdp = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES + LDS_RVAL_BYTES);
+    cx.wl = smem + LDS_RANK_BYTES + LDS_RVAL_BYTES + LDS_WDP_BYTES + wave * WAVE_LDS_BYTES;
     // rank table -> LDS, rows re-strided (two entries per thread per pass)
     for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
         const int row = i / (NDEV / 2), col2 = i - row * (NDEV / 2);
         reinterpret_cast<uint32_t *>(smem)[row * (RSTRIDE / 2) + col2] = reinterpret_cast<const uint32_t *>(rank_tab)[i];
     }
-    // Held-Karp item table -> LDS
-    for (int i = threadIdx.x; i < LDS_HKTAB_BYTES / 16; i += blockDim.x)
-        reinterpret_cast<uint4 *>(smem + LDS_RANK_BYTES)[i] = reinterpret_cast<const uint4 *>(step_tab)[i];
-    // zero diagonals of the four coarsened graphs (never overwritten): [pair][j][column j][cand & 1]
-    if (cx.lane < CANDS * 8)
-        *reinterpret_cast<double *>(cx.wl + OFF_GHAT + (cx.lane >> 4) * GHAT_PAIR_BYTES +
-                                    ((cx.lane & 7) * 16 + (cx.lane & 7)) * 16 + ((cx.lane >> 3) & 1) * 8) = 0.0;
+    for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
+        reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES)[i] = reinterpret_cast<const double2 *>(rank_val)[i];
+        reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES + LDS_RVAL_BYTES)[i] = reinterpret_cast<const double2 *>(W_dp)[i];
+    }
+    // zero diagonals of the eight coarsened graphs (never overwritten)
+    *reinterpret_cast<double *>(cx.wl + OFF_GHAT + ((cx.lane >> 3) * GH_CAND + (cx.lane & 7) * (GH_ROW + 1)) * 8) = 0.0;
     // matching role: candidate slot and the couple of stage pairs (2q, 2q+1) in lexicographic order
-    // (with NC = 2 the upper half of the wavefront repeats the lower half's work and writes nothing)
-    cx.mc = (cx.lane >> 4) % NC;
+    cx.mslot = cx.lane >> 4;
     const int q = (cx.lane & 15) < 14 ? (cx.lane & 15) : 13;
-    cx.couple_valid = (cx.lane & 15) < 14 && cx.lane < NC * 16;
+    cx.couple_valid = (cx.lane & 15) < 14;
 #pragma unroll
     for (int h = 0; h < 2; h++) {
         int t = 2 * q + h, a = 0;
@@ -202,193 +294,161 @@ __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16
         cx.j1[h] = a;
         cx.j2[h] = a + 1 + t;
     }
+    // with NC = 4 the upper half of the wavefront repeats the lower half's Held-Karp and DataP
+    cx.hc = (cx.lane >> 3) % NC;
+    cx.hv = cx.lane & 7;
     __syncthreads();
     return cx;
 }
 
-// Evaluates the NC (4 or 2) candidates whose rows are in the wavefront's LDS slice at OFF_PB (stage-major
-// bytes, already visible to all lanes); dev[c] = device at position `lane` of candidate c.
-// On return total[c] (Eq. 1) and datap[c] (Eq. 2 + max) are held by every lane. ghat_out, if not
-// null, receives the coarsened graphs of candidates cand0 .. cand0+3 that are < P.
-template <int NC>
-__device__ __forceinline__ void eval_quad(const wave_ctx &cx, const double *__restrict__ W_dp,
-                                          const double *__restrict__ rank_val, const int (&dev)[CANDS],
-                                          double (&total)[CANDS], double (&datap)[CANDS],
-                                          double *__restrict__ ghat_out, size_t cand0, size_t P)
+// a4 for one pass of four candidates: the bottleneck matchings of this lane's two stage pairs of the
+// candidate whose row is at pb, as two packed ranks.
+__device__ __forceinline__ uint32_t match_couple(const wave_ctx &cx, const unsigned char *pb)
 {
-    unsigned char *wl = cx.wl;
     const uint16_t *R = cx.R;
-    const int lane = cx.lane;
-    // ---- a4: bottleneck matchings of this lane's two stage pairs, as ranks ----
-    uint32_t gfull;
+    uint2 rowdev[2], coldev[2];
+    uint32_t coloff[2][8];
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        rowdev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * cx.j1[h]);   // devices of stage j1, slots 0..7
+        coldev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * cx.j2[h]);   // devices of stage j2
+#pragma unroll
+        for (int c = 0; c < 8; c++) coloff[h][c] = byte_of(coldev[h], c);
+    }
+    uint32_t G[256];
+    // rows are gathered one layer ahead of their use; the scheduling barriers keep the
+    // register footprint to two rows plus two layers of the table
+    uint32_t wnext[8];
     {
-        const unsigned char *pb = wl + OFF_PB + cx.mc * 64;
-        uint2 rowdev[2], coldev[2];
-        uint32_t coloff[2][8];
+        const uint32_t rb0 = byte_of(rowdev[0], 0) * RSTRIDE, rb1 = byte_of(rowdev[1], 0) * RSTRIDE;
 #pragma unroll
-        for (int h = 0; h < 2; h++) {
-            rowdev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * cx.j1[h]);   // devices of stage j1, slots 0..7
-            coldev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * cx.j2[h]);   // devices of stage j2
+        for (int c = 0; c < 8; c++)
+            wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
+    }
 #pragma unroll
-            for (int c = 0; c < 8; c++) coloff[h][c] = byte_of(coldev[h], c);
-        }
-        uint32_t G[256];
-        // rows are gathered one layer ahead of their use; the scheduling barriers keep the
-        // register footprint to two rows plus two layers of the table
-        uint32_t wnext[8];
-        {
-            const uint32_t rb0 = byte_of(rowdev[0], 0) * RSTRIDE, rb1 = byte_of(rowdev[1], 0) * RSTRIDE;
+    for (int r = 0; r < 8; r++) {
+        // row r of both blocks: w[c] = (rank of pair-0 entry (r,c)) | (rank of pair-1 entry) << 16
+        uint32_t w[8];
+#pragma unroll
+        for (int c = 0; c < 8; c++) w[c] = wnext[c];
+        if (r < 7) {
+            const uint32_t rb0 = byte_of(rowdev[0], r + 1) * RSTRIDE, rb1 = byte_of(rowdev[1], r + 1) * RSTRIDE;
 #pragma unroll
             for (int c = 0; c < 8; c++)
                 wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
         }
 #pragma unroll
-        for (int r = 0; r < 8; r++) {
-            // row r of both blocks: w[c] = (rank of pair-0 entry (r,c)) | (rank of pair-1 entry) << 16
-            uint32_t w[8];
+        for (int i = 0; i < BINOM8[r + 1]; i++) {
+            const int S = LAYER.s[r + 1][i];
+            uint32_t acc = 0;
+            bool first = true;
 #pragma unroll
-            for (int c = 0; c < 8; c++) w[c] = wnext[c];
-            if (r < 7) {
-                const uint32_t rb0 = byte_of(rowdev[0], r + 1) * RSTRIDE, rb1 = byte_of(rowdev[1], r + 1) * RSTRIDE;
-#pragma unroll
-                for (int c = 0; c < 8; c++)
-                    wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
+            for (int c = 0; c < 8; c++) {
+                if (!(S & (1 << c))) continue;
+                const uint32_t m = (r == 0) ? w[c] : pk_max(G[S ^ (1 << c)], w[c]);
+                acc = first ? m : pk_min(acc, m);
+                first = false;
             }
-#pragma unroll
-            for (int i = 0; i < BINOM8[r + 1]; i++) {
-                const int S = LAYER.s[r + 1][i];
-                uint32_t acc = 0;
-                bool first = true;
-#pragma unroll
-                for (int c = 0; c < 8; c++) {
-                    if (!(S & (1 << c))) continue;
-                    const uint32_t m = (r == 0) ? w[c] : pk_max(G[S ^ (1 << c)], w[c]);
-                    acc = first ? m : pk_min(acc, m);
-                    first = false;
-                }
-                G[S] = acc;
-            }
-            __builtin_amdgcn_sched_barrier(0);
+            G[S] = acc;
         }
-        gfull = G[255];
+        __builtin_amdgcn_sched_barrier(0);
     }
-    // ---- winning ranks -> fp64 weights -> coarsened graphs in LDS ----
-    {
-        const double e0 = rank_val[gfull & 0xFFFFu], e1 = rank_val[gfull >> 16];
-        if (cx.couple_valid) {   // entries [candidate pair][u][columns v and v + 8][candidate & 1]
-            double *gh = reinterpret_cast<double *>(wl + OFF_GHAT + (cx.mc >> 1) * GHAT_PAIR_BYTES) + (cx.mc & 1);
-#pragma unroll
-            for (int h = 0; h < 2; h++) {
-                const double e = h == 0 ? e0 : e1;
-                const int a = cx.j1[h], b = cx.j2[h];
-                gh[(a * 16 + b) * 2] = e;
-                gh[(a * 16 + b + 8) * 2] = e;
-                gh[(b * 16 + a) * 2] = e;
-                gh[(b * 16 + a + 8) * 2] = e;
-            }
+    return G[255];
+}
+
+// Evaluates the NC (8 or 4) candidates whose rows are in the wavefront's LDS slice at OFF_PB (stage-major
+// bytes, already visible to all lanes). On return every lane holds total (Eq. 1) and datap (Eq. 2 + max)
+// of candidate slot cx.hc. ghat_out, if not null, receives the coarsened graphs of candidates
+// cand0 .. cand0 + NC - 1 that are < P.
+template <int NC>
+__device__ __forceinline__ void eval_group(const wave_ctx &cx, double &total, double &datap,
+                                           double *__restrict__ ghat_out, size_t cand0, size_t P)
+{
+    unsigned char *wl = cx.wl;
+    const int lane = cx.lane;
+    double *gh = reinterpret_cast<double *>(wl + OFF_GHAT);
+    // ---- a4: matchings on ranks; winning ranks -> fp64 weights -> coarsened graphs in LDS ----
+#pragma nounroll
+    for (int pass = 0; pass < NC / 4; pass++) {
+        const int mc = 4 * pass + cx.mslot;
+        const uint32_t gfull = match_couple(cx, wl + OFF_PB + mc * 64);
+        const double e0 = cx.rank_val[gfull & 0xFFFFu], e1 = cx.rank_val[gfull >> 16];
+        if (cx.couple_valid) {
+            double *g = gh + mc * GH_CAND;
+            g[cx.j1[0] * GH_ROW + cx.j2[0]] = e0;
+            g[cx.j2[0] * GH_ROW + cx.j1[0]] = e0;
+            g[cx.j1[1] * GH_ROW + cx.j2[1]] = e1;
+            g[cx.j2[1] * GH_ROW + cx.j1[1]] = e1;
         }
     }
     WAVE_LDS_SYNC();
-
-    // ---- per candidate pair: a5 Held-Karp, a2/a3 DataP, a6 total ----
-#pragma nounroll
-    for (int pr = 0; pr < NC / 2; pr++) {
-        // DataP gathers first: their latency hides behind Held-Karp
-        double wv[2][8];
+    if (ghat_out != nullptr) {
 #pragma unroll
-        for (int h = 0; h < 2; h++) {
-            const int d = pr == 0 ? dev[h] : dev[2 + h];
-            const uint2 mates = *reinterpret_cast<const uint2 *>(wl + OFF_PB + (2 * pr + h) * 64 + (lane & ~7));
-            const double *wrow = W_dp + d * NDEV;
-#pragma unroll
-            for (int k = 0; k < 8; k++) wv[h][k] = wrow[byte_of(mates, k)];   // own slot: the zero diagonal
-        }
-        const uint32_t ghat_off = OFF_GHAT + pr * GHAT_PAIR_BYTES;
-        if (ghat_out != nullptr) {
-            const double2 g2 = *reinterpret_cast<const double2 *>(wl + ghat_off + ((lane >> 3) * 16 + (lane & 7)) * 16);
-            if (cand0 + 2 * pr < P) ghat_out[(cand0 + 2 * pr) * 64 + lane] = g2.x;
-            if (cand0 + 2 * pr + 1 < P) ghat_out[(cand0 + 2 * pr + 1) * 64 + lane] = g2.y;
-        }
-        // layer 1: tab[{v}][v] = 0, kept twice (entries v and v + 8 of the odd buffer)
-        if (lane < 16) *reinterpret_cast<double2 *>(wl + OFF_BUF1 + lane * 16) = make_double2(0.0, 0.0);
-        WAVE_LDS_SYNC();
-        hk_layer<2>(wl, cx.hktab, ghat_off, lane);
-        hk_layer<3>(wl, cx.hktab, ghat_off, lane);
-        hk_layer<4>(wl, cx.hktab, ghat_off, lane);
-        hk_layer<5>(wl, cx.hktab, ghat_off, lane);
-        hk_layer<6>(wl, cx.hktab, ghat_off, lane);
-        hk_layer<7>(wl, cx.hktab, ghat_off, lane);
-        // the 8 items of the last layer sit in lanes 0..7 (others hold +inf): PP = min over them
-        double2 pp = hk_layer<8>(wl, cx.hktab, ghat_off, lane);
-#pragma unroll
-        for (int o = 1; o <= 4; o <<= 1) {
-            pp.x = fmin(pp.x, __shfl_xor(pp.x, o));
-            pp.y = fmin(pp.y, __shfl_xor(pp.y, o));
-        }
-        pp.x = __shfl(pp.x, 0);
-        pp.y = __shfl(pp.y, 0);
-        double res[2], dpv[2];
-#pragma unroll
-        for (int h = 0; h < 2; h++) {
-            double sum = 0.0;
-#pragma unroll
-            for (int k = 0; k < 8; k++) sum = __dadd_rn(sum, wv[h][k]);
-#pragma unroll
-            for (int o = 32; o >= 1; o >>= 1) sum = fmax(sum, __shfl_xor(sum, o));
-            dpv[h] = sum;
-            res[h] = __dadd_rn(sum, h == 0 ? pp.x : pp.y);
-        }
-        if (pr == 0) {
-            total[0] = res[0]; total[1] = res[1]; datap[0] = dpv[0]; datap[1] = dpv[1];
-            if (NC == 2) { total[2] = total[3] = datap[2] = datap[3] = 0.0; }
-        } else {
-            total[2] = res[0]; total[3] = res[1]; datap[2] = dpv[0]; datap[3] = dpv[1];
-        }
-        WAVE_LDS_SYNC();   // the next pair reuses the buffers
+        for (int c = 0; c < NC; c++)
+            if (cand0 + c < P) ghat_out[(cand0 + c) * 64 + lane] = gh[c * GH_CAND + (lane >> 3) * GH_ROW + (lane & 7)];
     }
+    // ---- a5: Held-Karp in registers ----
+    double G[8];
+    G[0] = 0.0;
+#pragma unroll
+    for (int d = 1; d < 8; d++) G[d] = gh[cx.hc * GH_CAND + cx.hv * GH_ROW + (cx.hv ^ d)];
+    const double pp = hk_registers(G);
+    // ---- a2/a3: DataP of stage hv of candidate hc, then max over the candidate's 8 lanes ----
+    const uint2 devs = *reinterpret_cast<const uint2 *>(wl + OFF_PB + cx.hc * 64 + 8 * cx.hv);
+    uint32_t dv[8];
+#pragma unroll
+    for (int k = 0; k < 8; k++) dv[k] = byte_of(devs, k);
+    double dp = 0.0;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        const double *wrow = cx.Wdp + dv[i] * NDEV;
+        double sum = 0.0;
+#pragma unroll
+        for (int k = 0; k < 8; k++) sum = __dadd_rn(sum, wrow[dv[k]]);   // own slot: the zero diagonal
+        dp = i == 0 ? sum : fmax(dp, sum);
+    }
+    dp = fmax(dp, dpp_move<DPP_XOR1>(dp));
+    dp = fmax(dp, dpp_move<DPP_XOR2>(dp));
+    dp = fmax(dp, dpp_move<DPP_HALF_MIRROR>(dp));
+    datap = dp;
+    total = __dadd_rn(dp, pp);   // a6
+    WAVE_LDS_SYNC();             // the next group reuses the slice
 }
 
 template <int NC>
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
 k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank_tab,
-              const double *__restrict__ rank_val, const uint32_t *__restrict__ step_tab,
-              const int32_t *__restrict__ perm, size_t P, double *__restrict__ cost,
-              double *__restrict__ ghat_out, double *__restrict__ datap_out)
+              const double *__restrict__ rank_val, const int32_t *__restrict__ perm, size_t P,
+              double *__restrict__ cost, double *__restrict__ ghat_out, double *__restrict__ datap_out)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const wave_ctx cx = wave_setup<NC>(smem, rank_tab, step_tab);
+    const wave_ctx cx = wave_setup<NC>(smem, rank_tab, rank_val, W_dp);
     const int lane = cx.lane, wave = threadIdx.x >> 6;
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
-    const size_t nquads = (P + NC - 1) / NC;
-    for (size_t quad = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; quad < nquads; quad += nwaves) {
+    const size_t ngroups = (P + NC - 1) / NC;
+    for (size_t grp = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; grp < ngroups; grp += nwaves) {
         // ---- a1: NC candidate rows; position = lane: stage = lane / 8, slot = lane % 8 ----
-        int dev[CANDS] = {0, 0, 0, 0};
 #pragma unroll
         for (int c = 0; c < NC; c++) {
-            size_t cand = quad * NC + c;
+            size_t cand = grp * NC + c;
             if (cand >= P) cand = P - 1;   // ragged tail: recompute the last row, never stored
-            dev[c] = perm[cand * NDEV + lane];
-            cx.wl[OFF_PB + c * 64 + lane] = (unsigned char)dev[c];
+            cx.wl[OFF_PB + c * 64 + lane] = (unsigned char)perm[cand * NDEV + lane];
         }
         WAVE_LDS_SYNC();
-        double total[CANDS], datap[CANDS];
-        eval_quad<NC>(cx, W_dp, rank_val, dev, total, datap, ghat_out, quad * NC, P);
-        if (lane < NC) {
-            const size_t cand = quad * NC + lane;
-            const double t = lane == 0 ? total[0] : lane == 1 ? total[1] : lane == 2 ? total[2] : total[3];
-            const double d = lane == 0 ? datap[0] : lane == 1 ? datap[1] : lane == 2 ? datap[2] : datap[3];
-            if (cand < P) {
-                if (cost != nullptr) cost[cand] = t;
-                if (datap_out != nullptr) datap_out[cand] = d;
-            }
+        double total, datap;
+        eval_group<NC>(cx, total, datap, ghat_out, grp * NC, P);
+        const size_t cand = grp * NC + (lane >> 3);
+        if ((lane & 7) == 0 && lane < NC * 8 && cand < P) {
+            if (cost != nullptr) cost[cand] = total;
+            if (datap_out != nullptr) datap_out[cand] = datap;
         }
     }
 }
 
 // ---- Sec. 3.4 local search with the paper's four-candidate neighbourhood, all rounds in one launch
-// Each wavefront carries its four candidates through every round: propose a swap (fastest link inside
+// Each wavefront carries its candidates through every round: propose a swap (fastest link inside
 // each of the round's two stages, the four end-point swaps ranked by the paper's Gain), evaluate the
-// swapped allocation with eval_quad, keep it iff strictly cheaper. The fastest link is found on the
+// swapped allocation with eval_group, keep it iff strictly cheaper. The fastest link is found on the
 // ranks (same order and same ties as the weights); the Gain sums use the fp64 weights in slot order.
 __device__ __forceinline__ void pair8_decode(int e, int &i, int &k)
 {
@@ -405,32 +465,30 @@ template <int NC>
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
 k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_pp,
                   const uint16_t *__restrict__ rank_tab, const double *__restrict__ rank_val,
-                  const uint32_t *__restrict__ step_tab, int32_t *__restrict__ perm, size_t P, int moves,
-                  double *__restrict__ cost, int64_t *__restrict__ applied)
+                  int32_t *__restrict__ perm, size_t P, int moves, double *__restrict__ cost,
+                  int64_t *__restrict__ applied)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const wave_ctx cx = wave_setup<NC>(smem, rank_tab, step_tab);
+    const wave_ctx cx = wave_setup<NC>(smem, rank_tab, rank_val, W_dp);
     const int lane = cx.lane, wave = threadIdx.x >> 6;
     unsigned char *wl = cx.wl;
-    const int grp = (lane >> 4) % NC, sub = lane & 15;   // proposal role: 16 lanes per candidate
+    const int sub = lane & 15;   // proposal role: 16 lanes per candidate, four candidates per pass
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
-    const size_t nquads = (P + NC - 1) / NC;
-    for (size_t quad = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; quad < nquads; quad += nwaves) {
-        int cur[CANDS] = {0, 0, 0, 0};   // current allocation: device at position `lane`
-        double cur_cost[CANDS], unused[CANDS];
+    const size_t ngroups = (P + NC - 1) / NC;
+    for (size_t grp = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; grp < ngroups; grp += nwaves) {
 #pragma unroll
         for (int c = 0; c < NC; c++) {
-            size_t cand = quad * NC + c;
+            size_t cand = grp * NC + c;
             if (cand >= P) cand = P - 1;
-            cur[c] = perm[cand * NDEV + lane];
-            wl[OFF_PB + c * 64 + lane] = (unsigned char)cur[c];
-            wl[OFF_PBCUR + c * 64 + lane] = (unsigned char)cur[c];
+            const unsigned char d = (unsigned char)perm[cand * NDEV + lane];
+            wl[OFF_PB + c * 64 + lane] = d;
+            wl[OFF_PBCUR + c * 64 + lane] = d;
         }
         WAVE_LDS_SYNC();
-        eval_quad<NC>(cx, W_dp, rank_val, cur, cur_cost, unused, nullptr, quad * NC, P);
+        double cur_cost, unused;   // of candidate slot cx.hc
+        eval_group<NC>(cx, cur_cost, unused, nullptr, grp * NC, P);
 #pragma nounroll
         for (int r = 0; r < moves; r++) {
-            // ---- proposal for candidate `grp` by its 16 lanes ----
             int j, jp;
             {
                 int t = r % 28, a = 0;
@@ -441,87 +499,90 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
                 j = a;
                 jp = a + 1 + t;
             }
-            const unsigned char *pc = wl + OFF_PBCUR + grp * 64;
-            int slot[2][2];
+            const int Cj = 8 * j, Cjp = 8 * jp;
+            int ta[NC], tb[NC];   // proposed positions of every candidate slot, ta < tb
 #pragma unroll
-            for (int s = 0; s < 2; s++) {
-                const unsigned char *C = pc + 8 * (s == 0 ? j : jp);
-                uint32_t key = 0xFFFFFFFFu;   // (rank << 8) | pair index: first minimiser wins
+            for (int pass = 0; pass < NC / 4; pass++) {
+                // ---- proposal for candidate slot 4 * pass + lane / 16 by its 16 lanes ----
+                const unsigned char *pc = wl + OFF_PBCUR + (4 * pass + (lane >> 4)) * 64;
+                int slot[2][2];
 #pragma unroll
-                for (int e0 = 0; e0 < 32; e0 += 16) {
-                    const int e = e0 + sub;
-                    if (e < 28) {
-                        int i, k;
-                        pair8_decode(e, i, k);
-                        const uint32_t kk = ((uint32_t)cx.R[(int)C[i] * RSTRIDE + C[k]] << 8) | (uint32_t)e;
-                        key = kk < key ? kk : key;
+                for (int s = 0; s < 2; s++) {
+                    const unsigned char *C = pc + (s == 0 ? Cj : Cjp);
+                    uint32_t key = 0xFFFFFFFFu;   // (rank << 8) | pair index: first minimiser wins
+#pragma unroll
+                    for (int e0 = 0; e0 < 32; e0 += 16) {
+                        const int e = e0 + sub;
+                        if (e < 28) {
+                            int i, k;
+                            pair8_decode(e, i, k);
+                            const uint32_t kk = ((uint32_t)cx.R[(int)C[i] * RSTRIDE + C[k]] << 8) | (uint32_t)e;
+                            key = kk < key ? kk : key;
+                        }
+                    }
+#pragma unroll
+                    for (int o = 1; o <= 8; o <<= 1) {
+                        const uint32_t ok = __shfl_xor(key, o);
+                        key = ok < key ? ok : key;
+                    }
+                    pair8_decode((int)(key & 0xFFu), slot[s][0], slot[s][1]);
+                }
+                // lanes 0,1 of the group: mean over C_j' of w[x][.] for x = d1, d2; lanes 2,3: mean over C_j of w[y][.]
+                double mean = 0.0;
+                {
+                    const int side = (sub >> 1) & 1;
+                    const int dv = pc[(side == 0 ? Cj : Cjp) + slot[side][sub & 1]];
+                    const unsigned char *other = pc + (side == 0 ? Cjp : Cj);
+                    double sum = 0.0;
+                    if (sub < 4) {
+#pragma unroll
+                        for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, W_pp[dv * NDEV + other[i]]);
+                    }
+                    mean = __ddiv_rn(sum, 8.0);
+                }
+                const double link0 = W_pp[(int)pc[Cj + slot[0][0]] * NDEV + pc[Cj + slot[0][1]]];
+                const double link1 = W_pp[(int)pc[Cjp + slot[1][0]] * NDEV + pc[Cjp + slot[1][1]]];
+                const int base = lane & ~15;
+                const double mx[2] = {__shfl(mean, base + 0), __shfl(mean, base + 1)};
+                const double my[2] = {__shfl(mean, base + 2), __shfl(mean, base + 3)};
+                double bestg = 0.0;
+                int bk = -1;
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    double g = mx[k >> 1];
+                    g = __dadd_rn(g, -link0);
+                    g = __dadd_rn(g, my[k & 1]);
+                    g = __dadd_rn(g, -link1);
+                    if (bk < 0 || g > bestg) {
+                        bestg = g;
+                        bk = k;
                     }
                 }
+                const int pa = Cj + slot[0][bk >> 1], pb_ = Cjp + slot[1][bk & 1];   // positions, pa < pb_
 #pragma unroll
-                for (int o = 1; o <= 8; o <<= 1) {
-                    const uint32_t ok = __shfl_xor(key, o);
-                    key = ok < key ? ok : key;
-                }
-                pair8_decode((int)(key & 0xFFu), slot[s][0], slot[s][1]);
-            }
-            const int Cj = 8 * j, Cjp = 8 * jp;
-            // lanes 0,1 of the group: mean over C_j' of w[x][.] for x = d1, d2; lanes 2,3: mean over C_j of w[y][.]
-            double mean = 0.0;
-            {
-                const int side = (sub >> 1) & 1;
-                const int dv = pc[(side == 0 ? Cj : Cjp) + slot[side][sub & 1]];
-                const unsigned char *other = pc + (side == 0 ? Cjp : Cj);
-                double sum = 0.0;
-                if (sub < 4) {
-#pragma unroll
-                    for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, W_pp[dv * NDEV + other[i]]);
-                }
-                mean = __ddiv_rn(sum, 8.0);
-            }
-            const double link0 = W_pp[(int)pc[Cj + slot[0][0]] * NDEV + pc[Cj + slot[0][1]]];
-            const double link1 = W_pp[(int)pc[Cjp + slot[1][0]] * NDEV + pc[Cjp + slot[1][1]]];
-            const int base = lane & ~15;
-            const double mx[2] = {__shfl(mean, base + 0), __shfl(mean, base + 1)};
-            const double my[2] = {__shfl(mean, base + 2), __shfl(mean, base + 3)};
-            double bestg = 0.0;
-            int bk = -1;
-#pragma unroll
-            for (int k = 0; k < 4; k++) {
-                double g = mx[k >> 1];
-                g = __dadd_rn(g, -link0);
-                g = __dadd_rn(g, my[k & 1]);
-                g = __dadd_rn(g, -link1);
-                if (bk < 0 || g > bestg) {
-                    bestg = g;
-                    bk = k;
+                for (int c = 0; c < 4; c++) {
+                    ta[4 * pass + c] = __shfl(pa, c * 16);
+                    tb[4 * pass + c] = __shfl(pb_, c * 16);
                 }
             }
-            const int pa = Cj + slot[0][bk >> 1], pb_ = Cjp + slot[1][bk & 1];   // positions, pa < pb_
-            // ---- trial rows: every lane needs each candidate's swap ----
-            int trial[CANDS] = {0, 0, 0, 0}, ta[CANDS], tb[CANDS];
+            // ---- trial rows ----
 #pragma unroll
             for (int c = 0; c < NC; c++) {
-                ta[c] = __shfl(pa, c * 16);
-                tb[c] = __shfl(pb_, c * 16);
                 const int src = lane == ta[c] ? tb[c] : (lane == tb[c] ? ta[c] : lane);
-                trial[c] = wl[OFF_PBCUR + c * 64 + src];
+                wl[OFF_PB + c * 64 + lane] = wl[OFF_PBCUR + c * 64 + src];
             }
             WAVE_LDS_SYNC();
-#pragma unroll
-            for (int c = 0; c < NC; c++) wl[OFF_PB + c * 64 + lane] = (unsigned char)trial[c];
-            WAVE_LDS_SYNC();
-            double tcost[CANDS];
-            eval_quad<NC>(cx, W_dp, rank_val, trial, tcost, unused, nullptr, quad * NC, P);
+            double tcost;
+            eval_group<NC>(cx, tcost, unused, nullptr, grp * NC, P);
             // ---- accept iff strictly cheaper ----
+            const bool mine = tcost < cur_cost;   // uniform over the 8 lanes of a candidate slot
+            const uint64_t takes = __ballot(mine);
+            if (mine) cur_cost = tcost;
 #pragma unroll
             for (int c = 0; c < NC; c++) {
-                const bool take = tcost[c] < cur_cost[c];   // wave-uniform
-                if (take) {
-                    cur[c] = trial[c];
-                    cur_cost[c] = tcost[c];
-                    wl[OFF_PBCUR + c * 64 + lane] = (unsigned char)trial[c];
-                }
-                const size_t cand = quad * NC + c;
+                const bool take = (takes >> (8 * c)) & 1;   // wave-uniform
+                if (take) wl[OFF_PBCUR + c * 64 + lane] = wl[OFF_PB + c * 64 + lane];
+                const size_t cand = grp * NC + c;
                 if (applied != nullptr && lane == 0 && cand < P)
                     applied[cand * (size_t)moves + r] =
                         take ? (long long)ta[c] * NDEV - (long long)ta[c] * (ta[c] + 1) / 2 + (tb[c] - ta[c] - 1) : -1ll;
@@ -530,12 +591,12 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
         }
 #pragma unroll
         for (int c = 0; c < NC; c++) {
-            const size_t cand = quad * NC + c;
-            if (cand < P) {
-                perm[cand * NDEV + lane] = cur[c];
-                if (lane == 0) cost[cand] = cur_cost[c];
-            }
+            const size_t cand = grp * NC + c;
+            if (cand < P) perm[cand * NDEV + lane] = wl[OFF_PBCUR + c * 64 + lane];
         }
+        const size_t cand = grp * NC + (lane >> 3);
+        if ((lane & 7) == 0 && lane < NC * 8 && cand < P) cost[cand] = cur_cost;
+        WAVE_LDS_SYNC();
     }
 }
 
@@ -562,149 +623,11 @@ __global__ void k_rank_weights(const double *__restrict__ W_pp, int N, uint16_t 
     rank_val[r] = w;   // equal weights write equal bits
 }
 
-// ---- Held-Karp item table (problem independent, built once per process) ------------------------
-// A 128-bit LDS read is served 16 lanes at a time and is fastest when those 16 lanes hit 16 different
-// bank groups (address / 16 mod 16) - lanes that share an address are only free when adjacent. The
-// items are therefore laid out by a cyclic structure that makes this true by construction:
-//  * item (S, v) with S = v + ({0} u D) (mod 8) belongs to class D, a (k-1)-subset of {1..7}; the 8
-//    items of a class are the rotations v = 0..7 and occupy 8 consecutive lanes (lane % 8 = v);
-//  * a pass of 16 lanes holds two classes (halves h = 0, 1); the item's entry index in its layer's
-//    buffer is pass*16 + h*8 + v, so writes are dense and an entry's bank group is h*8 + v;
-//  * every class visits its predecessors in an order (d_1 .. d_{k-1}) of D: at step t all 8 lanes read
-//    u = v + d_t, i.e. the 8 rotations of ONE source class D' = (D \ d_t) - d_t of the previous layer:
-//    8 different bank groups, all in the half h(D') where that class was placed;
-//  * the read of a pass is conflict free when its two classes read from opposite halves; class
-//    placement and visiting orders are chosen by a small deterministic search to make that so;
-//  * ghat[u][v] is read from the lane's own column (see GHAT_PAIR_BYTES): never a conflict.
-struct hk_class {
-    uint8_t D;        // difference set as a bit mask over {1..7} (bit d set = d in D)
-    uint8_t ord[7];   // visiting order of D's elements
-};
-
-inline uint8_t hk_source_class(uint8_t D, int d)   // (D \ d) - d (mod 8), as a mask over {1..7}
-{
-    uint8_t out = 0;
-    for (int e = 1; e < 8; e++)
-        if (e != d && (D & (1 << e))) out |= (uint8_t)(1 << ((e - d + 8) & 7));
-    return out;
-}
-
-const std::vector<uint32_t> &hk_item_table()
-{
-    static std::vector<uint32_t> tab;
-    static std::once_flag once;
-    std::call_once(once, [] {
-        tab.assign((size_t)HK_TAB_WORDS4 * 64 * 4, 0u);
-        // half[D] (0/1) and pass[D] of every class of the previous layer, indexed by mask; -1: none
-        int prev_half[256], prev_pass[256], cur_half[256], cur_pass[256];
-        for (int i = 0; i < 256; i++) prev_half[i] = prev_pass[i] = -1;
-        uint64_t rng = 0x2545F4914F6CDD1Dull;
-        auto next = [&rng](uint32_t n) {
-            rng = rng * 6364136223846793005ull + 1442695040888963407ull;
-            return (uint32_t)((rng >> 33) % n);
-        };
-        for (int k = 2; k <= 8; k++) {
-            std::vector<hk_class> cls;
-            for (int D = 0; D < 256; D += 2)
-                if (__builtin_popcount(D) == k - 1) {
-                    hk_class c = {};
-                    c.D = (uint8_t)D;
-                    int t = 0;
-                    for (int d = 1; d < 8; d++)
-                        if (D & (1 << d)) c.ord[t++] = (uint8_t)d;
-                    cls.push_back(c);
-                }
-            const int nc = (int)cls.size(), np = (nc + 1) / 2;
-            // position i of `cls` = (pass i / 2, half i % 2). Cost: number of (pass, step) whose two
-            // classes read from the same half of the previous layer (layer 1 is kept in both halves).
-            auto pass_cost = [&](int p) {
-                if (2 * p + 1 >= nc || k == 2) return 0;
-                int c = 0;
-                for (int t = 0; t < k - 1; t++) {
-                    int ha = prev_half[hk_source_class(cls[2 * p].D, cls[2 * p].ord[t])];
-                    int hb = prev_half[hk_source_class(cls[2 * p + 1].D, cls[2 * p + 1].ord[t])];
-                    c += ha == hb;
-                }
-                return c;
-            };
-            std::vector<int> cost(np);
-            int total = 0;
-            for (int p = 0; p < np; p++) total += cost[p] = pass_cost(p);
-            for (int it = 0; it < 60000 && total > 0; it++) {
-                int a = (int)next(nc);
-                if (next(2) == 0 && k > 2) {
-                    int x = (int)next(k - 1), y = (int)next(k - 1);
-                    if (x == y) continue;
-                    std::swap(cls[a].ord[x], cls[a].ord[y]);
-                    int c = pass_cost(a / 2);
-                    if (c <= cost[a / 2]) {
-                        total += c - cost[a / 2];
-                        cost[a / 2] = c;
-                    } else
-                        std::swap(cls[a].ord[x], cls[a].ord[y]);
-                } else {
-                    int b = (int)next(nc);
-                    if (a / 2 == b / 2) continue;
-                    std::swap(cls[a], cls[b]);
-                    int ca = pass_cost(a / 2), cb = pass_cost(b / 2);
-                    if (ca + cb <= cost[a / 2] + cost[b / 2]) {
-                        total += ca + cb - cost[a / 2] - cost[b / 2];
-                        cost[a / 2] = ca;
-                        cost[b / 2] = cb;
-                    } else
-                        std::swap(cls[a], cls[b]);
-                }
-            }
-            for (int i = 0; i < 256; i++) cur_half[i] = cur_pass[i] = -1;
-            for (int i = 0; i < nc; i++) {
-                cur_pass[cls[i].D] = i / 2;
-                cur_half[cls[i].D] = i % 2;
-            }
-            // emit: item (S, v) of class i sits at step (i/2)/4, lane ((i/2)%4)*16 + (i%2)*8 + v
-            for (int i = 0; i < nc; i++)
-                for (int v = 0; v < 8; v++) {
-                    const int pass = i / 2, half = i % 2, s = pass / 4, lane = (pass % 4) * 16 + half * 8 + v;
-                    uint32_t word[8] = {0};
-                    word[0] = (uint32_t)((pass * 16 + half * 8 + v) * 16) | 0x80000000u;
-                    for (int t = 0; t < k - 1; t++) {
-                        const int d = cls[i].ord[t], u = (v + d) & 7;
-                        int src;   // entry index of (S \ v, u) in the previous layer's buffer
-                        if (k == 2)
-                            src = half * 8 + u;   // layer 1 is stored in both halves
-                        else {
-                            const uint8_t Ds = hk_source_class(cls[i].D, d);
-                            src = prev_pass[Ds] * 16 + prev_half[Ds] * 8 + u;
-                        }
-                        word[1 + t] = (uint32_t)(src * 16) | ((uint32_t)((u * 16 + half * 8 + v) * 16) << 16);
-                    }
-                    for (int w = 0; w < hk_words4(k) * 4; w++) {
-                        size_t word4 = (size_t)hk_tab_first(k) + (size_t)s * hk_words4(k) + w / 4;
-                        tab[(word4 * 64 + lane) * 4 + w % 4] = word[w];
-                    }
-                }
-            // lanes without an item still execute the reads: point them at their own bank group
-            for (int s = 0; s < hk_steps(k); s++)
-                for (int lane = 0; lane < 64; lane++) {
-                    size_t word4 = (size_t)hk_tab_first(k) + (size_t)s * hk_words4(k);
-                    if (tab[(word4 * 64 + lane) * 4] >> 31) continue;
-                    for (int w = 1; w < hk_words4(k) * 4; w++)
-                        tab[((word4 + w / 4) * 64 + lane) * 4 + w % 4] =
-                            (uint32_t)((lane & 15) * 16) | ((uint32_t)((lane & 15) * 16) << 16);
-                }
-            for (int i = 0; i < 256; i++) {
-                prev_half[i] = cur_half[i];
-                prev_pass[i] = cur_pass[i];
-            }
-        }
-    });
-    return tab;
-}
-
 }  // namespace
 
 bool dtfm_fast64_applicable(const dtfm_problem *pr) { return pr->N == 64 && pr->D_dp == 8 && pr->D_pp == 8; }
 
-// Builds the rank tables of a 64-device problem and uploads the Held-Karp item table.
+// Builds the rank tables of a 64-device problem.
 int dtfm_fast64_prepare(dtfm_problem *pr)
 {
     const int N = pr->N;
@@ -714,17 +637,13 @@ int dtfm_fast64_prepare(dtfm_problem *pr)
     hipLaunchKernelGGL(k_rank_weights, dim3((N * N + 255) / 256), dim3(256), 0, (hipStream_t) nullptr, pr->W_pp, N,
                        pr->f64_rank, pr->f64_rank_val);
     DTFM_HIP(hipGetLastError());
-
-    const std::vector<uint32_t> &tab = hk_item_table();
-    DTFM_HIP(hipMalloc((void **)&pr->f64_steps, tab.size() * sizeof(uint32_t)));
-    DTFM_HIP(hipMemcpy(pr->f64_steps, tab.data(), tab.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64<8>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64<4>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
-    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64<2>),
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<8>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<4>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
-    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<2>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
     hipDeviceProp_t prop;
     DTFM_HIP(hipGetDeviceProperties(&prop, pr->device));
@@ -737,30 +656,27 @@ void dtfm_fast64_release(dtfm_problem *pr)
 {
     if (pr->f64_rank) (void)hipFree(pr->f64_rank);
     if (pr->f64_rank_val) (void)hipFree(pr->f64_rank_val);
-    if (pr->f64_steps) (void)hipFree(pr->f64_steps);
 }
 
-// Four candidates per wavefront give the best throughput; when there are too few candidates to
-// give every wavefront slot of the chip a pass that way, two per wavefront halve the latency.
-static bool use_two(const dtfm_problem *pr, size_t rows)
-{
-    return (rows + 3) / 4 < 2 * (size_t)pr->f64_grid * WAVES_PER_BLOCK;
-}
+// Eight candidates per wavefront give the best throughput (every lane busy in Held-Karp); when there
+// are too few candidates to give every SIMD of the chip a wavefront that way, four per wavefront
+// shorten the pass.
+static bool use_four(const dtfm_problem *pr, size_t rows) { return rows <= 4 * 4 * (size_t)pr->f64_grid; }
 
 int dtfm_fast64_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows, double *cost, double *ghat,
                         double *datap, hipStream_t st)
 {
     if (rows == 0) return DTFM_OK;
-    const int nc = use_two(pr, rows) ? 2 : 4;
+    const int nc = use_four(pr, rows) ? 4 : 8;
     size_t passes = (rows + nc - 1) / nc;
     size_t blocks = (passes + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    if (nc == 2)
-        hipLaunchKernelGGL(k_eval_fast64<2>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
-                           pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, cost, ghat, datap);
-    else
+    if (nc == 4)
         hipLaunchKernelGGL(k_eval_fast64<4>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
-                           pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, cost, ghat, datap);
+                           pr->f64_rank, pr->f64_rank_val, perm, rows, cost, ghat, datap);
+    else
+        hipLaunchKernelGGL(k_eval_fast64<8>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
+                           pr->f64_rank, pr->f64_rank_val, perm, rows, cost, ghat, datap);
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
 }
@@ -769,18 +685,16 @@ int dtfm_fast64_ls_gain4_enqueue(const dtfm_problem *pr, int32_t *perm, size_t r
                                  int64_t *applied, hipStream_t st)
 {
     if (rows == 0) return DTFM_OK;
-    const int nc = use_two(pr, rows) ? 2 : 4;
+    const int nc = use_four(pr, rows) ? 4 : 8;
     size_t passes = (rows + nc - 1) / nc;
     size_t blocks = (passes + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    if (nc == 2)
-        hipLaunchKernelGGL(k_ls_gain4_fast64<2>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st,
-                           pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, moves, cost,
-                           applied);
-    else
+    if (nc == 4)
         hipLaunchKernelGGL(k_ls_gain4_fast64<4>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st,
-                           pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, pr->f64_steps, perm, rows, moves, cost,
-                           applied);
+                           pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied);
+    else
+        hipLaunchKernelGGL(k_ls_gain4_fast64<8>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st,
+                           pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied);
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
 }
