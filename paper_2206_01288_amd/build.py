@@ -26,6 +26,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# Per-file additions. The fused 64-device kernels are long straight-line register programmes; the
+# default scheduler orders them for low register pressure, which leaves every packed 16-bit result
+# one wait state away from its consumer. The ILP-first strategy interleaves the independent chains.
+FILE_FLAGS = {"dtfm_fast64.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"]}
+
+
 def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
@@ -46,7 +52,7 @@ def build(force: bool = False, verbose: bool = True) -> str:
         obj = os.path.join(OBJ, src[:-4] + ".o")
         objs.append(obj)
         if force or not os.path.exists(obj) or os.path.getmtime(obj) < dep_time:
-            jobs.append([hipcc] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj])
+            jobs.append([hipcc] + FLAGS + FILE_FLAGS.get(src, []) + extra + ["-c", os.path.join(CSRC, src), "-o", obj])
 
     def run(cmd):
         if verbose:

@@ -134,19 +134,24 @@ constexpr hk_program make_hk_program()
 }
 constexpr hk_program HKP = make_hk_program();
 
-// ---- LDS layout: three tables shared by the workgroup, then one slice per wavefront ----
-constexpr int MAXC = 8;                                                 // candidates per wavefront pass
+// ---- LDS layout: tables shared by the workgroup, then one slice per wavefront ----
+constexpr int MAXC = 32;                                                // most candidates per wavefront pass
 constexpr int LDS_RANK_BYTES = ((NDEV * RSTRIDE * 2 + 15) / 16) * 16;   // 8.25 KiB: u16 rank of W_pp
 constexpr int LDS_RVAL_BYTES = NDEV * NDEV * 8;                         // 32 KiB: rank -> weight
 constexpr int LDS_WDP_BYTES = NDEV * NDEV * 8;                          // 32 KiB: W_dp
-constexpr int OFF_PB = 0;                                // u8 [8 candidates][64]: rows under evaluation, stage-major
-constexpr int OFF_PBCUR = OFF_PB + MAXC * 64;            // u8 [8][64]: current rows (local search)
-// coarsened graphs, double [candidate][u][v] with rows padded to 9 and candidates to 73 entries
-constexpr int GH_ROW = 9, GH_CAND = 73;
-constexpr int OFF_GHAT = OFF_PBCUR + MAXC * 64;
-constexpr int WAVE_LDS_BYTES = ((OFF_GHAT + MAXC * GH_CAND * 8 + 15) / 16) * 16;
+constexpr int LDS_TABLES = LDS_RANK_BYTES + LDS_RVAL_BYTES + LDS_WDP_BYTES;
+constexpr int OFF_PB = 0;                        // u8 [NC candidates][64]: rows under evaluation, stage-major
+// coarsened graphs as winning ranks: u16 [candidate][stage pair 0..27, lexicographic]; the couple
+// (pairs 2q, 2q+1) of candidate c is the 32-bit word 14 c + q
+constexpr int off_ghr(int nc) { return OFF_PB + nc * 64; }
+constexpr int off_res(int nc) { return (off_ghr(nc) + nc * 28 * 2 + 7) / 8 * 8; }   // double [2][NC]: total, DataP
+constexpr int off_curc(int nc) { return off_res(nc) + 2 * nc * 8; }            // double [NC]: current costs (local search)
+constexpr int off_pbcur(int nc) { return off_curc(nc) + nc * 8; }              // u8 [NC][64]: current rows (local search)
+constexpr int off_prop(int nc) { return off_pbcur(nc) + nc * 64; }             // u8 [NC][2]: proposed positions (local search)
+constexpr int wave_lds_bytes(int nc, bool ls) { return ((ls ? off_prop(nc) + nc * 2 : off_curc(nc)) + 15) / 16 * 16; }
 constexpr int WAVES_PER_BLOCK = 8;
-constexpr int LDS_TOTAL = LDS_RANK_BYTES + LDS_RVAL_BYTES + LDS_WDP_BYTES + WAVES_PER_BLOCK * WAVE_LDS_BYTES;
+constexpr int lds_total(int nc, bool ls) { return LDS_TABLES + (ls ? LDS_WDP_BYTES : 0) + WAVES_PER_BLOCK * wave_lds_bytes(nc, ls); }
+static_assert(lds_total(MAXC, true) <= 160 * 1024, "LDS budget of a CU");
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
@@ -159,6 +164,15 @@ __device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b)
 {
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2, a),
                                                                   __builtin_bit_cast(u16x2, b)));
+}
+
+// two 16-bit table entries side by side in one register (low half, high half)
+__device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi)
+{
+    u16x2 v;
+    v.x = lo;
+    v.y = hi;
+    return __builtin_bit_cast(uint32_t, v);
 }
 
 // Orders this wavefront's earlier LDS writes before its later LDS reads as seen by other lanes.
@@ -195,6 +209,30 @@ __device__ __forceinline__ double lane_xor_direct(double x, int d)
     default: return dpp_move<DPP_HALF_MIRROR>(x);
     }
 }
+// the same exchange through the LDS crossbar (no memory access, no vector-ALU slot)
+template <int D>
+__device__ __forceinline__ double swizzle_xor(double x)
+{
+    const uint64_t b = __builtin_bit_cast(uint64_t, x);
+    const int lo = __builtin_amdgcn_ds_swizzle((int)(uint32_t)b, 0x1F | (D << 10));
+    const int hi = __builtin_amdgcn_ds_swizzle((int)(uint32_t)(b >> 32), 0x1F | (D << 10));
+    return __builtin_bit_cast(double, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+__device__ __forceinline__ double lane_xor_swizzle(double x, int d)
+{
+    switch (d) {
+    case 1: return swizzle_xor<1>(x);
+    case 2: return swizzle_xor<2>(x);
+    case 3: return swizzle_xor<3>(x);
+    case 4: return swizzle_xor<4>(x);
+    case 5: return swizzle_xor<5>(x);
+    case 6: return swizzle_xor<6>(x);
+    default: return swizzle_xor<7>(x);
+    }
+}
+#ifndef HK_SWIZZLE_SET
+#define HK_SWIZZLE_SET 0x70   // bit d set: the exchange by d goes through the LDS crossbar
+#endif
 
 // One layer of Held-Karp: classes with J elements from the classes with J - 1. Source-major order, so
 // that the mirrored copy of a source serves all its relaxations through d = 4, 5, 6.
@@ -205,7 +243,9 @@ __device__ __forceinline__ void hk_layer(const double (&prev)[35], double (&cur)
     for (int s = 0; s < BINOM7[J - 1]; s++) {
         const double x = prev[s];
         double xm = 0.0;
-        if (HKP.step[J][s][4] != 0xFF || HKP.step[J][s][5] != 0xFF || HKP.step[J][s][6] != 0xFF)
+        if ((HKP.step[J][s][4] != 0xFF && !((HK_SWIZZLE_SET >> 4) & 1)) ||
+            (HKP.step[J][s][5] != 0xFF && !((HK_SWIZZLE_SET >> 5) & 1)) ||
+            (HKP.step[J][s][6] != 0xFF && !((HK_SWIZZLE_SET >> 6) & 1)))
             xm = dpp_move<DPP_HALF_MIRROR>(x);
 #pragma unroll
         for (int d = 1; d < 8; d++) {
@@ -213,7 +253,9 @@ __device__ __forceinline__ void hk_layer(const double (&prev)[35], double (&cur)
             if (step == 0xFF) continue;
             const int i = step & 0x7F;
             // tab[S \ v][u] at u = v xor d, then + Ghat[u][v]
-            const double moved = (d >= 4 && d <= 6) ? lane_xor_direct(xm, d ^ 7) : lane_xor_direct(x, d);
+            double moved;
+            if ((HK_SWIZZLE_SET >> d) & 1) moved = lane_xor_swizzle(x, d);
+            else moved = (d >= 4 && d <= 6) ? lane_xor_direct(xm, d ^ 7) : lane_xor_direct(x, d);
             const double t = __dadd_rn(moved, G[d]);
             cur[i] = (step & 0x80) ? t : fmin(cur[i], t);
         }
@@ -244,23 +286,35 @@ __device__ __forceinline__ double hk_registers(const double (&G)[8])
 // byte k (0..7) of a 64-bit value held as two dwords
 __device__ __forceinline__ uint32_t byte_of(uint2 v, int k) { return ((k < 4 ? v.x : v.y) >> (8 * (k & 3))) & 0xFFu; }
 
+// index of the stage pair (a, b), a < b, in lexicographic order
+__device__ __forceinline__ int pair_index(int a, int b) { return a * 7 - a * (a - 1) / 2 + (b - a - 1); }
+// the inverse: e-th pair -> (i, k)
+__device__ __forceinline__ void pair8_decode(int e, int &i, int &k)
+{
+    int a = 0;
+    while (e >= 7 - a) {
+        e -= 7 - a;
+        a++;
+    }
+    i = a;
+    k = a + 1 + e;
+}
+
 // Per-wavefront context: LDS pointers and the lane's fixed roles.
 struct wave_ctx {
     unsigned char *wl;       // this wavefront's LDS slice
     const uint16_t *R;       // rank table (LDS)
     const double *rank_val;  // rank -> weight (LDS)
     const double *Wdp;       // W_dp (LDS)
+    const double *Wpp;       // W_pp (LDS; local-search kernel only)
     int lane;
-    int mslot;               // matching role: candidate slot 0..3 within a matching pass
-    bool couple_valid;       // lanes 14, 15 of each 16 repeat couple 13 and write nothing
-    int j1[2], j2[2];        // the lane's two stage pairs (j1 < j2)
-    int hc, hv;              // Held-Karp / DataP role: candidate slot, stage
+    int hv;                  // Held-Karp / DataP role: stage; the candidate slot is 8 * pass + lane / 8
 };
 
 // Loads the workgroup's tables into LDS and derives the lane roles. Ends with a workgroup barrier.
-template <int NC>
+template <int NC, bool LS>
 __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16_t *rank_tab,
-                                               const double *rank_val, const double *W_dp)
+                                               const double *rank_val, const double *W_dp, const double *W_pp)
 {
     wave_ctx cx;
     cx.lane = threadIdx.x & 63;
@@ -268,7 +322,8 @@ __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16
     cx.R = reinterpret_cast<const uint16_t *>(smem);
     cx.rank_val = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES);
     cx.Wdp = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES + LDS_RVAL_BYTES);
-    cx.wl = smem + LDS_RANK_BYTES + LDS_RVAL_BYTES + LDS_WDP_BYTES + wave * WAVE_LDS_BYTES;
+    cx.Wpp = reinterpret_cast<const double *>(smem + LDS_TABLES);
+    cx.wl = smem + LDS_TABLES + (LS ? LDS_WDP_BYTES : 0) + wave * wave_lds_bytes(NC, LS);
     // rank table -> LDS, rows re-strided (two entries per thread per pass)
     for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
         const int row = i / (NDEV / 2), col2 = i - row * (NDEV / 2);
@@ -277,41 +332,25 @@ __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16
     for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
         reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES)[i] = reinterpret_cast<const double2 *>(rank_val)[i];
         reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES + LDS_RVAL_BYTES)[i] = reinterpret_cast<const double2 *>(W_dp)[i];
+        if (LS) reinterpret_cast<double2 *>(smem + LDS_TABLES)[i] = reinterpret_cast<const double2 *>(W_pp)[i];
     }
-    // zero diagonals of the eight coarsened graphs (never overwritten)
-    *reinterpret_cast<double *>(cx.wl + OFF_GHAT + ((cx.lane >> 3) * GH_CAND + (cx.lane & 7) * (GH_ROW + 1)) * 8) = 0.0;
-    // matching role: candidate slot and the couple of stage pairs (2q, 2q+1) in lexicographic order
-    cx.mslot = cx.lane >> 4;
-    const int q = (cx.lane & 15) < 14 ? (cx.lane & 15) : 13;
-    cx.couple_valid = (cx.lane & 15) < 14;
-#pragma unroll
-    for (int h = 0; h < 2; h++) {
-        int t = 2 * q + h, a = 0;
-        while (t >= 7 - a) {
-            t -= 7 - a;
-            a++;
-        }
-        cx.j1[h] = a;
-        cx.j2[h] = a + 1 + t;
-    }
-    // with NC = 4 the upper half of the wavefront repeats the lower half's Held-Karp and DataP
-    cx.hc = (cx.lane >> 3) % NC;
     cx.hv = cx.lane & 7;
     __syncthreads();
     return cx;
 }
 
-// a4 for one pass of four candidates: the bottleneck matchings of this lane's two stage pairs of the
+// a4 for one lane: the bottleneck matchings of the stage pairs (j1[0], j2[0]) and (j1[1], j2[1]) of the
 // candidate whose row is at pb, as two packed ranks.
-__device__ __forceinline__ uint32_t match_couple(const wave_ctx &cx, const unsigned char *pb)
+__device__ __forceinline__ uint32_t match_couple(const wave_ctx &cx, const unsigned char *pb, const int (&j1)[2],
+                                                 const int (&j2)[2])
 {
     const uint16_t *R = cx.R;
     uint2 rowdev[2], coldev[2];
     uint32_t coloff[2][8];
 #pragma unroll
     for (int h = 0; h < 2; h++) {
-        rowdev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * cx.j1[h]);   // devices of stage j1, slots 0..7
-        coldev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * cx.j2[h]);   // devices of stage j2
+        rowdev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * j1[h]);   // devices of stage j1, slots 0..7
+        coldev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * j2[h]);   // devices of stage j2
 #pragma unroll
         for (int c = 0; c < 8; c++) coloff[h][c] = byte_of(coldev[h], c);
     }
@@ -322,8 +361,7 @@ __device__ __forceinline__ uint32_t match_couple(const wave_ctx &cx, const unsig
     {
         const uint32_t rb0 = byte_of(rowdev[0], 0) * RSTRIDE, rb1 = byte_of(rowdev[1], 0) * RSTRIDE;
 #pragma unroll
-        for (int c = 0; c < 8; c++)
-            wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
+        for (int c = 0; c < 8; c++) wnext[c] = pack2(R[rb0 + coloff[0][c]], R[rb1 + coloff[1][c]]);
     }
 #pragma unroll
     for (int r = 0; r < 8; r++) {
@@ -334,8 +372,7 @@ __device__ __forceinline__ uint32_t match_couple(const wave_ctx &cx, const unsig
         if (r < 7) {
             const uint32_t rb0 = byte_of(rowdev[0], r + 1) * RSTRIDE, rb1 = byte_of(rowdev[1], r + 1) * RSTRIDE;
 #pragma unroll
-            for (int c = 0; c < 8; c++)
-                wnext[c] = (uint32_t)R[rb0 + coloff[0][c]] | ((uint32_t)R[rb1 + coloff[1][c]] << 16);
+            for (int c = 0; c < 8; c++) wnext[c] = pack2(R[rb0 + coloff[0][c]], R[rb1 + coloff[1][c]]);
         }
 #pragma unroll
         for (int i = 0; i < BINOM8[r + 1]; i++) {
@@ -356,63 +393,78 @@ __device__ __forceinline__ uint32_t match_couple(const wave_ctx &cx, const unsig
     return G[255];
 }
 
-// Evaluates the NC (8 or 4) candidates whose rows are in the wavefront's LDS slice at OFF_PB (stage-major
-// bytes, already visible to all lanes). On return every lane holds total (Eq. 1) and datap (Eq. 2 + max)
-// of candidate slot cx.hc. ghat_out, if not null, receives the coarsened graphs of candidates
-// cand0 .. cand0 + NC - 1 that are < P.
+// Evaluates the NC (4, 8 or 32) candidates whose rows are in the wavefront's LDS slice at OFF_PB
+// (stage-major bytes, already visible to all lanes). The work items of the matching phase are the
+// NC * 14 (candidate, couple of stage pairs) combinations, 64 per pass: with NC = 32 every lane of all
+// seven passes is busy. Held-Karp and DataP then run NC / 8 passes of eight candidates (with NC = 4 the
+// upper half of the wavefront repeats the lower half). On return the slice holds, visible to all
+// lanes, total (Eq. 1) of candidate slot c at res[c] and DataP (Eq. 2 + max) at res[NC + c]. ghat_out,
+// if not null, receives the coarsened graphs of candidates cand0 .. cand0 + NC - 1 that are < P.
 template <int NC>
-__device__ __forceinline__ void eval_group(const wave_ctx &cx, double &total, double &datap,
-                                           double *__restrict__ ghat_out, size_t cand0, size_t P)
+__device__ __forceinline__ void eval_group(const wave_ctx &cx, double *__restrict__ ghat_out, size_t cand0, size_t P)
 {
     unsigned char *wl = cx.wl;
     const int lane = cx.lane;
-    double *gh = reinterpret_cast<double *>(wl + OFF_GHAT);
-    // ---- a4: matchings on ranks; winning ranks -> fp64 weights -> coarsened graphs in LDS ----
+    constexpr int ITEMS = NC * 14, MPASSES = (ITEMS + 63) / 64, HPASSES = (NC + 7) / 8;
+    uint32_t *ghr32 = reinterpret_cast<uint32_t *>(wl + off_ghr(NC));
+    const uint16_t *ghr16 = reinterpret_cast<const uint16_t *>(wl + off_ghr(NC));
+    double *res = reinterpret_cast<double *>(wl + off_res(NC));
+    // ---- a4: matchings on ranks; the two winning ranks of item t go to word t ----
 #pragma nounroll
-    for (int pass = 0; pass < NC / 4; pass++) {
-        const int mc = 4 * pass + cx.mslot;
-        const uint32_t gfull = match_couple(cx, wl + OFF_PB + mc * 64);
-        const double e0 = cx.rank_val[gfull & 0xFFFFu], e1 = cx.rank_val[gfull >> 16];
-        if (cx.couple_valid) {
-            double *g = gh + mc * GH_CAND;
-            g[cx.j1[0] * GH_ROW + cx.j2[0]] = e0;
-            g[cx.j2[0] * GH_ROW + cx.j1[0]] = e0;
-            g[cx.j1[1] * GH_ROW + cx.j2[1]] = e1;
-            g[cx.j2[1] * GH_ROW + cx.j1[1]] = e1;
-        }
+    for (int pass = 0; pass < MPASSES; pass++) {
+        int t = pass * 64 + lane;
+        const bool valid = t < ITEMS;
+        if (!valid) t = ITEMS - 1;   // idle lanes repeat the last item and write nothing
+        const int mc = t / 14, q = t - 14 * mc;
+        int j1[2], j2[2];
+        pair8_decode(2 * q, j1[0], j2[0]);
+        pair8_decode(2 * q + 1, j1[1], j2[1]);
+        const uint32_t gfull = match_couple(cx, wl + OFF_PB + mc * 64, j1, j2);
+        if (valid) ghr32[t] = gfull;
     }
     WAVE_LDS_SYNC();
     if (ghat_out != nullptr) {
-#pragma unroll
+        const int u = lane >> 3, v = lane & 7;
+        const int pi = pair_index(u < v ? u : v, u < v ? v : u);
+#pragma nounroll
         for (int c = 0; c < NC; c++)
-            if (cand0 + c < P) ghat_out[(cand0 + c) * 64 + lane] = gh[c * GH_CAND + (lane >> 3) * GH_ROW + (lane & 7)];
+            if (cand0 + c < P) ghat_out[(cand0 + c) * 64 + lane] = u == v ? 0.0 : cx.rank_val[ghr16[c * 28 + pi]];
     }
-    // ---- a5: Held-Karp in registers ----
-    double G[8];
-    G[0] = 0.0;
+#pragma nounroll
+    for (int h = 0; h < HPASSES; h++) {
+        const int hc = (8 * h + (lane >> 3)) % NC;
+        // ---- a5: winning ranks -> fp64 weights; Held-Karp in registers ----
+        double G[8];
+        G[0] = 0.0;
 #pragma unroll
-    for (int d = 1; d < 8; d++) G[d] = gh[cx.hc * GH_CAND + cx.hv * GH_ROW + (cx.hv ^ d)];
-    const double pp = hk_registers(G);
-    // ---- a2/a3: DataP of stage hv of candidate hc, then max over the candidate's 8 lanes ----
-    const uint2 devs = *reinterpret_cast<const uint2 *>(wl + OFF_PB + cx.hc * 64 + 8 * cx.hv);
-    uint32_t dv[8];
+        for (int d = 1; d < 8; d++) {
+            const int u = cx.hv ^ d;
+            G[d] = cx.rank_val[ghr16[hc * 28 + pair_index(u < cx.hv ? u : cx.hv, u < cx.hv ? cx.hv : u)]];
+        }
+        const double pp = hk_registers(G);
+        // ---- a2/a3: DataP of stage hv of candidate hc, then max over the candidate's 8 lanes ----
+        const uint2 devs = *reinterpret_cast<const uint2 *>(wl + OFF_PB + hc * 64 + 8 * cx.hv);
+        uint32_t dv[8];
 #pragma unroll
-    for (int k = 0; k < 8; k++) dv[k] = byte_of(devs, k);
-    double dp = 0.0;
+        for (int k = 0; k < 8; k++) dv[k] = byte_of(devs, k);
+        double dp = 0.0;
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
-        const double *wrow = cx.Wdp + dv[i] * NDEV;
-        double sum = 0.0;
+        for (int i = 0; i < 8; i++) {
+            const double *wrow = cx.Wdp + dv[i] * NDEV;
+            double sum = 0.0;
 #pragma unroll
-        for (int k = 0; k < 8; k++) sum = __dadd_rn(sum, wrow[dv[k]]);   // own slot: the zero diagonal
-        dp = i == 0 ? sum : fmax(dp, sum);
+            for (int k = 0; k < 8; k++) sum = __dadd_rn(sum, wrow[dv[k]]);   // own slot: the zero diagonal
+            dp = i == 0 ? sum : fmax(dp, sum);
+        }
+        dp = fmax(dp, dpp_move<DPP_XOR1>(dp));
+        dp = fmax(dp, dpp_move<DPP_XOR2>(dp));
+        dp = fmax(dp, dpp_move<DPP_HALF_MIRROR>(dp));
+        if (cx.hv == 0 && lane < NC * 8) {
+            res[hc] = __dadd_rn(dp, pp);   // a6
+            res[NC + hc] = dp;
+        }
     }
-    dp = fmax(dp, dpp_move<DPP_XOR1>(dp));
-    dp = fmax(dp, dpp_move<DPP_XOR2>(dp));
-    dp = fmax(dp, dpp_move<DPP_HALF_MIRROR>(dp));
-    datap = dp;
-    total = __dadd_rn(dp, pp);   // a6
-    WAVE_LDS_SYNC();             // the next group reuses the slice
+    WAVE_LDS_SYNC();
 }
 
 template <int NC>
@@ -422,7 +474,7 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
               double *__restrict__ cost, double *__restrict__ ghat_out, double *__restrict__ datap_out)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const wave_ctx cx = wave_setup<NC>(smem, rank_tab, rank_val, W_dp);
+    const wave_ctx cx = wave_setup<NC, false>(smem, rank_tab, rank_val, W_dp, nullptr);
     const int lane = cx.lane, wave = threadIdx.x >> 6;
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
     const size_t ngroups = (P + NC - 1) / NC;
@@ -435,13 +487,14 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
             cx.wl[OFF_PB + c * 64 + lane] = (unsigned char)perm[cand * NDEV + lane];
         }
         WAVE_LDS_SYNC();
-        double total, datap;
-        eval_group<NC>(cx, total, datap, ghat_out, grp * NC, P);
-        const size_t cand = grp * NC + (lane >> 3);
-        if ((lane & 7) == 0 && lane < NC * 8 && cand < P) {
-            if (cost != nullptr) cost[cand] = total;
-            if (datap_out != nullptr) datap_out[cand] = datap;
+        eval_group<NC>(cx, ghat_out, grp * NC, P);
+        const double *res = reinterpret_cast<const double *>(cx.wl + off_res(NC));
+        const size_t cand = grp * NC + lane;
+        if (lane < NC && cand < P) {
+            if (cost != nullptr) cost[cand] = res[lane];
+            if (datap_out != nullptr) datap_out[cand] = res[NC + lane];
         }
+        WAVE_LDS_SYNC();   // the next group reuses the slice
     }
 }
 
@@ -450,17 +503,6 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
 // each of the round's two stages, the four end-point swaps ranked by the paper's Gain), evaluate the
 // swapped allocation with eval_group, keep it iff strictly cheaper. The fastest link is found on the
 // ranks (same order and same ties as the weights); the Gain sums use the fp64 weights in slot order.
-__device__ __forceinline__ void pair8_decode(int e, int &i, int &k)
-{
-    int a = 0;
-    while (e >= 7 - a) {
-        e -= 7 - a;
-        a++;
-    }
-    i = a;
-    k = a + 1 + e;
-}
-
 template <int NC>
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
 k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_pp,
@@ -469,9 +511,12 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
                   int64_t *__restrict__ applied)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const wave_ctx cx = wave_setup<NC>(smem, rank_tab, rank_val, W_dp);
+    const wave_ctx cx = wave_setup<NC, true>(smem, rank_tab, rank_val, W_dp, W_pp);
     const int lane = cx.lane, wave = threadIdx.x >> 6;
     unsigned char *wl = cx.wl;
+    unsigned char *pbcur = wl + off_pbcur(NC), *prop = wl + off_prop(NC);
+    const double *res = reinterpret_cast<const double *>(wl + off_res(NC));
+    double *curc = reinterpret_cast<double *>(wl + off_curc(NC));
     const int sub = lane & 15;   // proposal role: 16 lanes per candidate, four candidates per pass
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
     const size_t ngroups = (P + NC - 1) / NC;
@@ -482,29 +527,21 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
             if (cand >= P) cand = P - 1;
             const unsigned char d = (unsigned char)perm[cand * NDEV + lane];
             wl[OFF_PB + c * 64 + lane] = d;
-            wl[OFF_PBCUR + c * 64 + lane] = d;
+            pbcur[c * 64 + lane] = d;
         }
         WAVE_LDS_SYNC();
-        double cur_cost, unused;   // of candidate slot cx.hc
-        eval_group<NC>(cx, cur_cost, unused, nullptr, grp * NC, P);
+        eval_group<NC>(cx, nullptr, grp * NC, P);
+        if (lane < NC) curc[lane] = res[lane];
 #pragma nounroll
         for (int r = 0; r < moves; r++) {
             int j, jp;
-            {
-                int t = r % 28, a = 0;
-                while (t >= 7 - a) {
-                    t -= 7 - a;
-                    a++;
-                }
-                j = a;
-                jp = a + 1 + t;
-            }
+            pair8_decode(r % 28, j, jp);
             const int Cj = 8 * j, Cjp = 8 * jp;
-            int ta[NC], tb[NC];   // proposed positions of every candidate slot, ta < tb
-#pragma unroll
+#pragma nounroll
             for (int pass = 0; pass < NC / 4; pass++) {
                 // ---- proposal for candidate slot 4 * pass + lane / 16 by its 16 lanes ----
-                const unsigned char *pc = wl + OFF_PBCUR + (4 * pass + (lane >> 4)) * 64;
+                const int pslot = 4 * pass + (lane >> 4);
+                const unsigned char *pc = pbcur + pslot * 64;
                 int slot[2][2];
 #pragma unroll
                 for (int s = 0; s < 2; s++) {
@@ -536,12 +573,12 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
                     double sum = 0.0;
                     if (sub < 4) {
 #pragma unroll
-                        for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, W_pp[dv * NDEV + other[i]]);
+                        for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, cx.Wpp[dv * NDEV + other[i]]);
                     }
                     mean = __ddiv_rn(sum, 8.0);
                 }
-                const double link0 = W_pp[(int)pc[Cj + slot[0][0]] * NDEV + pc[Cj + slot[0][1]]];
-                const double link1 = W_pp[(int)pc[Cjp + slot[1][0]] * NDEV + pc[Cjp + slot[1][1]]];
+                const double link0 = cx.Wpp[(int)pc[Cj + slot[0][0]] * NDEV + pc[Cj + slot[0][1]]];
+                const double link1 = cx.Wpp[(int)pc[Cjp + slot[1][0]] * NDEV + pc[Cjp + slot[1][1]]];
                 const int base = lane & ~15;
                 const double mx[2] = {__shfl(mean, base + 0), __shfl(mean, base + 1)};
                 const double my[2] = {__shfl(mean, base + 2), __shfl(mean, base + 3)};
@@ -558,44 +595,46 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
                         bk = k;
                     }
                 }
-                const int pa = Cj + slot[0][bk >> 1], pb_ = Cjp + slot[1][bk & 1];   // positions, pa < pb_
-#pragma unroll
-                for (int c = 0; c < 4; c++) {
-                    ta[4 * pass + c] = __shfl(pa, c * 16);
-                    tb[4 * pass + c] = __shfl(pb_, c * 16);
+                if (sub == 0) {   // positions, first < second
+                    prop[2 * pslot] = (unsigned char)(Cj + slot[0][bk >> 1]);
+                    prop[2 * pslot + 1] = (unsigned char)(Cjp + slot[1][bk & 1]);
                 }
             }
+            WAVE_LDS_SYNC();
             // ---- trial rows ----
 #pragma unroll
             for (int c = 0; c < NC; c++) {
-                const int src = lane == ta[c] ? tb[c] : (lane == tb[c] ? ta[c] : lane);
-                wl[OFF_PB + c * 64 + lane] = wl[OFF_PBCUR + c * 64 + src];
+                const int ta = prop[2 * c], tb = prop[2 * c + 1];
+                const int src = lane == ta ? tb : (lane == tb ? ta : lane);
+                wl[OFF_PB + c * 64 + lane] = pbcur[c * 64 + src];
             }
             WAVE_LDS_SYNC();
-            double tcost;
-            eval_group<NC>(cx, tcost, unused, nullptr, grp * NC, P);
+            eval_group<NC>(cx, nullptr, grp * NC, P);
             // ---- accept iff strictly cheaper ----
-            const bool mine = tcost < cur_cost;   // uniform over the 8 lanes of a candidate slot
+            bool mine = false;
+            if (lane < NC) {
+                const double t = res[lane];
+                mine = t < curc[lane];
+                if (mine) curc[lane] = t;
+            }
             const uint64_t takes = __ballot(mine);
-            if (mine) cur_cost = tcost;
 #pragma unroll
             for (int c = 0; c < NC; c++) {
-                const bool take = (takes >> (8 * c)) & 1;   // wave-uniform
-                if (take) wl[OFF_PBCUR + c * 64 + lane] = wl[OFF_PB + c * 64 + lane];
-                const size_t cand = grp * NC + c;
-                if (applied != nullptr && lane == 0 && cand < P)
-                    applied[cand * (size_t)moves + r] =
-                        take ? (long long)ta[c] * NDEV - (long long)ta[c] * (ta[c] + 1) / 2 + (tb[c] - ta[c] - 1) : -1ll;
+                const bool take = (takes >> c) & 1;   // wave-uniform
+                if (take) pbcur[c * 64 + lane] = wl[OFF_PB + c * 64 + lane];
+            }
+            if (applied != nullptr && lane < NC && grp * NC + lane < P) {
+                const long long ta = prop[2 * lane], tb = prop[2 * lane + 1];
+                applied[(grp * NC + lane) * (size_t)moves + r] = mine ? ta * NDEV - ta * (ta + 1) / 2 + (tb - ta - 1) : -1ll;
             }
             WAVE_LDS_SYNC();
         }
 #pragma unroll
         for (int c = 0; c < NC; c++) {
             const size_t cand = grp * NC + c;
-            if (cand < P) perm[cand * NDEV + lane] = wl[OFF_PBCUR + c * 64 + lane];
+            if (cand < P) perm[cand * NDEV + lane] = pbcur[c * 64 + lane];
         }
-        const size_t cand = grp * NC + (lane >> 3);
-        if ((lane & 7) == 0 && lane < NC * 8 && cand < P) cost[cand] = cur_cost;
+        if (lane < NC && grp * NC + lane < P) cost[grp * NC + lane] = curc[lane];
         WAVE_LDS_SYNC();
     }
 }
@@ -637,14 +676,18 @@ int dtfm_fast64_prepare(dtfm_problem *pr)
     hipLaunchKernelGGL(k_rank_weights, dim3((N * N + 255) / 256), dim3(256), 0, (hipStream_t) nullptr, pr->W_pp, N,
                        pr->f64_rank, pr->f64_rank_val);
     DTFM_HIP(hipGetLastError());
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64<32>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(32, false)));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64<8>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(8, false)));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64<4>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(4, false)));
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<32>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(32, true)));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<8>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(8, true)));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<4>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL));
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(4, true)));
     hipDeviceProp_t prop;
     DTFM_HIP(hipGetDeviceProperties(&prop, pr->device));
     pr->f64_grid = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
@@ -658,43 +701,61 @@ void dtfm_fast64_release(dtfm_problem *pr)
     if (pr->f64_rank_val) (void)hipFree(pr->f64_rank_val);
 }
 
-// Eight candidates per wavefront give the best throughput (every lane busy in Held-Karp); when there
-// are too few candidates to give every SIMD of the chip a wavefront that way, four per wavefront
-// shorten the pass.
-static bool use_four(const dtfm_problem *pr, size_t rows) { return rows <= 4 * 4 * (size_t)pr->f64_grid; }
+// Candidates per wavefront pass. 32 keep every lane of the matching phase busy (32 * 14 couples = 7
+// full passes) and are used once that still gives every wavefront slot of the chip a pass; 8 fill
+// Held-Karp's lanes; when there are too few candidates to give every SIMD of the chip a wavefront
+// that way, 4 per wavefront shorten the pass.
+static int group_size(const dtfm_problem *pr, size_t rows)
+{
+    const size_t simds = 4 * (size_t)pr->f64_grid;
+    if (rows >= 32 * 2 * simds) return 32;
+    return rows <= 4 * simds ? 4 : 8;
+}
+
+template <int NC>
+static void launch_eval(const dtfm_problem *pr, const int32_t *perm, size_t rows, double *cost, double *ghat,
+                        double *datap, hipStream_t st)
+{
+    size_t passes = (rows + NC - 1) / NC;
+    size_t blocks = (passes + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
+    hipLaunchKernelGGL(k_eval_fast64<NC>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), lds_total(NC, false), st,
+                       pr->W_dp, pr->f64_rank, pr->f64_rank_val, perm, rows, cost, ghat, datap);
+}
 
 int dtfm_fast64_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows, double *cost, double *ghat,
                         double *datap, hipStream_t st)
 {
     if (rows == 0) return DTFM_OK;
-    const int nc = use_four(pr, rows) ? 4 : 8;
-    size_t passes = (rows + nc - 1) / nc;
-    size_t blocks = (passes + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-    if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    if (nc == 4)
-        hipLaunchKernelGGL(k_eval_fast64<4>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
-                           pr->f64_rank, pr->f64_rank_val, perm, rows, cost, ghat, datap);
-    else
-        hipLaunchKernelGGL(k_eval_fast64<8>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st, pr->W_dp,
-                           pr->f64_rank, pr->f64_rank_val, perm, rows, cost, ghat, datap);
+    switch (group_size(pr, rows)) {
+    case 32: launch_eval<32>(pr, perm, rows, cost, ghat, datap, st); break;
+    case 8: launch_eval<8>(pr, perm, rows, cost, ghat, datap, st); break;
+    default: launch_eval<4>(pr, perm, rows, cost, ghat, datap, st); break;
+    }
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
+}
+
+template <int NC>
+static void launch_ls(const dtfm_problem *pr, int32_t *perm, size_t rows, int moves, double *cost, int64_t *applied,
+                      hipStream_t st)
+{
+    size_t passes = (rows + NC - 1) / NC;
+    size_t blocks = (passes + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
+    hipLaunchKernelGGL(k_ls_gain4_fast64<NC>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), lds_total(NC, true), st,
+                       pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied);
 }
 
 int dtfm_fast64_ls_gain4_enqueue(const dtfm_problem *pr, int32_t *perm, size_t rows, int moves, double *cost,
                                  int64_t *applied, hipStream_t st)
 {
     if (rows == 0) return DTFM_OK;
-    const int nc = use_four(pr, rows) ? 4 : 8;
-    size_t passes = (rows + nc - 1) / nc;
-    size_t blocks = (passes + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-    if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    if (nc == 4)
-        hipLaunchKernelGGL(k_ls_gain4_fast64<4>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st,
-                           pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied);
-    else
-        hipLaunchKernelGGL(k_ls_gain4_fast64<8>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), LDS_TOTAL, st,
-                           pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied);
+    switch (group_size(pr, rows)) {
+    case 32: launch_ls<32>(pr, perm, rows, moves, cost, applied, st); break;
+    case 8: launch_ls<8>(pr, perm, rows, moves, cost, applied, st); break;
+    default: launch_ls<4>(pr, perm, rows, moves, cost, applied, st); break;
+    }
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
 }

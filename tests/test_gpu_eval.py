@@ -59,8 +59,8 @@ def test_config2_full_population(name, P):
         assert np.all(c == c[0])
 
 
-def test_config2_large_population_four_candidates_per_wavefront():
-    # populations of 16384 and more take the four-candidates-per-wavefront variant of the fused kernel
+def test_config2_population_eight_candidates_per_wavefront():
+    # populations between 4097 and 65535 take the eight-candidates-per-wavefront variant of the fused kernel
     w = workloads.config("C2")
     o, g = both(w)
     perms = workloads.random_population(20003, 64, seed=11)
@@ -70,6 +70,26 @@ def test_config2_large_population_four_candidates_per_wavefront():
     ghat, datap = dtfm.coarsened_graph(g, dperm)
     ghat, datap = host(ghat), host(datap)
     for p in (0, 1, 2, 3, 9999, 20000, 20001, 20002):
+        assert np.array_equal(ghat[p], o.coarsen(perms[p])) and datap[p] == o.datap(perms[p])
+
+
+def test_config2_population_thirty_two_candidates_per_wavefront():
+    # 65536 candidates and more: 32 per wavefront pass (7 full matching passes, 4 Held-Karp passes);
+    # 65573 = 2049 groups of 32 with a ragged last group of 5
+    w = workloads.config("C2")
+    o, g = both(w)
+    P = 65573
+    perms = workloads.random_population(P, 64, seed=13)
+    dperm = dev(perms)
+    c = host(dtfm.eval_population(g, dperm))
+    sel = np.r_[0:1100, 30000:31100, P - 1100:P]
+    assert_costs_equal(c[sel], o.eval_population(perms[sel]))
+    # every row: the same bits as the four-per-wavefront variant gives on chunks of 4096
+    for lo in range(0, P, 4096):
+        assert np.array_equal(c[lo:lo + 4096], host(dtfm.eval_population(g, dperm[lo:lo + 4096].contiguous())))
+    ghat, datap = dtfm.coarsened_graph(g, dperm)
+    ghat, datap = host(ghat), host(datap)
+    for p in (0, 31, 32, 33, 40000, P - 6, P - 5, P - 1):
         assert np.array_equal(ghat[p], o.coarsen(perms[p])) and datap[p] == o.datap(perms[p])
 
 

@@ -68,13 +68,15 @@ def test_gain4_config2():
     assert (applied >= 0).any()
 
 
-def test_gain4_large_population_four_candidates_per_wavefront():
+@pytest.mark.parametrize("P", [16500, 65573])
+def test_gain4_large_population_variants(P):
+    # 16500: eight candidates per wavefront pass; 65573: thirty-two, with a ragged last group
     w = workloads.config("C2")
     o, g = both(w)
-    perms = workloads.random_population(16500, 64, seed=12)
+    perms = workloads.random_population(P, 64, seed=12)
     d = dev(perms)
     cost, applied = dtfm.local_search(g, d, 3, dtfm.GAIN4, want_applied=True)
-    sel = np.r_[0:40, 8000:8040, 16460:16500]
+    sel = np.r_[0:40, 8000:8040, P - 40:P]
     rp, rc, ra = o.local_search(perms[sel], 3, oracle.GAIN4)
     assert np.array_equal(host(d)[sel], rp) and np.array_equal(host(applied)[sel], ra)
     assert_costs_equal(host(cost)[sel], rc)
