@@ -46,9 +46,10 @@ import workloads  # noqa: E402
 # (fp64 add/min/max issue at full rate), twice that for packed 16-bit ops.
 VALU_LANE_OPS_PER_S = 256 * 4 * 16 * 2.4e9
 # HBM bytes per candidate of the evaluation kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/k_eval_fast64_C2_P1048576.md (271.8 MB + 10.5 MB per 1,048,576 candidates,
-# each counter scaled by its reading for a 1 GiB device copy). Algorithmic: 4N + 8 = 264 B.
-MEASURED_HBM_BYTES_PER_CANDIDATE = 269.2
+# summarised in profiles/k_eval_fast64_C2_P1048576.md (297.1 MB + 16.3 MB per 1,048,576 candidates,
+# each counter scaled by its reading for a 1 GiB device copy; 19 MB of the reads are the 72 KiB of
+# tables every workgroup stages in LDS). Algorithmic: 4N + 8 = 264 B.
+MEASURED_HBM_BYTES_PER_CANDIDATE = 298.8
 
 
 def algorithmic_ops(N, D_dp, D_pp):
@@ -115,7 +116,7 @@ def main():
         # launch size, and a plain copy of known size to calibrate the HBM byte counters
         perms = torch.from_numpy(workloads.random_population(1 << 16, N, seed=3)).cuda().repeat(16, 1).contiguous()
         out = torch.empty(perms.shape[0], dtype=torch.float64, device="cuda")
-        for _ in range(10):
+        for _ in range(40):
             dtfm.eval_population(prob, perms, out)
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -142,26 +143,27 @@ def main():
     best = float(trace[-1].item()) if args.steps > 0 else float("nan")
 
     # ---- roofline of the population-evaluation work, HIP events on the launch stream ---------
-    def time_eval(Pe, reps):
+    def time_eval(Pe, reps, warm):
+        """Average duration of one dtfm_eval_population launch on Pe candidates: `warm` untimed
+        launches (the clocks of an idle part take some tens of milliseconds to come up), then `reps`
+        launches back to back between two HIP events recorded on the launch stream."""
         base = torch.from_numpy(workloads.random_population(min(Pe, 1 << 16), N, seed=3)).cuda()
         perms = base if Pe <= base.shape[0] else base.repeat(Pe // base.shape[0], 1).contiguous()
         out = torch.empty(Pe, dtype=torch.float64, device="cuda")
-        for _ in range(3):
+        for _ in range(warm):
             dtfm.eval_population(prob, perms, out)
-        torch.cuda.synchronize()
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for a, b in ev:
-            a.record()
+        start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for _ in range(reps):
             dtfm.eval_population(prob, perms, out)
-            b.record()
+        end.record()
         torch.cuda.synchronize()
-        ms = np.array([a.elapsed_time(b) for a, b in ev])
-        return float(ms.mean()) * 1e-3
+        return start.elapsed_time(end) * 1e-3 / reps
 
     ops = algorithmic_ops(N, w.D_dp, w.D_pp)
-    t_small = time_eval(P, 50)
+    t_small = time_eval(P, 200, 50)
     P_big = 1 << 20
-    t_big = time_eval(P_big, 10)
+    t_big = time_eval(P_big, 100, 30)
     ops64 = ops["datap_fp64"] + ops["held_karp_fp64"]
     ops16 = ops["matching_u16"]
     total_ops = ops64 + ops16
@@ -174,7 +176,7 @@ def main():
                 "traffic_unit": "bytes per launch (rocprofv3 counters, see profiles/)",
                 "algorithmic_hbm_bytes_per_launch": (4 * N + 8) * P_big,
                 "kernel": "k_eval_fast64 (dtfm_eval_population)", "launch_candidates": P_big,
-                "launch_seconds": t_big, "ops_per_candidate": ops,
+                "launch_seconds": t_big, "launches_timed": 100, "ops_per_candidate": ops,
                 "eval_population_cands_per_s": {"P=4096": P / t_small, "P=1048576": P_big / t_big}}
 
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
