@@ -288,17 +288,15 @@ __device__ __forceinline__ uint32_t byte_of(uint2 v, int k) { return ((k < 4 ? v
 
 // index of the stage pair (a, b), a < b, in lexicographic order
 __device__ __forceinline__ int pair_index(int a, int b) { return a * 7 - a * (a - 1) / 2 + (b - a - 1); }
-// the inverse: e-th pair -> (i, k)
+// the inverse: e-th pair -> (i, k); the pairs starting with i = 0..6 begin at e = 0, 7, 13, 18, 22, 25, 27
 __device__ __forceinline__ void pair8_decode(int e, int &i, int &k)
 {
-    int a = 0;
-    while (e >= 7 - a) {
-        e -= 7 - a;
-        a++;
-    }
+    const int a = (e >= 7) + (e >= 13) + (e >= 18) + (e >= 22) + (e >= 25) + (e >= 27);
     i = a;
-    k = a + 1 + e;
+    k = e - (a * 7 - a * (a - 1) / 2) + a + 1;
 }
+// byte k (0..7, not known at compile time) of a 64-bit value held as two dwords
+__device__ __forceinline__ uint32_t byte_at(uint2 v, int k) { return ((k < 4 ? v.x : v.y) >> (8 * (k & 3))) & 0xFFu; }
 
 // Per-wavefront context: LDS pointers and the lane's fixed roles.
 struct wave_ctx {
@@ -518,6 +516,9 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
     const double *res = reinterpret_cast<const double *>(wl + off_res(NC));
     double *curc = reinterpret_cast<double *>(wl + off_curc(NC));
     const int sub = lane & 15;   // proposal role: 16 lanes per candidate, four candidates per pass
+    int ea_i, ea_k, eb_i, eb_k;   // the two slot pairs this lane looks at when the fastest link is sought
+    pair8_decode(sub, ea_i, ea_k);
+    pair8_decode(sub < 12 ? sub + 16 : sub, eb_i, eb_k);
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
     const size_t ngroups = (P + NC - 1) / NC;
     for (size_t grp = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; grp < ngroups; grp += nwaves) {
@@ -539,49 +540,41 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
             const int Cj = 8 * j, Cjp = 8 * jp;
 #pragma nounroll
             for (int pass = 0; pass < NC / 4; pass++) {
-                // ---- proposal for candidate slot 4 * pass + lane / 16 by its 16 lanes ----
+                // ---- proposal for candidate slot 4 * pass + lane / 16 by its 16 lanes: registers and
+                // lane exchanges only, apart from the table gathers ----
                 const int pslot = 4 * pass + (lane >> 4);
                 const unsigned char *pc = pbcur + pslot * 64;
+                const uint2 cdev[2] = {*reinterpret_cast<const uint2 *>(pc + Cj), *reinterpret_cast<const uint2 *>(pc + Cjp)};
                 int slot[2][2];
 #pragma unroll
                 for (int s = 0; s < 2; s++) {
-                    const unsigned char *C = pc + (s == 0 ? Cj : Cjp);
-                    uint32_t key = 0xFFFFFFFFu;   // (rank << 8) | pair index: first minimiser wins
-#pragma unroll
-                    for (int e0 = 0; e0 < 32; e0 += 16) {
-                        const int e = e0 + sub;
-                        if (e < 28) {
-                            int i, k;
-                            pair8_decode(e, i, k);
-                            const uint32_t kk = ((uint32_t)cx.R[(int)C[i] * RSTRIDE + C[k]] << 8) | (uint32_t)e;
-                            key = kk < key ? kk : key;
-                        }
-                    }
-#pragma unroll
-                    for (int o = 1; o <= 8; o <<= 1) {
-                        const uint32_t ok = __shfl_xor(key, o);
-                        key = ok < key ? ok : key;
-                    }
+                    // fastest link inside the stage: key = (rank << 8) | pair index, first minimiser wins;
+                    // this lane looks at slot pairs `sub` and `sub + 16`
+                    uint32_t key = ((uint32_t)cx.R[byte_at(cdev[s], ea_i) * RSTRIDE + byte_at(cdev[s], ea_k)] << 8) | (uint32_t)sub;
+                    const uint32_t kb = ((uint32_t)cx.R[byte_at(cdev[s], eb_i) * RSTRIDE + byte_at(cdev[s], eb_k)] << 8) | (uint32_t)(sub + 16);
+                    if (sub < 12 && kb < key) key = kb;
+                    key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x128, 0xF, 0xF, true));   // row_ror:8
+                    key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x124, 0xF, 0xF, true));   // row_ror:4
+                    key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x122, 0xF, 0xF, true));   // row_ror:2
+                    key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x121, 0xF, 0xF, true));   // row_ror:1
                     pair8_decode((int)(key & 0xFFu), slot[s][0], slot[s][1]);
                 }
-                // lanes 0,1 of the group: mean over C_j' of w[x][.] for x = d1, d2; lanes 2,3: mean over C_j of w[y][.]
-                double mean = 0.0;
+                // every quad of lanes computes the four means itself: lanes 0,1 the mean over C_j' of w[x][.] for
+                // x = d1, d2; lanes 2,3 the mean over C_j of w[y][.] for y = d1', d2'
+                double mean;
                 {
-                    const int side = (sub >> 1) & 1;
-                    const int dv = pc[(side == 0 ? Cj : Cjp) + slot[side][sub & 1]];
-                    const unsigned char *other = pc + (side == 0 ? Cjp : Cj);
+                    const int side = (lane >> 1) & 1, which = lane & 1;
+                    const uint32_t dv = byte_at(cdev[side], side == 0 ? slot[0][which] : slot[1][which]);
+                    const uint2 other = cdev[side ^ 1];
                     double sum = 0.0;
-                    if (sub < 4) {
 #pragma unroll
-                        for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, cx.Wpp[dv * NDEV + other[i]]);
-                    }
+                    for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, cx.Wpp[dv * NDEV + byte_of(other, i)]);
                     mean = __ddiv_rn(sum, 8.0);
                 }
-                const double link0 = cx.Wpp[(int)pc[Cj + slot[0][0]] * NDEV + pc[Cj + slot[0][1]]];
-                const double link1 = cx.Wpp[(int)pc[Cjp + slot[1][0]] * NDEV + pc[Cjp + slot[1][1]]];
-                const int base = lane & ~15;
-                const double mx[2] = {__shfl(mean, base + 0), __shfl(mean, base + 1)};
-                const double my[2] = {__shfl(mean, base + 2), __shfl(mean, base + 3)};
+                const double link0 = cx.Wpp[byte_at(cdev[0], slot[0][0]) * NDEV + byte_at(cdev[0], slot[0][1])];
+                const double link1 = cx.Wpp[byte_at(cdev[1], slot[1][0]) * NDEV + byte_at(cdev[1], slot[1][1])];
+                const double mx[2] = {dpp_move<0x00>(mean), dpp_move<0x55>(mean)};   // lane 0 / lane 1 of the quad
+                const double my[2] = {dpp_move<0xAA>(mean), dpp_move<0xFF>(mean)};   // lane 2 / lane 3
                 double bestg = 0.0;
                 int bk = -1;
 #pragma unroll

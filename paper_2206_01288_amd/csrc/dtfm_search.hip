@@ -506,11 +506,27 @@ __global__ void k_rank_count(const double *__restrict__ cost, const double *__re
     const double ci = i < P ? cost[i] : off_cost[i - P];
     const int j1 = j0 + DTFM_RANK_CHUNK < n ? j0 + DTFM_RANK_CHUNK : n;
     int cnt = 0;
-    // the key index j is the same for every lane: the keys come through the scalar cache
+    // the key index j is the same for every lane: the keys come through the scalar cache. A chunk that
+    // lies wholly before (after) this block's elements needs no index comparison: ties go to the key.
+    const int i0 = blockIdx.x * blockDim.x;
+    if (j1 <= i0) {
 #pragma unroll 8
-    for (int j = j0; j < j1; j++) {
-        const double cj = j < P ? cost[j] : off_cost[j - P];
-        cnt += (cj < ci || (cj == ci && j < i)) ? 1 : 0;
+        for (int j = j0; j < j1; j++) {
+            const double cj = j < P ? cost[j] : off_cost[j - P];
+            cnt += cj <= ci ? 1 : 0;
+        }
+    } else if (j0 >= i0 + (int)blockDim.x) {
+#pragma unroll 8
+        for (int j = j0; j < j1; j++) {
+            const double cj = j < P ? cost[j] : off_cost[j - P];
+            cnt += cj < ci ? 1 : 0;
+        }
+    } else {
+#pragma unroll 8
+        for (int j = j0; j < j1; j++) {
+            const double cj = j < P ? cost[j] : off_cost[j - P];
+            cnt += (cj < ci || (cj == ci && j < i)) ? 1 : 0;
+        }
     }
     if (cnt) atomicAdd(&rank[i], cnt);
 }
@@ -536,13 +552,17 @@ __global__ void k_fill_i32(int32_t *__restrict__ dst, int32_t v, size_t n)
     if (i < n) dst[i] = v;
 }
 
-__global__ void k_gather_rows(const int32_t *__restrict__ pop, const int32_t *__restrict__ off, int P, int N,
-                              const int32_t *__restrict__ src, int32_t *__restrict__ next)
+// Copies the survivors' rows in rank order; also clears the rank counters for the next generation
+// (they have been consumed by k_rank_place).
+__global__ void k_gather_rows(const int32_t *__restrict__ pop, const int32_t *__restrict__ off, int P, int L, int N,
+                              const int32_t *__restrict__ src, int32_t *__restrict__ next, int32_t *__restrict__ rank)
 {
     size_t r = blockIdx.x;
     int o = src[r];
     const int32_t *s = o < P ? pop + (size_t)o * N : off + (size_t)(o - P) * N;
     for (int q = threadIdx.x; q < N; q += blockDim.x) next[r * N + q] = s[q];
+    if (threadIdx.x == 0)
+        for (int k = (int)r; k < P + L; k += P) rank[k] = 0;
 }
 
 dtfm_ga_bufs dtfm_ga_carve(const dtfm_problem *pr, dtfm_arena &ar, const dtfm_ga_params &prm)
@@ -572,27 +592,38 @@ int dtfm_ga_enqueue(const dtfm_problem *pr, const dtfm_ga_bufs &b, uint64_t seed
     }
     int rc = dtfm_eval_enqueue(pr, b.ls.ev, population, P, cost, st);
     if (rc != DTFM_OK) return rc;
+    const int nk = P + L;
+    hipLaunchKernelGGL(k_fill_i32, dim3((nk + 255) / 256), dim3(256), 0, st, b.rank, 0, (size_t)nk);
+    DTFM_HIP(hipGetLastError());
+    // the population alternates between the caller's buffers and the arena's
+    int32_t *pop_cur = population, *pop_next = b.next;
+    double *cost_cur = cost, *cost_next = b.next_cost;
     for (int g = 0; g < generations; g++) {
         hipLaunchKernelGGL(k_make_offspring, dim3(L), dim3(DTFM_WAVE), 3 * N * sizeof(int32_t), st, k0, k1,
-                           (uint32_t)g, population, P, N, pr->D_dp, prm.m_x, prm.m_m, b.off);
+                           (uint32_t)g, pop_cur, P, N, pr->D_dp, prm.m_x, prm.m_m, b.off);
         DTFM_HIP(hipGetLastError());
         rc = dtfm_ls_enqueue(pr, b.ls, b.off, L, prm.ls_moves, prm.neighbourhood, b.off_cost, nullptr, st);
         if (rc != DTFM_OK) return rc;
-        const int nk = P + L;
-        hipLaunchKernelGGL(k_fill_i32, dim3((nk + 255) / 256), dim3(256), 0, st, b.rank, 0, (size_t)nk);
-        DTFM_HIP(hipGetLastError());
         hipLaunchKernelGGL(k_rank_count, dim3((nk + 255) / 256, (nk + DTFM_RANK_CHUNK - 1) / DTFM_RANK_CHUNK), dim3(256), 0,
-                           st, cost, b.off_cost, P, L, b.rank);
+                           st, cost_cur, b.off_cost, P, L, b.rank);
         DTFM_HIP(hipGetLastError());
-        hipLaunchKernelGGL(k_rank_place, dim3((nk + 255) / 256), dim3(256), 0, st, cost, b.off_cost, P, L, b.rank,
-                           b.next_cost, b.src, best_trace + g);
+        hipLaunchKernelGGL(k_rank_place, dim3((nk + 255) / 256), dim3(256), 0, st, cost_cur, b.off_cost, P, L, b.rank,
+                           cost_next, b.src, best_trace + g);
         DTFM_HIP(hipGetLastError());
-        hipLaunchKernelGGL(k_gather_rows, dim3(P), dim3(DTFM_WAVE), 0, st, population, b.off, P, N, b.src, b.next);
+        hipLaunchKernelGGL(k_gather_rows, dim3(P), dim3(DTFM_WAVE), 0, st, pop_cur, b.off, P, L, N, b.src, pop_next, b.rank);
         DTFM_HIP(hipGetLastError());
+        int32_t *tp = pop_cur;
+        pop_cur = pop_next;
+        pop_next = tp;
+        double *tc = cost_cur;
+        cost_cur = cost_next;
+        cost_next = tc;
+    }
+    if (pop_cur != population) {
         size_t n = (size_t)P * N;
-        hipLaunchKernelGGL(k_copy_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, b.next, population, n);
+        hipLaunchKernelGGL(k_copy_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, pop_cur, population, n);
         DTFM_HIP(hipGetLastError());
-        hipLaunchKernelGGL(k_copy_f64, dim3((P + 255) / 256), dim3(256), 0, st, b.next_cost, cost, (size_t)P);
+        hipLaunchKernelGGL(k_copy_f64, dim3((P + 255) / 256), dim3(256), 0, st, cost_cur, cost, (size_t)P);
         DTFM_HIP(hipGetLastError());
     }
     return DTFM_OK;
