@@ -29,7 +29,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 # Per-file additions. The fused 64-device kernels are long straight-line register programmes; the
 # default scheduler orders them for low register pressure, which leaves every packed 16-bit result
 # one wait state away from its consumer. The ILP-first strategy interleaves the independent chains.
-FILE_FLAGS = {"dtfm_fast64.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"]}
+_ILP = ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"]
+FILE_FLAGS = {"dtfm_fast64.hip": _ILP, "dtfm_fast64_allpairs.hip": _ILP}
 
 
 def sources():

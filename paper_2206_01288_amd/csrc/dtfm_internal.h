@@ -48,7 +48,6 @@ struct dtfm_problem {
     bool fast64;
     uint16_t *f64_rank;     // device, N*N: rank of W_pp[d][d'] among all off-diagonal weights
     double *f64_rank_val;   // device, N*N: rank -> weight
-    uint32_t *f64_steps;    // device: per-lane item tables of the layered programmes
     int f64_grid;           // workgroups launched (one per CU)
 };
 
@@ -107,6 +106,12 @@ int dtfm_fast64_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows
 // all `moves` rounds of the GAIN4 local search in one launch; perm in/out, cost out, applied may be null
 int dtfm_fast64_ls_gain4_enqueue(const dtfm_problem *pr, int32_t *perm, size_t rows, int moves, double *cost,
                                  int64_t *applied, hipStream_t st);
+
+// all `moves` >= 1 rounds of the ALL_PAIRS local search with incremental move evaluation in one launch
+// (dtfm_fast64_allpairs.hip); perm in/out, cost out, applied may be null
+int dtfm_fast64_allpairs_prepare();
+int dtfm_fast64_ls_allpairs_enqueue(const dtfm_problem *pr, int32_t *perm, size_t rows, int moves, double *cost,
+                                    int64_t *applied, hipStream_t st);
 
 // ---- search (dtfm_search.hip) -----------------------------------------------------------------
 struct dtfm_ls_bufs {

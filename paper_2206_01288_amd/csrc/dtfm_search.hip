@@ -317,6 +317,8 @@ int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm
     if (P == 0) return DTFM_OK;
     if (pr->fast64 && neighbourhood == DTFM_GAIN4)
         return dtfm_fast64_ls_gain4_enqueue(pr, perm, P, moves, cost, applied, st);
+    if (pr->fast64 && neighbourhood == DTFM_ALL_PAIRS && moves > 0)
+        return dtfm_fast64_ls_allpairs_enqueue(pr, perm, P, moves, cost, applied, st);
     const int N = pr->N;
     const long long M = (long long)N * (N - 1) / 2;
     int rc = dtfm_eval_enqueue(pr, b.ev, perm, P, b.cur, st);
