@@ -125,6 +125,13 @@ int dtfm_validate_population(dtfm_problem *prob, const int32_t *perm, int P, int
 int dtfm_local_search(dtfm_problem *prob, int32_t *perm, int P, int moves, int neighbourhood,
                       double *cost, int64_t *applied, void *hip_stream);
 
+/* Move evaluation of the local search (Sec. 3.4, "find o* that leads to better cost"): the cost
+ * (Eq. 1) of every allocation one swap away from each row. move_cost: device, P*N(N-1)/2 doubles,
+ * out: at [p*N(N-1)/2 + m] the cost of row p with positions a < b exchanged, m the index of (a, b)
+ * in lexicographic order, m = a*N - a(a+1)/2 + (b-a-1); the same bits as dtfm_eval_population on
+ * the swapped row. perm: device, P*N, read only. Enqueues only. Errors: NULL, ARG (P < 0), HIP. */
+int dtfm_move_costs(dtfm_problem *prob, const int32_t *perm, int P, double *move_cost, void *hip_stream);
+
 /* Parameters of the evolutionary search. */
 typedef struct {
     int32_t P;              /* population size, >= 1 */

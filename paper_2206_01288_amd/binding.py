@@ -17,7 +17,8 @@ KL = 2
 # every entry point include/dtfm.h declares
 DECLARED_SYMBOLS = [
     "dtfm_create_problem", "dtfm_destroy_problem", "dtfm_get_weights", "dtfm_eval_population",
-    "dtfm_coarsened_graph", "dtfm_get_assignment", "dtfm_validate_population", "dtfm_local_search", "dtfm_evolve",
+    "dtfm_coarsened_graph", "dtfm_get_assignment", "dtfm_validate_population", "dtfm_local_search",
+    "dtfm_move_costs", "dtfm_evolve",
     "dtfm_philox_blocks", "dtfm_status_string", "dtfm_last_hip_error",
 ]
 
@@ -60,6 +61,7 @@ def load_library():
     L.dtfm_get_assignment.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p]
     L.dtfm_validate_population.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p]
     L.dtfm_local_search.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p]
+    L.dtfm_move_costs.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p]
     L.dtfm_evolve.argtypes = [c_void_p, c_uint64, c_int, POINTER(GAParams), c_void_p, c_void_p, c_void_p, c_void_p]
     L.dtfm_philox_blocks.argtypes = [c_uint64, c_uint32, c_uint32, c_uint32, c_uint32, c_int, c_void_p, c_void_p]
     L.dtfm_status_string.argtypes = [c_int]
@@ -205,6 +207,18 @@ def local_search(prob: Problem, perm, moves: int, neighbourhood: int = ALL_PAIRS
                                _dev_ptr(applied, torch.int64, P * moves, "applied") if applied is not None
                                else c_void_p(0), _stream(stream)))
     return cost, applied
+
+
+def move_costs(prob: Problem, perm, out=None, stream=None):
+    """perm: device int32 [P, N] (read only). Returns the cost of every swap, device float64 [P, N(N-1)/2]."""
+    import torch
+    L = load_library()
+    P, M = perm.shape[0], prob.N * (prob.N - 1) // 2
+    if out is None:
+        out = torch.empty((P, M), dtype=torch.float64, device=perm.device)
+    _check(L.dtfm_move_costs(prob.handle, _dev_ptr(perm, torch.int32, P * prob.N, "perm"), P,
+                             _dev_ptr(out, torch.float64, P * M, "move_cost"), _stream(stream)))
+    return out
 
 
 def evolve(prob: Problem, seed: int, generations: int, P: int, lam=None, m_x=None, m_m: int = 1,

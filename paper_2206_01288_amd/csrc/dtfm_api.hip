@@ -266,6 +266,21 @@ extern "C" int dtfm_local_search(dtfm_problem *pr, int32_t *perm, int P, int mov
     return dtfm_ls_enqueue(pr, b, perm, (size_t)P, moves, neighbourhood, cost, applied, (hipStream_t)hip_stream);
 }
 
+extern "C" int dtfm_move_costs(dtfm_problem *pr, const int32_t *perm, int P, double *move_cost, void *hip_stream)
+{
+    if (pr == nullptr) return DTFM_ERR_NULL;
+    if (P < 0) return DTFM_ERR_ARG;
+    if (P == 0 || pr->N < 2) return DTFM_OK;
+    if (perm == nullptr || move_cost == nullptr) return DTFM_ERR_NULL;
+    dtfm_arena measure = {nullptr, 0};
+    dtfm_ls_carve(pr, measure, (size_t)P, DTFM_ALL_PAIRS);
+    int rc = ensure_scratch(pr, measure.off);
+    if (rc != DTFM_OK) return rc;
+    dtfm_arena ar = {pr->scratch, 0};
+    dtfm_ls_bufs b = dtfm_ls_carve(pr, ar, (size_t)P, DTFM_ALL_PAIRS);
+    return dtfm_move_costs_enqueue(pr, b, perm, (size_t)P, move_cost, (hipStream_t)hip_stream);
+}
+
 extern "C" int dtfm_evolve(dtfm_problem *pr, uint64_t seed, int generations, const dtfm_ga_params *prm,
                            int32_t *population, double *cost, double *best_trace, void *hip_stream)
 {

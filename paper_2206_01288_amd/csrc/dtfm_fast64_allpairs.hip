@@ -20,6 +20,7 @@
 namespace {
 
 // ---- per-wavefront LDS slice ----
+constexpr int N_MOVES = NDEV * (NDEV - 1) / 2;
 constexpr int AP_OFF_CUR = 0;                          // u8 [64]: the candidate's current row, stage-major
 constexpr int AP_OFF_EDGE = AP_OFF_CUR + 64;           // u16 [64 + 64 + 2*64*8]: edge ranks, one index space:
 constexpr int AP_EDGE_GBM = 0;                         //   [u][v]      the round's own coarsened graph
@@ -94,7 +95,7 @@ __device__ __forceinline__ void keep_best(double &bc, uint32_t &bk, double c, ui
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
 k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank_tab,
                      const double *__restrict__ rank_val_g, int32_t *__restrict__ perm, size_t P, int moves,
-                     double *__restrict__ cost, int64_t *__restrict__ applied)
+                     double *__restrict__ cost, int64_t *__restrict__ applied, double *__restrict__ move_cost)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     stage_tables(smem, rank_tab, rank_val_g, W_dp);
@@ -221,6 +222,8 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
                     const double total = __dadd_rn(dpm[mv], pp);
                     const uint32_t a = 8 * j + (mv >> 3), b = 8 * jp + (mv & 7);
                     keep_best(bestc, bestk, total, 64 * a + b);
+                    if (move_cost != nullptr && hv == 0)
+                        move_cost[cand * (size_t)N_MOVES + (a * NDEV - a * (a + 1) / 2 + (b - a - 1))] = total;
                     if (bpass == 7) WAVE_LDS_SYNC();   // the next batch overwrites the slice
                 }
             }
@@ -240,7 +243,11 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
 #pragma unroll
                 for (int q = 0; q < 8; q++)
                     if (q != s) d = fmax(d, dpb[q]);
-                if (valid) keep_best(bestc, bestk, __dadd_rn(d, pp_base), 64 * (8 * s + i) + (8 * s + k));
+                const uint32_t a = 8 * s + i, b = 8 * s + k;
+                const double total = __dadd_rn(d, pp_base);
+                if (valid) keep_best(bestc, bestk, total, 64 * a + b);
+                if (move_cost != nullptr && valid)
+                    move_cost[cand * (size_t)N_MOVES + (a * NDEV - a * (a + 1) / 2 + (b - a - 1))] = total;
             }
             // ---- cheapest swap of the round (lowest index on ties); applied iff strictly cheaper ----
 #pragma unroll
@@ -249,6 +256,7 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
                 const uint32_t ok = (uint32_t)__shfl_xor((int)bestk, o);
                 keep_best(bestc, bestk, oc, ok);
             }
+            if (move_cost != nullptr) break;   // pricing only: the row stays as it is
             const bool take = bestc < cur_cost;
             const int a = (int)(bestk >> 6), b = (int)(bestk & 63);
             if (applied != nullptr && lane == 0)
@@ -265,8 +273,10 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
             }
             WAVE_LDS_SYNC();
         }
-        perm[cand * NDEV + lane] = cur[lane];
-        if (lane == 0) cost[cand] = cur_cost;
+        if (move_cost == nullptr) {
+            perm[cand * NDEV + lane] = cur[lane];
+            if (lane == 0) cost[cand] = cur_cost;
+        }
         WAVE_LDS_SYNC();
     }
 }
@@ -289,7 +299,21 @@ int dtfm_fast64_ls_allpairs_enqueue(const dtfm_problem *pr, int32_t *perm, size_
     size_t blocks = (rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
     hipLaunchKernelGGL(k_ls_allpairs_fast64, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), AP_LDS_TOTAL, st, pr->W_dp,
-                       pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied);
+                       pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied, (double *)nullptr);
+    DTFM_HIP(hipGetLastError());
+    return DTFM_OK;
+}
+
+// The cost of every swap of every row: move_cost[p * 2016 + move index]; perm is only read.
+int dtfm_fast64_move_costs_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows, double *move_cost,
+                                   hipStream_t st)
+{
+    if (rows == 0) return DTFM_OK;
+    size_t blocks = (rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
+    hipLaunchKernelGGL(k_ls_allpairs_fast64, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), AP_LDS_TOTAL, st, pr->W_dp,
+                       pr->f64_rank, pr->f64_rank_val, const_cast<int32_t *>(perm), rows, 1, (double *)nullptr,
+                       (int64_t *)nullptr, move_cost);
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
 }

@@ -113,6 +113,10 @@ int dtfm_fast64_allpairs_prepare();
 int dtfm_fast64_ls_allpairs_enqueue(const dtfm_problem *pr, int32_t *perm, size_t rows, int moves, double *cost,
                                     int64_t *applied, hipStream_t st);
 
+// cost of every swap of every row (rows * 2016 doubles); perm is only read
+int dtfm_fast64_move_costs_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows, double *move_cost,
+                                   hipStream_t st);
+
 // ---- search (dtfm_search.hip) -----------------------------------------------------------------
 struct dtfm_ls_bufs {
     double *cur;        // P: current cost of each candidate
@@ -126,6 +130,10 @@ struct dtfm_ls_bufs {
 dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int neighbourhood);
 int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm, size_t P, int moves,
                     int neighbourhood, double *cost, int64_t *applied, hipStream_t st);
+
+// cost of every swap a < b of every row, out[p * N(N-1)/2 + move index]
+int dtfm_move_costs_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, const int32_t *perm, size_t P, double *out,
+                            hipStream_t st);
 
 struct dtfm_ga_bufs {
     int32_t *off;       // lambda * N

@@ -311,6 +311,24 @@ dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int
     return b;
 }
 
+int dtfm_move_costs_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, const int32_t *perm, size_t P, double *out,
+                            hipStream_t st)
+{
+    const int N = pr->N;
+    const long long M = (long long)N * (N - 1) / 2;
+    if (P == 0 || M == 0) return DTFM_OK;
+    if (pr->fast64) return dtfm_fast64_move_costs_enqueue(pr, perm, P, out, st);
+    for (size_t p0 = 0; p0 < P; p0 += b.chunk) {
+        size_t cp = P - p0 < b.chunk ? P - p0 : b.chunk;
+        size_t rows = cp * (size_t)M;
+        hipLaunchKernelGGL(k_make_swapped, dim3((unsigned)rows), dim3(DTFM_WAVE), 0, st, perm, N, M, p0, b.tmp_perm);
+        DTFM_HIP(hipGetLastError());
+        int rc = dtfm_eval_enqueue(pr, b.ev, b.tmp_perm, rows, out + p0 * (size_t)M, st);
+        if (rc != DTFM_OK) return rc;
+    }
+    return DTFM_OK;
+}
+
 int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm, size_t P, int moves,
                     int neighbourhood, double *cost, int64_t *applied, hipStream_t st)
 {

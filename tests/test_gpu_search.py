@@ -37,6 +37,66 @@ def test_all_pairs_config3_sample():
     assert (applied >= 0).all()
 
 
+def _swapped_rows(row):
+    """every allocation one swap of positions a < b away from row, in move-index order"""
+    N = row.shape[0]
+    out = []
+    for a in range(N):
+        for b in range(a + 1, N):
+            r = row.copy()
+            r[a], r[b] = row[b], row[a]
+            out.append(r)
+    return np.array(out, dtype=np.int32)
+
+
+@pytest.mark.parametrize("name,rows", [("C2", (0, 5, 11)), ("C2b", (1,)), ("C3h", (2,)), ("C1", (0, 1, 2, 3)), ("C4", (0,))])
+def test_move_costs_every_swap_against_oracle(name, rows):
+    # incremental move evaluation (64-device shape) and the generic path: the cost of EVERY swap of a row
+    # equals the oracle's evaluation of the swapped row, bit for bit. C2b: the paper's table, heavy ties.
+    w = workloads.config(name)
+    o, g = both(w)
+    perms = workloads.random_population(12, w.N, seed=21)
+    if name == "C4":   # 32640 swaps of one row: the oracle prices a sample of them
+        mc = host(dtfm.move_costs(g, dev(perms[:1])))
+        sw = _swapped_rows(perms[0])
+        sel = np.r_[0:60, 16000:16060, sw.shape[0] - 60:sw.shape[0]]
+        assert_costs_equal(mc[0][sel], o.eval_population(sw[sel]))
+        return
+    mc = host(dtfm.move_costs(g, dev(perms)))
+    assert mc.shape == (12, w.N * (w.N - 1) // 2)
+    for p in rows:
+        assert_costs_equal(mc[p], o.eval_population(_swapped_rows(perms[p])))
+    # the argmin of a row's move costs is what one ALL_PAIRS round applies
+    d = dev(perms)
+    cur = host(dtfm.eval_population(g, d))
+    cost, applied = dtfm.local_search(g, d, 1, dtfm.ALL_PAIRS, want_applied=True)
+    best = np.argmin(mc, axis=1)
+    exp = np.where(mc[np.arange(12), best] < cur, best, -1)
+    assert np.array_equal(host(applied)[:, 0], exp)
+
+
+def test_all_pairs_paper_table_ties_fused():
+    # the paper's Case-5 tables (no jitter: many exactly equal weights) through the fused kernel
+    w = workloads.config("C2b")
+    _ls_parity(w, workloads.random_population(5, 64, seed=9), 3, dtfm.ALL_PAIRS)
+
+
+def test_all_pairs_ragged_candidate_counts():
+    # one wavefront per candidate, 8 per workgroup: counts around the workgroup size and the grid
+    w = workloads.config("C2")
+    o, g = both(w)
+    for P in (1, 7, 9, 2049):
+        perms = workloads.random_population(P, 64, seed=30 + P)
+        d = dev(perms)
+        cost, applied = dtfm.local_search(g, d, 2, dtfm.ALL_PAIRS, want_applied=True)
+        sel = np.unique(np.r_[0, P // 2, P - 1])
+        rp, rc, ra = o.local_search(perms[sel], 2, oracle.ALL_PAIRS)
+        assert np.array_equal(host(d)[sel], rp) and np.array_equal(host(applied)[sel], ra)
+        assert_costs_equal(host(cost)[sel], rc)
+        assert dtfm.validate_population(g, d) == 0
+        assert torch.equal(dtfm.eval_population(g, d), cost)
+
+
 def test_all_pairs_homogeneous_never_moves():
     w = workloads.config("C3h")
     o, g = both(w)
