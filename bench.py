@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--general-shapes", action="store_true",
                     help="only population evaluations at configurations C4 and C5 (for rocprofv3 runs of the "
                          "general-shape kernels)")
+    ap.add_argument("--all-pairs", action="store_true",
+                    help="only configuration 3: 20 rounds of the ALL_PAIRS local search on 4096 candidates (for "
+                         "rocprofv3 runs of the incremental move-evaluation kernel)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (candidates are independent; see DESIGN.md "
@@ -103,6 +106,25 @@ def main():
             res[name] = {"population": Pg, "ms_per_eval_population": (time.perf_counter() - t0) / 3 * 1e3}
             dtfm.destroy_problem(pg)
         print(json.dumps({"general_shapes": res}))
+        return
+
+    if args.all_pairs:
+        w3 = workloads.config("C3")
+        p3 = dtfm.create_problem(w3.latency, w3.bandwidth, w3.c_dp, w3.c_pp, w3.D_dp, w3.D_pp)
+        base = torch.from_numpy(workloads.random_population(4096, w3.N, seed=1)).cuda()
+        rounds, M = 20, w3.N * (w3.N - 1) // 2
+        dtfm.local_search(p3, base.clone(), rounds, dtfm.ALL_PAIRS)
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(3):
+            d = base.clone()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            dtfm.local_search(p3, d, rounds, dtfm.ALL_PAIRS)
+            torch.cuda.synchronize()
+            ms.append((time.perf_counter() - t0) * 1e3)
+        print(json.dumps({"all_pairs": {"candidates": 4096, "rounds": rounds, "moves_per_round": M, "ms": min(ms),
+                                        "move_evaluations_per_s": 4096 * rounds * M / (min(ms) * 1e-3)}}))
         return
 
     w = workloads.config("C2")
