@@ -1,6 +1,6 @@
 // Fused population-evaluation kernel for the 64-device shape (N = 64, D_dp = 8, D_pp = 8): one
-// wavefront evaluates eight candidates end to end (Eqs. 1-4); apart from the table gathers the whole
-// evaluation is register arithmetic.
+// wavefront evaluates a group of 4, 8 or 32 candidates end to end (Eqs. 1-4); apart from the table
+// gathers the whole evaluation is register arithmetic.
 //
 //   Matching (Eq. 3)   The bottleneck value of a block depends only on the ORDER of its entries,
 //                      so the kernel works on 16-bit ranks of W_pp (rank table in LDS, built once
@@ -8,19 +8,19 @@
 //                      bit-identical to working on the doubles. Per stage pair a min-max dynamic
 //                      programme over column subsets, row by row:
 //                          g[S] = min_{c in S} max(g[S \ c], w[|S|-1][c]),   g[all] = optimum.
-//                      Lane = (candidate 0..3, couple of stage pairs 0..13), two passes for the eight
-//                      candidates: two pairs packed in one 32-bit register, 16-bit packed max/min.
-//                      Every lane walks the subsets in the same order, so the whole table lives in
-//                      registers with compile-time indices: no table traffic, no index arithmetic,
-//                      2 ALU ops per transition.
+//                      A lane takes a couple of stage pairs of one candidate: two pairs packed in
+//                      one 32-bit register, 16-bit packed max/min. The work items are the 14 x NC
+//                      (candidate, couple) combinations, 64 per pass. Every lane walks the subsets
+//                      in the same order, so the whole table lives in registers with compile-time
+//                      indices: no table traffic, no index arithmetic, 2 ALU ops per transition.
 //   Held-Karp (Eq. 4)  lane = (candidate 0..7, stage v 0..7). The stages are taken as the group
 //                      Z_2^3: item (S, v) with S = v xor ({0} u D) belongs to class D (a subset of
 //                      {1..7}), and lane v holds the items (class D, v) of ALL classes, one register
 //                      pair per class. The relaxation tab[S][v] = min_u tab[S \ v][u] + Ghat[u][v] with
 //                      u = v xor d reads class (D \ d) xor d at lane v xor d: a compile-time register
-//                      and a lane exchange within the 8 lanes of the candidate, done by data-parallel
-//                      primitive moves (xor 1, 2, 3: quad permutations; xor 7: mirror of the 8 lanes;
-//                      xor 4, 5, 6: mirror, then a quad permutation). No memory traffic at all.
+//                      and a lane exchange within the 8 lanes of the candidate (xor 1, 2, 3: DPP quad
+//                      permutations; xor 7: DPP mirror of the 8 lanes; xor 4, 5, 6: through the LDS
+//                      crossbar, no memory access). No table traffic at all.
 //   DataP (Eq. 2)      lane = (candidate, stage): the 8 x 8 entries of W_dp (LDS copy) of the stage's
 //                      devices summed in slot order (the device's own slot adds the zero diagonal),
 //                      max over the stage, then over the 8 lanes of the candidate.
