@@ -61,6 +61,7 @@ def test_null_arguments():
     assert L.dtfm_eval_population(None, None, 1, None, None) == 1
     assert L.dtfm_local_search(None, None, 1, 1, 0, None, None, None) == 1
     assert L.dtfm_evolve(None, 0, 1, None, None, None, None, None) == 1
+    assert L.dtfm_move_costs(None, None, 1, None, None) == 1
     assert L.dtfm_philox_blocks(0, 0, 0, 0, 0, -1, None, None) == 4
     assert L.dtfm_philox_blocks(0, 0, 0, 0, 0, 3, None, None) == 1
     L.dtfm_destroy_problem(None)
