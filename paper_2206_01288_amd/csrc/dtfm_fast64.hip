@@ -87,7 +87,7 @@ __device__ __forceinline__ uint32_t match_couple(const wave_ctx &cx, const unsig
         coldev[h] = *reinterpret_cast<const uint2 *>(pb + 8 * j2[h]);   // devices of stage j2
     }
     uint32_t G[256];
-    match_rows<8>(cx.R, rowdev, coldev, G);
+    match_rows<8, true>(cx.R, rowdev, coldev, G);
     return G[255];
 }
 

@@ -130,7 +130,7 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
                 const uint2 rowdev[2] = {drop_byte(cj, i0), drop_byte(cj, i0 + 1)};
                 const uint2 coldev[2] = {ck, ck};
                 uint32_t G[256];
-                match_rows<7>(R, rowdev, coldev, G);
+                match_rows<7, false>(R, rowdev, coldev, G);
                 if (valid) {
                     uint32_t lo[4], hi[4];
 #pragma unroll
@@ -186,7 +186,7 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
                         const uint2 rowdev[2] = {put_byte(cj, si, byte_at(cjp, sp)), put_byte(cj, si, byte_at(cjp, sp + 1))};
                         const uint2 coldev[2] = {put_byte(cjp, sp, sx), put_byte(cjp, sp + 1, sx)};
                         uint32_t G[256];
-                        match_rows<8>(R, rowdev, coldev, G);
+                        match_rows<8, false>(R, rowdev, coldev, G);
                         if (lane < 32) reinterpret_cast<uint32_t *>(edge + AP_EDGE_SCR)[l] = G[255];
                     }
                     // DataP after the swap

@@ -266,12 +266,20 @@ __device__ __forceinline__ void pair8_decode(int e, int &i, int &k)
 // byte k (0..7, not known at compile time) of a 64-bit value held as two dwords
 __device__ __forceinline__ uint32_t byte_at(uint2 v, int k) { return ((k < 4 ? v.x : v.y) >> (8 * (k & 3))) & 0xFFu; }
 
+// always true, but not to the compiler: splits straight-line code into basic blocks
+__device__ __forceinline__ bool opaque_true()
+{
+    int t = 1;
+    asm volatile("" : "+s"(t));
+    return t != 0;
+}
+
 // The min-max subset programme of Eq. 3 for two blocks at once (low and high halves of every
 // register): after NROWS rows, G[S] for the column subsets S with NROWS elements is the bottleneck
 // optimum of matching rows 0 .. NROWS-1 into S. rowdev[h] / coldev[h]: the devices of the rows and of
 // the 8 columns of block h, one per byte. With NROWS = 8, G[255] is the optimum of the block; with
 // NROWS = 7, G[255 ^ (1 << c)] is the optimum of the 7 rows into all columns but c.
-template <int NROWS>
+template <int NROWS, bool SPLIT_ROWS>
 __device__ __forceinline__ void match_rows(const uint16_t *R, const uint2 (&rowdev)[2], const uint2 (&coldev)[2],
                                            uint32_t (&G)[256])
 {
@@ -290,6 +298,12 @@ __device__ __forceinline__ void match_rows(const uint16_t *R, const uint2 (&rowd
     }
 #pragma unroll
     for (int r = 0; r < NROWS; r++) {
+        // With SPLIT_ROWS every row from the third on is a basic block of its own (a branch on a value
+        // the compiler cannot see, always taken): the instruction scheduler then cannot pile the gathers
+        // of all rows, with their LDS bank conflicts, in front of the programme; those of row r + 1 are
+        // issued with the arithmetic of row r and hidden behind it. It shortens a lone wavefront's pass
+        // by a few per cent; kernels that keep more state alive around the programme do better without.
+        if (SPLIT_ROWS && r >= 2 && !opaque_true()) continue;
         // row r of both blocks: w[c] = (rank of block-0 entry (r,c)) | (rank of block-1 entry) << 16
         uint32_t w[8];
 #pragma unroll
