@@ -93,6 +93,21 @@ def test_config2_population_thirty_two_candidates_per_wavefront():
         assert np.array_equal(ghat[p], o.coarsen(perms[p])) and datap[p] == o.datap(perms[p])
 
 
+@pytest.mark.parametrize("P", [4095, 4096, 4097, 65535, 65536])
+def test_population_sizes_where_the_group_size_changes(P):
+    # 4 candidates per wavefront pass up to 4096, 8 up to 65535, 32 from 65536: around each switch the costs
+    # are those of the oracle (sampled) and, row by row, those of small separately evaluated chunks
+    w = workloads.config("C2")
+    o, g = both(w)
+    perms = workloads.random_population(P, 64, seed=40)
+    dperm = dev(perms)
+    c = host(dtfm.eval_population(g, dperm))
+    sel = np.r_[0:64, P // 2:P // 2 + 64, P - 64:P]
+    assert_costs_equal(c[sel], o.eval_population(perms[sel]))
+    for lo in range(0, P, 1500):
+        assert np.array_equal(c[lo:lo + 1500], host(dtfm.eval_population(g, dperm[lo:lo + 1500].contiguous())))
+
+
 def test_config4_full_population_sampled():
     w = workloads.config("C4")
     o, g = both(w)
