@@ -26,6 +26,7 @@ constexpr int AP_OFF_EDGE = AP_OFF_CUR + 64;           // u16 [64 + 64 + 2*64*8]
 constexpr int AP_EDGE_GBM = 0;                         //   [u][v]      the round's own coarsened graph
 constexpr int AP_EDGE_SCR = 64;                        //   [mv]        edge (j,j') after swap mv = 8 i + i'
 constexpr int AP_EDGE_REP = 128;                       //   [side][mv][k] edge (j,k) (side 0) / (j',k) (side 1) after swap mv
+constexpr int AP_EDGE_SCR_ODD = 128 + 1024;            //   [mv]        the same for odd batches, in the unused F[0][0] block
 constexpr int AP_OFF_F = AP_OFF_EDGE + (128 + 1024) * 2;   // u16 [j][k][i][c]
 constexpr int AP_OFF_DPM = AP_OFF_F + 8 * 8 * 8 * 8 * 2;   // double [64]: DataP after swap mv
 constexpr int AP_OFF_DPB = AP_OFF_DPM + 64 * 8;            // double [8]: DataP of every stage of the current row
@@ -165,9 +166,9 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
 #pragma nounroll
             for (int it = 0; it < n_it; it++) {
                 // it = 0: Held-Karp of the row itself; then 28 batches (j < j') of 8 passes of 8 swaps
-                const int bpass = (it - 1) & 7;
+                const int bpass = (it - 1) & 7, batch = (it - 1) >> 3;
                 if (it > 0 && bpass == 0) {
-                    pair8_decode((it - 1) >> 3, j, jp);
+                    pair8_decode(batch, j, jp);
                     const uint2 cj = *reinterpret_cast<const uint2 *>(cur + 8 * j), cjp = *reinterpret_cast<const uint2 *>(cur + 8 * jp);
                     const int i = lane >> 3, ip = lane & 7;            // this lane's swap mv = lane
                     const uint32_t x = byte_at(cj, i), y = byte_at(cjp, ip);
@@ -179,15 +180,19 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
                         edge[AP_EDGE_REP + lane * 8 + k] = (uint16_t)replaced_row(R, F + ((j * 8 + k) * 8 + i) * 8, y, ck);
                         edge[AP_EDGE_REP + (64 + lane) * 8 + k] = (uint16_t)replaced_row(R, F + ((jp * 8 + k) * 8 + ip) * 8, x, ck);
                     }
-                    // edge (j,j'): lanes 0..31 take swaps 2 lane and 2 lane + 1 (same i, i' and i' + 1)
-                    {
+                    // edge (j,j'), for this batch and the next one at once (every other batch): lanes 0..31 take
+                    // this batch's swaps 2 l and 2 l + 1 (same i, i' and i' + 1), lanes 32..63 the next batch's
+                    if ((batch & 1) == 0) {
                         const int l = lane & 31, si = l >> 2, sp = 2 * (l & 3);
-                        const uint32_t sx = byte_at(cj, si);
-                        const uint2 rowdev[2] = {put_byte(cj, si, byte_at(cjp, sp)), put_byte(cj, si, byte_at(cjp, sp + 1))};
-                        const uint2 coldev[2] = {put_byte(cjp, sp, sx), put_byte(cjp, sp + 1, sx)};
+                        int sj = j, sjp = jp;
+                        if (lane >= 32) pair8_decode(batch + 1 < 28 ? batch + 1 : batch, sj, sjp);
+                        const uint2 scj = *reinterpret_cast<const uint2 *>(cur + 8 * sj), scjp = *reinterpret_cast<const uint2 *>(cur + 8 * sjp);
+                        const uint32_t sx = byte_at(scj, si);
+                        const uint2 rowdev[2] = {put_byte(scj, si, byte_at(scjp, sp)), put_byte(scj, si, byte_at(scjp, sp + 1))};
+                        const uint2 coldev[2] = {put_byte(scjp, sp, sx), put_byte(scjp, sp + 1, sx)};
                         uint32_t G[256];
                         match_rows<8, false>(R, rowdev, coldev, G);
-                        if (lane < 32) reinterpret_cast<uint32_t *>(edge + AP_EDGE_SCR)[l] = G[255];
+                        reinterpret_cast<uint32_t *>(edge + (lane < 32 ? AP_EDGE_SCR : AP_EDGE_SCR_ODD))[l] = G[255];
                     }
                     // DataP after the swap
                     {
@@ -207,7 +212,7 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
                     const int u = hv ^ d;
                     int e = AP_EDGE_GBM + hv * 8 + u;
                     if (it > 0) {
-                        if ((hv == j && u == jp) || (hv == jp && u == j)) e = AP_EDGE_SCR + mv;
+                        if ((hv == j && u == jp) || (hv == jp && u == j)) e = ((batch & 1) ? AP_EDGE_SCR_ODD : AP_EDGE_SCR) + mv;
                         else if (hv == j) e = AP_EDGE_REP + mv * 8 + u;
                         else if (u == j) e = AP_EDGE_REP + mv * 8 + hv;
                         else if (hv == jp) e = AP_EDGE_REP + (64 + mv) * 8 + u;
