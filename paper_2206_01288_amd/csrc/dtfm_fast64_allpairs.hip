@@ -162,7 +162,7 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
             double bestc = INFINITY, pp_base = 0.0;
             uint32_t bestk = 0xFFFFFFFFu;   // key = 64 a + b of positions a < b: the order of the move indices
             const int n_it = 1 + 28 * 8;
-            int j = 0, jp = 0;
+            int j = 99, jp = 99;   // no stage: the first pass prices the row itself
 #pragma nounroll
             for (int it = 0; it < n_it; it++) {
                 // it = 0: Held-Karp of the row itself; then 28 batches (j < j') of 8 passes of 8 swaps
@@ -210,14 +210,13 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
 #pragma unroll
                 for (int d = 1; d < 8; d++) {
                     const int u = hv ^ d;
+                    // which edge rank this is: the (j,j') edge after the swap, an edge of j or j' with a row
+                    // replaced, or an edge of the row's own coarsened graph (always, when it = 0: j = j' = 99)
+                    const bool vj = hv == j, uj = u == j, vjp = hv == jp, ujp = u == jp;
                     int e = AP_EDGE_GBM + hv * 8 + u;
-                    if (it > 0) {
-                        if ((hv == j && u == jp) || (hv == jp && u == j)) e = ((batch & 1) ? AP_EDGE_SCR_ODD : AP_EDGE_SCR) + mv;
-                        else if (hv == j) e = AP_EDGE_REP + mv * 8 + u;
-                        else if (u == j) e = AP_EDGE_REP + mv * 8 + hv;
-                        else if (hv == jp) e = AP_EDGE_REP + (64 + mv) * 8 + u;
-                        else if (u == jp) e = AP_EDGE_REP + (64 + mv) * 8 + hv;
-                    }
+                    e = (vjp || ujp) ? AP_EDGE_REP + (64 + mv) * 8 + (vjp ? u : hv) : e;
+                    e = (vj || uj) ? AP_EDGE_REP + mv * 8 + (vj ? u : hv) : e;
+                    e = ((vj && ujp) || (vjp && uj)) ? ((batch & 1) ? AP_EDGE_SCR_ODD : AP_EDGE_SCR) + mv : e;
                     G[d] = rank_val[edge[e]];
                 }
                 const double pp = hk_registers(G);
