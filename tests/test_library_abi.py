@@ -65,3 +65,12 @@ def test_null_arguments():
     assert L.dtfm_philox_blocks(0, 0, 0, 0, 0, -1, None, None) == 4
     assert L.dtfm_philox_blocks(0, 0, 0, 0, 0, 3, None, None) == 1
     L.dtfm_destroy_problem(None)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # every figure of this build is a one-GPU figure: bench.py --gpus N with N > 1 exits with a message
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
