@@ -516,6 +516,30 @@ __global__ void k_make_offspring(uint32_t k0, uint32_t k1, uint32_t g, const int
 // P+L keys is split: block (x, y) counts, for 256 elements i, the keys of chunk y (staged in LDS)
 // that precede them, and adds the partial count to rank[i].
 #define DTFM_RANK_CHUNK 256
+// counts the keys key[0..m) that precede element (ci, i); j_first = index of key[0] among all keys.
+// MODE 0: key <= ci (the keys all have lower indices), 1: key < ci (all higher), 2: index compared.
+// The key address is the same for every lane: the loads go through the scalar cache, sixteen keys at a time.
+template <int MODE>
+__device__ __forceinline__ int count_before(const double *__restrict__ key, int m, int j_first, double ci, int i)
+{
+    int cnt = 0, t = 0;
+    for (; t + 16 <= m; t += 16) {
+        double k8[16];
+#pragma unroll
+        for (int e = 0; e < 16; e++) k8[e] = key[t + e];
+#pragma unroll
+        for (int e = 0; e < 16; e++)
+            cnt += MODE == 0 ? (k8[e] <= ci ? 1 : 0)
+                 : MODE == 1 ? (k8[e] < ci ? 1 : 0)
+                             : ((k8[e] < ci || (k8[e] == ci && j_first + t + e < i)) ? 1 : 0);
+    }
+    for (; t < m; t++) {
+        const double kj = key[t];
+        cnt += MODE == 0 ? (kj <= ci ? 1 : 0) : MODE == 1 ? (kj < ci ? 1 : 0) : ((kj < ci || (kj == ci && j_first + t < i)) ? 1 : 0);
+    }
+    return cnt;
+}
+
 __global__ void k_rank_count(const double *__restrict__ cost, const double *__restrict__ off_cost, int P, int L,
                              int32_t *__restrict__ rank)
 {
@@ -525,29 +549,18 @@ __global__ void k_rank_count(const double *__restrict__ cost, const double *__re
     if (i >= n) return;
     const double ci = i < P ? cost[i] : off_cost[i - P];
     const int j1 = j0 + DTFM_RANK_CHUNK < n ? j0 + DTFM_RANK_CHUNK : n;
-    int cnt = 0;
-    // the key index j is the same for every lane: the keys come through the scalar cache. A chunk that
-    // lies wholly before (after) this block's elements needs no index comparison: ties go to the key.
+    // the chunk's keys: [ja, jb) among the parents, [jc, jd) among the offspring
+    const int ja = j0 < P ? j0 : P, jb = j1 < P ? j1 : P, jc = j0 > P ? j0 : P, jd = j1 > P ? j1 : P;
+    // A chunk that lies wholly before (after) this block's elements needs no index comparison: ties go
+    // to the key (to the element).
     const int i0 = blockIdx.x * blockDim.x;
-    if (j1 <= i0) {
-#pragma unroll 8
-        for (int j = j0; j < j1; j++) {
-            const double cj = j < P ? cost[j] : off_cost[j - P];
-            cnt += cj <= ci ? 1 : 0;
-        }
-    } else if (j0 >= i0 + (int)blockDim.x) {
-#pragma unroll 8
-        for (int j = j0; j < j1; j++) {
-            const double cj = j < P ? cost[j] : off_cost[j - P];
-            cnt += cj < ci ? 1 : 0;
-        }
-    } else {
-#pragma unroll 8
-        for (int j = j0; j < j1; j++) {
-            const double cj = j < P ? cost[j] : off_cost[j - P];
-            cnt += (cj < ci || (cj == ci && j < i)) ? 1 : 0;
-        }
-    }
+    int cnt;
+    if (j1 <= i0)
+        cnt = count_before<0>(cost + ja, jb - ja, ja, ci, i) + count_before<0>(off_cost + (jc - P), jd - jc, jc, ci, i);
+    else if (j0 >= i0 + (int)blockDim.x)
+        cnt = count_before<1>(cost + ja, jb - ja, ja, ci, i) + count_before<1>(off_cost + (jc - P), jd - jc, jc, ci, i);
+    else
+        cnt = count_before<2>(cost + ja, jb - ja, ja, ci, i) + count_before<2>(off_cost + (jc - P), jd - jc, jc, ci, i);
     if (cnt) atomicAdd(&rank[i], cnt);
 }
 
