@@ -38,8 +38,12 @@ constexpr int off_res(int nc) { return (off_ghr(nc) + nc * 28 * 2 + 7) / 8 * 8; 
 constexpr int off_curc(int nc) { return off_res(nc) + 2 * nc * 8; }            // double [NC]: current costs (local search)
 constexpr int off_pbcur(int nc) { return off_curc(nc) + nc * 8; }              // u8 [NC][64]: current rows (local search)
 constexpr int off_prop(int nc) { return off_pbcur(nc) + nc * 64; }             // u8 [NC][2]: proposed positions (local search)
-constexpr int wave_lds_bytes(int nc, bool ls) { return ((ls ? off_prop(nc) + nc * 2 : off_curc(nc)) + 15) / 16 * 16; }
-constexpr int lds_total(int nc, bool ls) { return LDS_TABLES + (ls ? LDS_WDP_BYTES : 0) + WAVES_PER_BLOCK * wave_lds_bytes(nc, ls); }
+constexpr int off_ghrcur(int nc) { return (off_prop(nc) + nc * 2 + 3) / 4 * 4; }   // u16 [NC][28]: coarsened graphs of the current rows
+constexpr int wave_lds_bytes(int nc, bool ls) { return ((ls ? off_ghrcur(nc) + nc * 28 * 2 : off_curc(nc)) + 15) / 16 * 16; }
+// the local-search kernels also keep W_pp in LDS (for the proposals), except with 32 candidates per
+// wavefront, where the slices need the room and two wavefronts per SIMD hide the latency of L2
+constexpr bool wpp_in_lds(int nc, bool ls) { return ls && nc < 32; }
+constexpr int lds_total(int nc, bool ls) { return LDS_TABLES + (wpp_in_lds(nc, ls) ? LDS_WDP_BYTES : 0) + WAVES_PER_BLOCK * wave_lds_bytes(nc, ls); }
 static_assert(lds_total(MAXC, true) <= 160 * 1024, "LDS budget of a CU");
 
 // Per-wavefront context: LDS pointers and the lane's fixed roles.
@@ -48,7 +52,7 @@ struct wave_ctx {
     const uint16_t *R;       // rank table (LDS)
     const double *rank_val;  // rank -> weight (LDS)
     const double *Wdp;       // W_dp (LDS)
-    const double *Wpp;       // W_pp (LDS; local-search kernel only)
+    const double *Wpp;       // W_pp (local-search kernels only; LDS copy or the global table)
     int lane;
     int hv;                  // Held-Karp / DataP role: stage; the candidate slot is 8 * pass + lane / 8
 };
@@ -64,10 +68,10 @@ __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16
     cx.R = reinterpret_cast<const uint16_t *>(smem);
     cx.rank_val = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES);
     cx.Wdp = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES + LDS_RVAL_BYTES);
-    cx.Wpp = reinterpret_cast<const double *>(smem + LDS_TABLES);
-    cx.wl = smem + LDS_TABLES + (LS ? LDS_WDP_BYTES : 0) + wave * wave_lds_bytes(NC, LS);
+    cx.Wpp = wpp_in_lds(NC, LS) ? reinterpret_cast<const double *>(smem + LDS_TABLES) : W_pp;
+    cx.wl = smem + LDS_TABLES + (wpp_in_lds(NC, LS) ? LDS_WDP_BYTES : 0) + wave * wave_lds_bytes(NC, LS);
     stage_tables(smem, rank_tab, rank_val, W_dp);
-    if (LS)
+    if (wpp_in_lds(NC, LS))
         for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x)
             reinterpret_cast<double2 *>(smem + LDS_TABLES)[i] = reinterpret_cast<const double2 *>(W_pp)[i];
     cx.hv = cx.lane & 7;
@@ -98,27 +102,55 @@ __device__ __forceinline__ uint32_t match_couple(const wave_ctx &cx, const unsig
 // upper half of the wavefront repeats the lower half). On return the slice holds, visible to all
 // lanes, total (Eq. 1) of candidate slot c at res[c] and DataP (Eq. 2 + max) at res[NC + c]. ghat_out,
 // if not null, receives the coarsened graphs of candidates cand0 .. cand0 + NC - 1 that are < P.
-template <int NC>
-__device__ __forceinline__ void eval_group(const wave_ctx &cx, double *__restrict__ ghat_out, size_t cand0, size_t P)
+// With INC and sj >= 0 (sj < sjp) the rows differ from rows whose winning ranks are already in the
+// slice only in stages sj and sjp: only the 13 stage pairs that contain one of them are matched
+// again (7 couples per candidate, the last with its second pair repeated).
+template <int NC, bool INC>
+__device__ __forceinline__ void eval_group(const wave_ctx &cx, double *__restrict__ ghat_out, size_t cand0, size_t P,
+                                           int sj, int sjp)
 {
     unsigned char *wl = cx.wl;
     const int lane = cx.lane;
-    constexpr int ITEMS = NC * 14, MPASSES = (ITEMS + 63) / 64, HPASSES = (NC + 7) / 8;
-    uint32_t *ghr32 = reinterpret_cast<uint32_t *>(wl + off_ghr(NC));
-    const uint16_t *ghr16 = reinterpret_cast<const uint16_t *>(wl + off_ghr(NC));
+    constexpr int HPASSES = (NC + 7) / 8;
+    uint16_t *ghr16 = reinterpret_cast<uint16_t *>(wl + off_ghr(NC));
     double *res = reinterpret_cast<double *>(wl + off_res(NC));
-    // ---- a4: matchings on ranks; the two winning ranks of item t go to word t ----
+    // ---- a4: matchings on ranks; the winning ranks of stage pair (a, b) of candidate c go to [c][index of (a, b)] ----
+    const bool inc = INC && sj >= 0;
+    const int per_cand = inc ? 7 : 14, items = NC * per_cand, mpasses = (items + 63) / 64;
 #pragma nounroll
-    for (int pass = 0; pass < MPASSES; pass++) {
+    for (int pass = 0; pass < mpasses; pass++) {
         int t = pass * 64 + lane;
-        const bool valid = t < ITEMS;
-        if (!valid) t = ITEMS - 1;   // idle lanes repeat the last item and write nothing
-        const int mc = t / 14, q = t - 14 * mc;
+        const bool valid = t < items;
+        if (!valid) t = items - 1;   // idle lanes repeat the last item and write nothing
+        const int mc = t / per_cand, q = t - per_cand * mc;
         int j1[2], j2[2];
-        pair8_decode(2 * q, j1[0], j2[0]);
-        pair8_decode(2 * q + 1, j1[1], j2[1]);
+        if (!inc) {
+            pair8_decode(2 * q, j1[0], j2[0]);
+            pair8_decode(2 * q + 1, j1[1], j2[1]);
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                // changed pair number e = 0..12: (sj, k) for the 7 stages k != sj, then (sjp, k) for the 6 others
+                const int e = 2 * q + h < 12 ? 2 * q + h : 12;
+                int a, k;
+                if (e < 7) {
+                    a = sj;
+                    k = e + (e >= sj ? 1 : 0);
+                } else {
+                    a = sjp;
+                    k = e - 7;
+                    k += k >= sj ? 1 : 0;
+                    k += k >= sjp ? 1 : 0;
+                }
+                j1[h] = a < k ? a : k;
+                j2[h] = a < k ? k : a;
+            }
+        }
         const uint32_t gfull = match_couple(cx, wl + OFF_PB + mc * 64, j1, j2);
-        if (valid) ghr32[t] = gfull;
+        if (valid) {
+            ghr16[mc * 28 + pair_index(j1[0], j2[0])] = (uint16_t)gfull;
+            ghr16[mc * 28 + pair_index(j1[1], j2[1])] = (uint16_t)(gfull >> 16);
+        }
     }
     WAVE_LDS_SYNC();
     if (ghat_out != nullptr) {
@@ -185,7 +217,7 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
             cx.wl[OFF_PB + c * 64 + lane] = (unsigned char)perm[cand * NDEV + lane];
         }
         WAVE_LDS_SYNC();
-        eval_group<NC>(cx, ghat_out, grp * NC, P);
+        eval_group<NC, false>(cx, ghat_out, grp * NC, P, -1, -1);
         const double *res = reinterpret_cast<const double *>(cx.wl + off_res(NC));
         const size_t cand = grp * NC + lane;
         if (lane < NC && cand < P) {
@@ -193,6 +225,75 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
             if (datap_out != nullptr) datap_out[cand] = res[NC + lane];
         }
         WAVE_LDS_SYNC();   // the next group reuses the slice
+    }
+}
+
+// The round's proposal for every candidate slot (Sec. 3.4, "Improving Local Search Strategy"): the fastest
+// link inside stage j and inside stage jp of the current row, and of the four swaps of their end points
+// the one of largest Gain; its two positions (first < second) go to prop[2 c], prop[2 c + 1].
+template <int NC>
+__device__ __forceinline__ void propose_gain4(const wave_ctx &cx, const unsigned char *pbcur, unsigned char *prop, int j,
+                                              int jp)
+{
+    const int lane = cx.lane, sub = lane & 15;   // 16 lanes per candidate, four candidates per pass
+    int ea_i, ea_k, eb_i, eb_k;                  // the two slot pairs this lane looks at when the fastest link is sought
+    pair8_decode(sub, ea_i, ea_k);
+    pair8_decode(sub < 12 ? sub + 16 : sub, eb_i, eb_k);
+    const int Cj = 8 * j, Cjp = 8 * jp;
+#pragma nounroll
+    for (int pass = 0; pass < NC / 4; pass++) {
+        // ---- proposal for candidate slot 4 * pass + lane / 16 by its 16 lanes: registers and
+        // lane exchanges only, apart from the table gathers ----
+        const int pslot = 4 * pass + (lane >> 4);
+        const unsigned char *pc = pbcur + pslot * 64;
+        const uint2 cdev[2] = {*reinterpret_cast<const uint2 *>(pc + Cj), *reinterpret_cast<const uint2 *>(pc + Cjp)};
+        int slot[2][2];
+#pragma unroll
+        for (int s = 0; s < 2; s++) {
+            // fastest link inside the stage: key = (rank << 8) | pair index, first minimiser wins;
+            // this lane looks at slot pairs `sub` and `sub + 16`
+            uint32_t key = ((uint32_t)cx.R[byte_at(cdev[s], ea_i) * RSTRIDE + byte_at(cdev[s], ea_k)] << 8) | (uint32_t)sub;
+            const uint32_t kb = ((uint32_t)cx.R[byte_at(cdev[s], eb_i) * RSTRIDE + byte_at(cdev[s], eb_k)] << 8) | (uint32_t)(sub + 16);
+            if (sub < 12 && kb < key) key = kb;
+            key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x128, 0xF, 0xF, true));   // row_ror:8
+            key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x124, 0xF, 0xF, true));   // row_ror:4
+            key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x122, 0xF, 0xF, true));   // row_ror:2
+            key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x121, 0xF, 0xF, true));   // row_ror:1
+            pair8_decode((int)(key & 0xFFu), slot[s][0], slot[s][1]);
+        }
+        // every quad of lanes computes the four means itself: lanes 0,1 the mean over C_j' of w[x][.] for
+        // x = d1, d2; lanes 2,3 the mean over C_j of w[y][.] for y = d1', d2'
+        double mean;
+        {
+            const int side = (lane >> 1) & 1, which = lane & 1;
+            const uint32_t dv = byte_at(cdev[side], side == 0 ? slot[0][which] : slot[1][which]);
+            const uint2 other = cdev[side ^ 1];
+            double sum = 0.0;
+#pragma unroll
+            for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, cx.Wpp[dv * NDEV + byte_of(other, i)]);
+            mean = __ddiv_rn(sum, 8.0);
+        }
+        const double link0 = cx.Wpp[byte_at(cdev[0], slot[0][0]) * NDEV + byte_at(cdev[0], slot[0][1])];
+        const double link1 = cx.Wpp[byte_at(cdev[1], slot[1][0]) * NDEV + byte_at(cdev[1], slot[1][1])];
+        const double mx[2] = {dpp_move<0x00>(mean), dpp_move<0x55>(mean)};   // lane 0 / lane 1 of the quad
+        const double my[2] = {dpp_move<0xAA>(mean), dpp_move<0xFF>(mean)};   // lane 2 / lane 3
+        double bestg = 0.0;
+        int bk = -1;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            double g = mx[k >> 1];
+            g = __dadd_rn(g, -link0);
+            g = __dadd_rn(g, my[k & 1]);
+            g = __dadd_rn(g, -link1);
+            if (bk < 0 || g > bestg) {
+                bestg = g;
+                bk = k;
+            }
+        }
+        if (sub == 0) {   // positions, first < second
+            prop[2 * pslot] = (unsigned char)(Cj + slot[0][bk >> 1]);
+            prop[2 * pslot + 1] = (unsigned char)(Cjp + slot[1][bk & 1]);
+        }
     }
 }
 
@@ -215,10 +316,7 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
     unsigned char *pbcur = wl + off_pbcur(NC), *prop = wl + off_prop(NC);
     const double *res = reinterpret_cast<const double *>(wl + off_res(NC));
     double *curc = reinterpret_cast<double *>(wl + off_curc(NC));
-    const int sub = lane & 15;   // proposal role: 16 lanes per candidate, four candidates per pass
-    int ea_i, ea_k, eb_i, eb_k;   // the two slot pairs this lane looks at when the fastest link is sought
-    pair8_decode(sub, ea_i, ea_k);
-    pair8_decode(sub < 12 ? sub + 16 : sub, eb_i, eb_k);
+    uint32_t *ghr32 = reinterpret_cast<uint32_t *>(wl + off_ghr(NC)), *ghrcur32 = reinterpret_cast<uint32_t *>(wl + off_ghrcur(NC));
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
     const size_t ngroups = (P + NC - 1) / NC;
     for (size_t grp = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; grp < ngroups; grp += nwaves) {
@@ -231,78 +329,31 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
             pbcur[c * 64 + lane] = d;
         }
         WAVE_LDS_SYNC();
-        eval_group<NC>(cx, nullptr, grp * NC, P);
-        if (lane < NC) curc[lane] = res[lane];
+        // round -1 prices the rows as they are; each later round prices the rows with the proposed swap
 #pragma nounroll
-        for (int r = 0; r < moves; r++) {
-            int j, jp;
-            pair8_decode(r % 28, j, jp);
-            const int Cj = 8 * j, Cjp = 8 * jp;
-#pragma nounroll
-            for (int pass = 0; pass < NC / 4; pass++) {
-                // ---- proposal for candidate slot 4 * pass + lane / 16 by its 16 lanes: registers and
-                // lane exchanges only, apart from the table gathers ----
-                const int pslot = 4 * pass + (lane >> 4);
-                const unsigned char *pc = pbcur + pslot * 64;
-                const uint2 cdev[2] = {*reinterpret_cast<const uint2 *>(pc + Cj), *reinterpret_cast<const uint2 *>(pc + Cjp)};
-                int slot[2][2];
+        for (int r = -1; r < moves; r++) {
+            int j = -1, jp = -1;
+            if (r >= 0) {
+                pair8_decode(r % 28, j, jp);
+                propose_gain4<NC>(cx, pbcur, prop, j, jp);
+                WAVE_LDS_SYNC();
+                // ---- trial rows; the evaluation starts from the current rows' coarsened graphs ----
 #pragma unroll
-                for (int s = 0; s < 2; s++) {
-                    // fastest link inside the stage: key = (rank << 8) | pair index, first minimiser wins;
-                    // this lane looks at slot pairs `sub` and `sub + 16`
-                    uint32_t key = ((uint32_t)cx.R[byte_at(cdev[s], ea_i) * RSTRIDE + byte_at(cdev[s], ea_k)] << 8) | (uint32_t)sub;
-                    const uint32_t kb = ((uint32_t)cx.R[byte_at(cdev[s], eb_i) * RSTRIDE + byte_at(cdev[s], eb_k)] << 8) | (uint32_t)(sub + 16);
-                    if (sub < 12 && kb < key) key = kb;
-                    key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x128, 0xF, 0xF, true));   // row_ror:8
-                    key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x124, 0xF, 0xF, true));   // row_ror:4
-                    key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x122, 0xF, 0xF, true));   // row_ror:2
-                    key = min(key, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)key, 0x121, 0xF, 0xF, true));   // row_ror:1
-                    pair8_decode((int)(key & 0xFFu), slot[s][0], slot[s][1]);
+                for (int c = 0; c < NC; c++) {
+                    const int ta = prop[2 * c], tb = prop[2 * c + 1];
+                    const int src = lane == ta ? tb : (lane == tb ? ta : lane);
+                    wl[OFF_PB + c * 64 + lane] = pbcur[c * 64 + src];
                 }
-                // every quad of lanes computes the four means itself: lanes 0,1 the mean over C_j' of w[x][.] for
-                // x = d1, d2; lanes 2,3 the mean over C_j of w[y][.] for y = d1', d2'
-                double mean;
-                {
-                    const int side = (lane >> 1) & 1, which = lane & 1;
-                    const uint32_t dv = byte_at(cdev[side], side == 0 ? slot[0][which] : slot[1][which]);
-                    const uint2 other = cdev[side ^ 1];
-                    double sum = 0.0;
-#pragma unroll
-                    for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, cx.Wpp[dv * NDEV + byte_of(other, i)]);
-                    mean = __ddiv_rn(sum, 8.0);
-                }
-                const double link0 = cx.Wpp[byte_at(cdev[0], slot[0][0]) * NDEV + byte_at(cdev[0], slot[0][1])];
-                const double link1 = cx.Wpp[byte_at(cdev[1], slot[1][0]) * NDEV + byte_at(cdev[1], slot[1][1])];
-                const double mx[2] = {dpp_move<0x00>(mean), dpp_move<0x55>(mean)};   // lane 0 / lane 1 of the quad
-                const double my[2] = {dpp_move<0xAA>(mean), dpp_move<0xFF>(mean)};   // lane 2 / lane 3
-                double bestg = 0.0;
-                int bk = -1;
-#pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    double g = mx[k >> 1];
-                    g = __dadd_rn(g, -link0);
-                    g = __dadd_rn(g, my[k & 1]);
-                    g = __dadd_rn(g, -link1);
-                    if (bk < 0 || g > bestg) {
-                        bestg = g;
-                        bk = k;
-                    }
-                }
-                if (sub == 0) {   // positions, first < second
-                    prop[2 * pslot] = (unsigned char)(Cj + slot[0][bk >> 1]);
-                    prop[2 * pslot + 1] = (unsigned char)(Cjp + slot[1][bk & 1]);
-                }
+                for (int w = lane; w < NC * 14; w += 64) ghr32[w] = ghrcur32[w];
+                WAVE_LDS_SYNC();
             }
-            WAVE_LDS_SYNC();
-            // ---- trial rows ----
-#pragma unroll
-            for (int c = 0; c < NC; c++) {
-                const int ta = prop[2 * c], tb = prop[2 * c + 1];
-                const int src = lane == ta ? tb : (lane == tb ? ta : lane);
-                wl[OFF_PB + c * 64 + lane] = pbcur[c * 64 + src];
+            eval_group<NC, true>(cx, nullptr, grp * NC, P, j, jp);
+            if (r < 0) {
+                if (lane < NC) curc[lane] = res[lane];
+                for (int w = lane; w < NC * 14; w += 64) ghrcur32[w] = ghr32[w];
+                WAVE_LDS_SYNC();
+                continue;
             }
-            WAVE_LDS_SYNC();
-            eval_group<NC>(cx, nullptr, grp * NC, P);
             // ---- accept iff strictly cheaper ----
             bool mine = false;
             if (lane < NC) {
@@ -316,6 +367,8 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
                 const bool take = (takes >> c) & 1;   // wave-uniform
                 if (take) pbcur[c * 64 + lane] = wl[OFF_PB + c * 64 + lane];
             }
+            for (int w = lane; w < NC * 14; w += 64)
+                if ((takes >> (w / 14)) & 1) ghrcur32[w] = ghr32[w];
             if (applied != nullptr && lane < NC && grp * NC + lane < P) {
                 const long long ta = prop[2 * lane], tb = prop[2 * lane + 1];
                 applied[(grp * NC + lane) * (size_t)moves + r] = mine ? ta * NDEV - ta * (ta + 1) / 2 + (tb - ta - 1) : -1ll;
