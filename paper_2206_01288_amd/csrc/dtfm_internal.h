@@ -140,7 +140,6 @@ struct dtfm_ga_bufs {
     double *off_cost;   // lambda
     int32_t *next;      // P * N
     double *next_cost;  // P
-    int32_t *src;       // P: origin index of each survivor
     int32_t *rank;      // P + lambda: rank of each key under (cost, origin)
     dtfm_ls_bufs ls;
 };

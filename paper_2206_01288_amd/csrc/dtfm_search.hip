@@ -564,17 +564,24 @@ __global__ void k_rank_count(const double *__restrict__ cost, const double *__re
     if (cnt) atomicAdd(&rank[i], cnt);
 }
 
-__global__ void k_rank_place(const double *__restrict__ cost, const double *__restrict__ off_cost, int P, int L,
-                             const int32_t *__restrict__ rank, double *__restrict__ next_cost,
-                             int32_t *__restrict__ src, double *__restrict__ trace_slot)
+// Replacement, second step: one workgroup per element; an element whose rank is below P is a survivor:
+// its row and cost go to position `rank` of the next population, the lowest to the trace. The element's
+// rank counter is cleared for the next generation.
+__global__ void k_rank_place(const int32_t *__restrict__ pop, const int32_t *__restrict__ off,
+                             const double *__restrict__ cost, const double *__restrict__ off_cost, int P, int L, int N,
+                             int32_t *__restrict__ rank, int32_t *__restrict__ next, double *__restrict__ next_cost,
+                             double *__restrict__ trace_slot)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= P + L) return;
+    const int i = blockIdx.x;
     const int r = rank[i];
-    if (r < P) {
+    __syncthreads();   // every thread has read the counter before thread 0 clears it
+    if (threadIdx.x == 0) rank[i] = 0;
+    if (r >= P) return;
+    const int32_t *s = i < P ? pop + (size_t)i * N : off + (size_t)(i - P) * N;
+    for (int q = threadIdx.x; q < N; q += blockDim.x) next[(size_t)r * N + q] = s[q];
+    if (threadIdx.x == 0) {
         const double ci = i < P ? cost[i] : off_cost[i - P];
         next_cost[r] = ci;
-        src[r] = i;
         if (r == 0) *trace_slot = ci;
     }
 }
@@ -585,19 +592,6 @@ __global__ void k_fill_i32(int32_t *__restrict__ dst, int32_t v, size_t n)
     if (i < n) dst[i] = v;
 }
 
-// Copies the survivors' rows in rank order; also clears the rank counters for the next generation
-// (they have been consumed by k_rank_place).
-__global__ void k_gather_rows(const int32_t *__restrict__ pop, const int32_t *__restrict__ off, int P, int L, int N,
-                              const int32_t *__restrict__ src, int32_t *__restrict__ next, int32_t *__restrict__ rank)
-{
-    size_t r = blockIdx.x;
-    int o = src[r];
-    const int32_t *s = o < P ? pop + (size_t)o * N : off + (size_t)(o - P) * N;
-    for (int q = threadIdx.x; q < N; q += blockDim.x) next[r * N + q] = s[q];
-    if (threadIdx.x == 0)
-        for (int k = (int)r; k < P + L; k += P) rank[k] = 0;
-}
-
 dtfm_ga_bufs dtfm_ga_carve(const dtfm_problem *pr, dtfm_arena &ar, const dtfm_ga_params &prm)
 {
     dtfm_ga_bufs b;
@@ -606,7 +600,6 @@ dtfm_ga_bufs dtfm_ga_carve(const dtfm_problem *pr, dtfm_arena &ar, const dtfm_ga
     b.off_cost = ar.take<double>(L);
     b.next = ar.take<int32_t>(P * N);
     b.next_cost = ar.take<double>(P);
-    b.src = ar.take<int32_t>(P);
     b.rank = ar.take<int32_t>(P + L);
     b.ls = dtfm_ls_carve(pr, ar, P > L ? P : L, prm.neighbourhood);
     return b;
@@ -640,10 +633,8 @@ int dtfm_ga_enqueue(const dtfm_problem *pr, const dtfm_ga_bufs &b, uint64_t seed
         hipLaunchKernelGGL(k_rank_count, dim3((nk + 255) / 256, (nk + DTFM_RANK_CHUNK - 1) / DTFM_RANK_CHUNK), dim3(256), 0,
                            st, cost_cur, b.off_cost, P, L, b.rank);
         DTFM_HIP(hipGetLastError());
-        hipLaunchKernelGGL(k_rank_place, dim3((nk + 255) / 256), dim3(256), 0, st, cost_cur, b.off_cost, P, L, b.rank,
-                           cost_next, b.src, best_trace + g);
-        DTFM_HIP(hipGetLastError());
-        hipLaunchKernelGGL(k_gather_rows, dim3(P), dim3(DTFM_WAVE), 0, st, pop_cur, b.off, P, L, N, b.src, pop_next, b.rank);
+        hipLaunchKernelGGL(k_rank_place, dim3(nk), dim3(DTFM_WAVE), 0, st, pop_cur, b.off, cost_cur, b.off_cost, P, L, N,
+                           b.rank, pop_next, cost_next, best_trace + g);
         DTFM_HIP(hipGetLastError());
         int32_t *tp = pop_cur;
         pop_cur = pop_next;
