@@ -50,6 +50,11 @@ VALU_LANE_OPS_PER_S = 256 * 4 * 16 * 2.4e9
 # each counter scaled by its reading for a 1 GiB device copy; 19 MB of the reads are the 72 KiB of
 # tables every workgroup stages in LDS). Algorithmic: 4N + 8 = 264 B.
 MEASURED_HBM_BYTES_PER_CANDIDATE = 298.8
+# Counter readings of the same launch from the same file (rocprofv3 --pmc): share of the vector-ALU
+# issue slots and of the LDS cycles in use, vector instructions per candidate.
+MEASURED_COUNTERS = {"valu_busy_frac": 0.805, "lds_busy_frac": 0.424, "lds_bank_conflict_frac_of_lds": 0.49,
+                     "valu_instructions_per_candidate": 653, "hbm_GBps": 225.0, "hbm_frac_of_8TBps": 0.028,
+                     "source": "profiles/k_eval_fast64_C2_P1048576.md"}
 
 
 def algorithmic_ops(N, D_dp, D_pp):
@@ -199,6 +204,7 @@ def main():
                 "algorithmic_hbm_bytes_per_launch": (4 * N + 8) * P_big,
                 "kernel": "k_eval_fast64 (dtfm_eval_population)", "launch_candidates": P_big,
                 "launch_seconds": t_big, "launches_timed": 100, "ops_per_candidate": ops,
+                "rocprof_counters": MEASURED_COUNTERS,
                 "eval_population_cands_per_s": {"P=4096": P / t_small, "P=1048576": P_big / t_big}}
 
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
