@@ -78,6 +78,65 @@ __global__ void k_datap(const double *__restrict__ W_dp, const int32_t *__restri
     }
 }
 
+// Eq. 2 when W_dp does not fit the 4 MiB L2 of an XCD (N = 1024: 8 MiB), so that k_datap's gathers miss
+// it eight times out of nine. Workgroups are handed to the 8 XCDs round robin, so workgroup b runs on XCD
+// b mod 8; it takes, of its candidates, only the positions whose DEVICE d has d mod 8 = b mod 8: every
+// XCD then gathers from one eighth of the rows of W_dp (1 MiB), which stays in its L2. A candidate holds
+// every device once, so a slice is exactly the devices x, x + 8, ..: its positions are compacted into
+// LDS and each thread sums one row (slot order, own slot skipped). The slices' maxima meet in datap[p]
+// through an atomic max on the bit pattern (weights are >= +0.0, so the order of the bits is the order
+// of the values); datap must be zero on entry. Only the mapping of work to XCDs is an assumption
+// about the hardware; the result does not depend on it.
+#define DTFM_XCDS 8
+__global__ void k_datap_sliced(const double *__restrict__ W_dp, const int32_t *__restrict__ perm, int N,
+                               int D_dp, int D_pp, size_t P, size_t stride, double *__restrict__ datap,
+                               double *__restrict__ ghat)
+{
+    extern __shared__ int32_t s_all[];
+    int32_t *s_perm = s_all, *s_list = s_all + N;   // the row; the positions of this slice
+    __shared__ int s_count;
+    __shared__ double s_red[16];
+    const int x = blockIdx.x % DTFM_XCDS;
+    for (size_t p = blockIdx.x / DTFM_XCDS; p < P; p += stride) {
+        __syncthreads();
+        if (threadIdx.x == 0) s_count = 0;
+        const int32_t *row = perm + p * N;
+        for (int q = threadIdx.x; q < N; q += blockDim.x) s_perm[q] = row[q];
+        if (ghat != nullptr && x == 0)
+            for (int j = threadIdx.x; j < D_pp; j += blockDim.x) ghat[(p * D_pp + j) * D_pp + j] = 0.0;
+        __syncthreads();
+        for (int q = threadIdx.x; q < N; q += blockDim.x)
+            if ((s_perm[q] % DTFM_XCDS) == x) s_list[atomicAdd(&s_count, 1)] = q;
+        __syncthreads();
+        const int cnt = s_count;
+        double worst = 0.0;   // all weights are >= 0, so every row sum is >= +0.0
+        for (int t = threadIdx.x; t < cnt; t += blockDim.x) {
+            const int q = s_list[t], j = q / D_dp, i = q - j * D_dp;
+            const double *wr = W_dp + (size_t)s_perm[q] * N;
+            const int32_t *C = s_perm + j * D_dp;
+            double sum = 0.0;
+            for (int k = 0; k < D_dp; k++)
+                if (k != i) sum = __dadd_rn(sum, wr[C[k]]);
+            worst = fmax(worst, sum);
+        }
+        for (int o = 32; o >= 1; o >>= 1) worst = fmax(worst, __shfl_xor(worst, o));
+        const int wave = threadIdx.x / DTFM_WAVE, nw = (blockDim.x + DTFM_WAVE - 1) / DTFM_WAVE;
+        if ((threadIdx.x & (DTFM_WAVE - 1)) == 0) s_red[wave] = worst;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double m = s_red[0];
+            for (int w = 1; w < nw; w++) m = fmax(m, s_red[w]);
+            atomicMax(reinterpret_cast<unsigned long long *>(datap + p), (unsigned long long)__double_as_longlong(m));
+        }
+    }
+}
+
+__global__ void k_zero_f64(double *__restrict__ dst, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = 0.0;
+}
+
 // ------------------------------------------------------------------------------------------------
 // a4: bottleneck assignment for one (candidate, stage pair) per wavefront, lane c = column c (device
 // at slot c of the second stage). The optimum of Eq. 3 is one of the block's entries and depends
@@ -410,8 +469,18 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
     const int N = pr->N, n = pr->D_pp;
     int threads = ((N + DTFM_WAVE - 1) / DTFM_WAVE) * DTFM_WAVE;
     if (threads > 1024) threads = 1024;
-    hipLaunchKernelGGL(k_datap, dim3((unsigned)rows), dim3(threads), N * sizeof(int32_t), st, pr->W_dp,
-                       perm, N, pr->D_dp, n, b.datap, b.ghat);
+    if ((size_t)N * N * sizeof(double) > ((size_t)2 << 20) && N % DTFM_XCDS == 0) {
+        // W_dp larger than half an XCD's L2: one slice of its rows per XCD
+        hipLaunchKernelGGL(k_zero_f64, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, b.datap, rows);
+        DTFM_HIP(hipGetLastError());
+        size_t per_slice = rows < 512 ? rows : 512;   // workgroups per slice; each strides over the candidates
+        int slice_threads = ((N / DTFM_XCDS + DTFM_WAVE - 1) / DTFM_WAVE) * DTFM_WAVE;
+        hipLaunchKernelGGL(k_datap_sliced, dim3((unsigned)(per_slice * DTFM_XCDS)), dim3(slice_threads),
+                           2 * N * sizeof(int32_t), st, pr->W_dp, perm, N, pr->D_dp, n, rows, per_slice, b.datap, b.ghat);
+    } else {
+        hipLaunchKernelGGL(k_datap, dim3((unsigned)rows), dim3(threads), N * sizeof(int32_t), st, pr->W_dp,
+                           perm, N, pr->D_dp, n, b.datap, b.ghat);
+    }
     DTFM_HIP(hipGetLastError());
     if (pr->npairs > 0) {
         size_t total = rows * (size_t)pr->npairs;
