@@ -235,6 +235,16 @@ def test_evolve_config2_shape():
     assert np.all(np.diff(trace) <= 0)
 
 
+def test_evolve_replacement_across_key_chunks():
+    # populations and offspring counts that are not multiples of the rank kernel's 256-key chunks, with the
+    # parents/offspring boundary inside a chunk; odd and even generation counts (the population alternates
+    # between two buffers); the homogeneous network makes every cost tie, so only origin indices decide
+    w = workloads.config("C1")
+    _evolve_parity(w, 21, 3, 300, lam=77, ls_moves=1, neighbourhood=dtfm.GAIN4)
+    _evolve_parity(w, 22, 4, 257, lam=600, m_x=2, ls_moves=0)
+    _evolve_parity(workloads.config("C3h"), 23, 2, 130, lam=140, ls_moves=1, neighbourhood=dtfm.GAIN4)
+
+
 def test_evolve_config5_shape_small_population():
     w = workloads.config("C5")
     _evolve_parity(w, 7, 2, 5, ls_moves=2, neighbourhood=dtfm.GAIN4)
