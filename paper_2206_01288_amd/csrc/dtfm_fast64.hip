@@ -173,19 +173,7 @@ __device__ __forceinline__ void eval_group(const wave_ctx &cx, double *__restric
         }
         const double pp = hk_registers(G);
         // ---- a2/a3: DataP of stage hv of candidate hc, then max over the candidate's 8 lanes ----
-        const uint2 devs = *reinterpret_cast<const uint2 *>(wl + OFF_PB + hc * 64 + 8 * cx.hv);
-        uint32_t dv[8];
-#pragma unroll
-        for (int k = 0; k < 8; k++) dv[k] = byte_of(devs, k);
-        double dp = 0.0;
-#pragma unroll
-        for (int i = 0; i < 8; i++) {
-            const double *wrow = cx.Wdp + dv[i] * NDEV;
-            double sum = 0.0;
-#pragma unroll
-            for (int k = 0; k < 8; k++) sum = __dadd_rn(sum, wrow[dv[k]]);   // own slot: the zero diagonal
-            dp = i == 0 ? sum : fmax(dp, sum);
-        }
+        double dp = stage_datap(cx.Wdp, *reinterpret_cast<const uint2 *>(wl + OFF_PB + hc * 64 + 8 * cx.hv));
         dp = fmax(dp, dpp_move<DPP_XOR1>(dp));
         dp = fmax(dp, dpp_move<DPP_XOR2>(dp));
         dp = fmax(dp, dpp_move<DPP_HALF_MIRROR>(dp));

@@ -66,24 +66,6 @@ __device__ __forceinline__ uint32_t replaced_row(const uint16_t *R, const uint16
     return best;
 }
 
-// DataP of one stage (Eq. 2): max over its devices of the row sums taken in slot order
-__device__ __forceinline__ double stage_datap(const double *Wdp, uint2 devs)
-{
-    uint32_t dv[8];
-#pragma unroll
-    for (int k = 0; k < 8; k++) dv[k] = byte_of(devs, k);
-    double dp = 0.0;
-#pragma unroll
-    for (int i = 0; i < 8; i++) {
-        const double *wrow = Wdp + dv[i] * NDEV;
-        double sum = 0.0;
-#pragma unroll
-        for (int k = 0; k < 8; k++) sum = __dadd_rn(sum, wrow[dv[k]]);   // own slot: the zero diagonal
-        dp = i == 0 ? sum : fmax(dp, sum);
-    }
-    return dp;
-}
-
 // running minimum under (cost, key)
 __device__ __forceinline__ void keep_best(double &bc, uint32_t &bk, double c, uint32_t k)
 {

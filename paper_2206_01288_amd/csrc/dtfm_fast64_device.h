@@ -266,6 +266,35 @@ __device__ __forceinline__ void pair8_decode(int e, int &i, int &k)
 // byte k (0..7, not known at compile time) of a 64-bit value held as two dwords
 __device__ __forceinline__ uint32_t byte_at(uint2 v, int k) { return ((k < 4 ? v.x : v.y) >> (8 * (k & 3))) & 0xFFu; }
 
+// DataP of one stage (Eq. 2): max over its 8 devices of the row sums, each taken in slot order with
+// the device's own slot skipped. W_dp is bitwise symmetric, so the 28 entries above the diagonal serve
+// both row sums they appear in; a sum starts from its first term (0.0 + w = w for w >= +0.0).
+__device__ __forceinline__ double stage_datap(const double *Wdp, uint2 devs)
+{
+    uint32_t dv[8];
+#pragma unroll
+    for (int k = 0; k < 8; k++) dv[k] = byte_of(devs, k);
+    double w[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; i++)
+#pragma unroll
+        for (int k = i + 1; k < 8; k++) w[i][k] = w[k][i] = Wdp[dv[i] * NDEV + dv[k]];
+    double dp = 0.0;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        double sum = 0.0;
+        bool first = true;
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            if (k == i) continue;
+            sum = first ? w[i][k] : __dadd_rn(sum, w[i][k]);
+            first = false;
+        }
+        dp = i == 0 ? sum : fmax(dp, sum);
+    }
+    return dp;
+}
+
 // always true, but not to the compiler: splits straight-line code into basic blocks
 __device__ __forceinline__ bool opaque_true()
 {
