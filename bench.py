@@ -46,14 +46,14 @@ import workloads  # noqa: E402
 # (fp64 add/min/max issue at full rate), twice that for packed 16-bit ops.
 VALU_LANE_OPS_PER_S = 256 * 4 * 16 * 2.4e9
 # HBM bytes per candidate of the evaluation kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/k_eval_fast64_C2_P1048576.md (297.1 MB + 16.3 MB per 1,048,576 candidates,
+# summarised in profiles/k_eval_fast64_C2_P1048576.md (297.9 MB + 34.9 MB per 1,048,576 candidates,
 # each counter scaled by its reading for a 1 GiB device copy; 19 MB of the reads are the 72 KiB of
-# tables every workgroup stages in LDS). Algorithmic: 4N + 8 = 264 B.
-MEASURED_HBM_BYTES_PER_CANDIDATE = 298.8
+# tables every workgroup stages in LDS, 26 MB of the writes register spills). Algorithmic: 4N + 8 = 264 B.
+MEASURED_HBM_BYTES_PER_CANDIDATE = 317.4
 # Counter readings of the same launch from the same file (rocprofv3 --pmc): share of the vector-ALU
 # issue slots and of the LDS cycles in use, vector instructions per candidate.
-MEASURED_COUNTERS = {"valu_busy_frac": 0.805, "lds_busy_frac": 0.424, "lds_bank_conflict_frac_of_lds": 0.49,
-                     "valu_instructions_per_candidate": 653, "hbm_GBps": 225.0, "hbm_frac_of_8TBps": 0.028,
+MEASURED_COUNTERS = {"valu_busy_frac": 0.826, "lds_busy_frac": 0.403, "lds_bank_conflict_frac_of_lds": 0.47,
+                     "valu_instructions_per_candidate": 651, "hbm_GBps": 245.0, "hbm_frac_of_8TBps": 0.031,
                      "source": "profiles/k_eval_fast64_C2_P1048576.md"}
 
 

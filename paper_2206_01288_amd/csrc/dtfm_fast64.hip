@@ -198,7 +198,7 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
     const size_t ngroups = (P + NC - 1) / NC;
     for (size_t grp = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; grp < ngroups; grp += nwaves) {
         // ---- a1: NC candidate rows; position = lane: stage = lane / 8, slot = lane % 8 ----
-#pragma unroll
+#pragma unroll 8
         for (int c = 0; c < NC; c++) {
             size_t cand = grp * NC + c;
             if (cand >= P) cand = P - 1;   // ragged tail: recompute the last row, never stored
@@ -308,7 +308,7 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
     const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
     const size_t ngroups = (P + NC - 1) / NC;
     for (size_t grp = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; grp < ngroups; grp += nwaves) {
-#pragma unroll
+#pragma unroll 8
         for (int c = 0; c < NC; c++) {
             size_t cand = grp * NC + c;
             if (cand >= P) cand = P - 1;
@@ -326,7 +326,7 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
                 propose_gain4<NC>(cx, pbcur, prop, j, jp);
                 WAVE_LDS_SYNC();
                 // ---- trial rows; the evaluation starts from the current rows' coarsened graphs ----
-#pragma unroll
+#pragma unroll 8
                 for (int c = 0; c < NC; c++) {
                     const int ta = prop[2 * c], tb = prop[2 * c + 1];
                     const int src = lane == ta ? tb : (lane == tb ? ta : lane);
@@ -350,7 +350,7 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
                 if (mine) curc[lane] = t;
             }
             const uint64_t takes = __ballot(mine);
-#pragma unroll
+#pragma unroll 8
             for (int c = 0; c < NC; c++) {
                 const bool take = (takes >> c) & 1;   // wave-uniform
                 if (take) pbcur[c * 64 + lane] = wl[OFF_PB + c * 64 + lane];
@@ -363,7 +363,7 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
             }
             WAVE_LDS_SYNC();
         }
-#pragma unroll
+#pragma unroll 8
         for (int c = 0; c < NC; c++) {
             const size_t cand = grp * NC + c;
             if (cand < P) perm[cand * NDEV + lane] = pbcur[c * 64 + lane];
