@@ -156,20 +156,39 @@ template <int NB>  // number of 16-row register blocks: D_dp <= 16 * NB
 __global__ void __launch_bounds__(256)
 k_match(const uint32_t *__restrict__ Wr, const double *__restrict__ rank_val,
         const int32_t *__restrict__ perm, int N, int D_dp, int D_pp, int npairs, size_t total,
-        double *__restrict__ ghat)
+        double *__restrict__ ghat, int inc_j, int inc_jp)
 {
     const int lane = threadIdx.x & (DTFM_WAVE - 1);
     size_t item = (size_t)blockIdx.x * (blockDim.x / DTFM_WAVE) + threadIdx.x / DTFM_WAVE;
     if (item >= total) return;  // whole wavefront leaves together
     size_t p = item / npairs;
     int t = (int)(item - p * npairs);
-    // t-th stage pair (j1 < j2) in lexicographic order
-    int j1 = 0, rem = t;
-    while (rem >= D_pp - 1 - j1) {
-        rem -= D_pp - 1 - j1;
-        j1++;
+    int j1, j2;
+    if (inc_j < 0) {
+        // t-th stage pair (j1 < j2) in lexicographic order
+        int rem = t;
+        j1 = 0;
+        while (rem >= D_pp - 1 - j1) {
+            rem -= D_pp - 1 - j1;
+            j1++;
+        }
+        j2 = j1 + 1 + rem;
+    } else {
+        // only the npairs = 2 D_pp - 3 pairs that contain stage inc_j or inc_jp (inc_j < inc_jp): (inc_j, k) for
+        // the D_pp - 1 stages k != inc_j, then (inc_jp, k) for the D_pp - 2 others
+        int a, k;
+        if (t < D_pp - 1) {
+            a = inc_j;
+            k = t + (t >= inc_j ? 1 : 0);
+        } else {
+            a = inc_jp;
+            k = t - (D_pp - 1);
+            k += k >= inc_j ? 1 : 0;
+            k += k >= inc_jp ? 1 : 0;
+        }
+        j1 = a < k ? a : k;
+        j2 = a < k ? k : a;
     }
-    int j2 = j1 + 1 + rem;
     const int32_t *row = perm + p * N;
     const int32_t *Ca = row + j1 * D_dp;
     const bool active = lane < D_dp;
@@ -462,6 +481,14 @@ dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t ro
 int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int32_t *perm,
                       size_t rows, double *cost, hipStream_t st)
 {
+    return dtfm_eval_inc_enqueue(pr, b, perm, rows, cost, -1, -1, st);
+}
+
+// As dtfm_eval_enqueue; with inc_j >= 0 (inc_j < inc_jp) b.ghat already holds the coarsened graphs of rows
+// that differ from `perm` only in stages inc_j and inc_jp: only the edges of those two stages are matched again.
+int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int32_t *perm, size_t rows,
+                          double *cost, int inc_j, int inc_jp, hipStream_t st)
+{
     if (rows == 0) return DTFM_OK;
     if (pr->fast64)
         return cost != nullptr ? dtfm_fast64_enqueue(pr, perm, rows, cost, nullptr, nullptr, st)
@@ -483,12 +510,13 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
     }
     DTFM_HIP(hipGetLastError());
     if (pr->npairs > 0) {
-        size_t total = rows * (size_t)pr->npairs;
+        const int match_pairs = inc_j >= 0 ? 2 * n - 3 : pr->npairs;
+        size_t total = rows * (size_t)match_pairs;
         const int waves_per_block = 4;
         size_t blocks = (total + waves_per_block - 1) / waves_per_block;
         auto kern = pr->D_dp <= 16 ? k_match<1> : pr->D_dp <= 32 ? k_match<2> : pr->D_dp <= 48 ? k_match<3> : k_match<4>;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(waves_per_block * DTFM_WAVE), 0, st,
-                           pr->W_rank, pr->rank_val, perm, N, pr->D_dp, n, pr->npairs, total, b.ghat);
+                           pr->W_rank, pr->rank_val, perm, N, pr->D_dp, n, match_pairs, total, b.ghat, inc_j, inc_jp);
         DTFM_HIP(hipGetLastError());
     }
     if (cost == nullptr) return DTFM_OK;

@@ -82,6 +82,10 @@ dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t ro
 // enqueues a2..a6 for `rows` candidates; cost may be null (then only datap/ghat are produced)
 int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int32_t *perm,
                       size_t rows, double *cost, hipStream_t st);
+// the same when b.ghat already holds the coarsened graphs of rows that differ from `perm` only in stages
+// inc_j < inc_jp (inc_j < 0: plain evaluation): only the edges of those two stages are matched again
+int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int32_t *perm, size_t rows,
+                          double *cost, int inc_j, int inc_jp, hipStream_t st);
 int dtfm_weights_enqueue(const double *lat_dev, const double *bw_dev, int N, double shard,
                          double c_pp, double *W_dp, double *W_pp, hipStream_t st);
 
@@ -125,6 +129,7 @@ struct dtfm_ls_bufs {
     int32_t *move_ab;   // 2 * P (GAIN4: proposed positions)
     size_t chunk;       // candidates per ALL_PAIRS chunk
     size_t rows;        // rows evaluated per eval call
+    double *ghat_cur;   // P * D_pp * D_pp: coarsened graphs of the current rows (GAIN4 / KL rounds)
     dtfm_eval_bufs ev;
 };
 dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int neighbourhood);

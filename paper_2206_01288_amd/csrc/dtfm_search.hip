@@ -252,6 +252,16 @@ __global__ void k_kl_propose(const double *__restrict__ W_pp, const int32_t *__r
 }
 
 // GAIN4 and KL: accept the proposed swap iff its cost is strictly lower.
+// GAIN4 / KL rounds: the coarsened graph of an accepted trial row becomes the candidate's current one
+// (runs before k_accept, on the same condition)
+__global__ void k_keep_ghat(const double *__restrict__ tmp_cost, const double *__restrict__ cur, int nn,
+                            const double *__restrict__ ghat_trial, double *__restrict__ ghat_cur)
+{
+    const size_t p = blockIdx.x;
+    if (!(tmp_cost[p] < cur[p])) return;
+    for (int e = threadIdx.x; e < nn; e += blockDim.x) ghat_cur[p * nn + e] = ghat_trial[p * nn + e];
+}
+
 __global__ void k_accept(int32_t *__restrict__ perm, int N, const double *__restrict__ tmp_cost,
                          double *__restrict__ cur, const int32_t *__restrict__ move_ab,
                          int64_t *__restrict__ applied, int moves, int r, size_t P)
@@ -307,6 +317,7 @@ dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int
     }
     b.tmp_perm = ar.take<int32_t>(b.rows * N);
     b.tmp_cost = ar.take<double>(b.rows);
+    b.ghat_cur = ar.take<double>(P * (size_t)pr->D_pp * pr->D_pp);
     b.ev = dtfm_eval_carve(pr, ar, b.rows);
     return b;
 }
@@ -365,11 +376,40 @@ int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm
                 DTFM_HIP(hipGetLastError());
             }
         } else {
+            // A round's trial rows differ from the current rows in the round's two stages only: with three or
+            // more stages the trial evaluation starts from the current rows' coarsened graphs and matches
+            // again only the 2 D_pp - 3 edges of those two stages.
+            const int n = pr->D_pp, nn = n * n;
+            const bool inc = n >= 3 && !pr->fast64;   // the 64-device shape prices rows with its own fused kernel
+            int j = -1, jp = -1;
+            if (inc) {
+                int t = r % pr->npairs;   // the round's stage pair, lexicographic order
+                j = 0;
+                while (t >= n - 1 - j) {
+                    t -= n - 1 - j;
+                    j++;
+                }
+                jp = j + 1 + t;
+                if (r == 0) {   // the evaluation above left the current rows' graphs in b.ev.ghat
+                    hipLaunchKernelGGL(k_copy_f64, dim3((unsigned)((P * nn + 255) / 256)), dim3(256), 0, st, b.ev.ghat,
+                                       b.ghat_cur, P * nn);
+                    DTFM_HIP(hipGetLastError());
+                } else {
+                    hipLaunchKernelGGL(k_copy_f64, dim3((unsigned)((P * nn + 255) / 256)), dim3(256), 0, st, b.ghat_cur,
+                                       b.ev.ghat, P * nn);
+                    DTFM_HIP(hipGetLastError());
+                }
+            }
             hipLaunchKernelGGL(neighbourhood == DTFM_KL ? k_kl_propose : k_gain4_propose, dim3((unsigned)P),
                                dim3(DTFM_WAVE), 0, st, pr->W_pp, perm, N, pr->D_dp, pr->D_pp, r, b.tmp_perm, b.move_ab);
             DTFM_HIP(hipGetLastError());
-            rc = dtfm_eval_enqueue(pr, b.ev, b.tmp_perm, P, b.tmp_cost, st);
+            rc = dtfm_eval_inc_enqueue(pr, b.ev, b.tmp_perm, P, b.tmp_cost, j, jp, st);
             if (rc != DTFM_OK) return rc;
+            if (inc) {
+                hipLaunchKernelGGL(k_keep_ghat, dim3((unsigned)P), dim3(DTFM_WAVE), 0, st, b.tmp_cost, b.cur, nn, b.ev.ghat,
+                                   b.ghat_cur);
+                DTFM_HIP(hipGetLastError());
+            }
             hipLaunchKernelGGL(k_accept, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, perm, N, b.tmp_cost,
                                b.cur, b.move_ab, applied, moves, r, P);
             DTFM_HIP(hipGetLastError());
