@@ -151,6 +151,7 @@ __global__ void k_zero_f64(double *__restrict__ dst, size_t n)
 // an unvisited column: a perfect matching of rows 0..r0 within theta exists iff an alternating path
 // from r0 to a free column exists within theta (Berge), so the final theta is the new optimum.
 typedef uint32_t dtfm_u32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t dtfm_u32x32 __attribute__((ext_vector_type(32)));
 
 template <int NB>  // number of 16-row register blocks: D_dp <= 16 * NB
 __global__ void __launch_bounds__(256)
@@ -194,34 +195,29 @@ k_match(const uint32_t *__restrict__ Wr, const double *__restrict__ rank_val,
     const bool active = lane < D_dp;
     const uint32_t *col = Wr + (active ? row[j2 * D_dp + lane] : 0);
 
-    dtfm_u32x16 E0, E1, E2, E3;
+    // The block's column for this lane in registers: 16 entries (NB = 1), 32 (NB = 2) or two vectors of 32.
+    dtfm_u32x16 E0;
+    dtfm_u32x32 F0, F1;
 #pragma unroll
     for (int r = 0; r < 16; r++) {
-        E0[r] = r < D_dp ? col[(size_t)Ca[r] * N] : 0xffffffffu;
-        if (NB > 1) E1[r] = r + 16 < D_dp ? col[(size_t)Ca[r + 16] * N] : 0xffffffffu;
-        if (NB > 2) E2[r] = r + 32 < D_dp ? col[(size_t)Ca[r + 32] * N] : 0xffffffffu;
-        if (NB > 3) E3[r] = r + 48 < D_dp ? col[(size_t)Ca[r + 48] * N] : 0xffffffffu;
+        if (NB == 1) E0[r] = r < D_dp ? col[(size_t)Ca[r] * N] : 0xffffffffu;
     }
-    // E[r] for a wavefront-uniform r. The empty asm statements keep the four register-relative
+#pragma unroll
+    for (int r = 0; r < 32; r++) {
+        if (NB > 1) F0[r] = r < D_dp ? col[(size_t)Ca[r] * N] : 0xffffffffu;
+        if (NB > 2) F1[r] = r + 32 < D_dp ? col[(size_t)Ca[r + 32] * N] : 0xffffffffu;
+    }
+    // E[r] for a wavefront-uniform r. The empty asm statements keep the two register-relative
     // reads apart (merged into one 64-entry access they would go through scratch memory).
     auto entry = [&](int r) -> uint32_t {
-        const int lo = r & 15, hi = r >> 4;
-        uint32_t w = E0[lo];
-        asm volatile("" : "+v"(w));
-        if (NB > 1) {
-            uint32_t x = E1[lo];
+        if (NB == 1) return E0[r & 15];
+        const int lo = r & 31, hi = r >> 5;
+        uint32_t w = F0[lo];
+        if (NB > 2) {
+            asm volatile("" : "+v"(w));
+            uint32_t x = F1[lo];
             asm volatile("" : "+v"(x));
             w = hi == 1 ? x : w;
-        }
-        if (NB > 2) {
-            uint32_t x = E2[lo];
-            asm volatile("" : "+v"(x));
-            w = hi == 2 ? x : w;
-        }
-        if (NB > 3) {
-            uint32_t x = E3[lo];
-            asm volatile("" : "+v"(x));
-            w = hi == 3 ? x : w;
         }
         return w;
     };
