@@ -504,13 +504,16 @@ __global__ void k_init_population(uint32_t k0, uint32_t k1, int N, int32_t *__re
 
 // One offspring per workgroup: selection (two uniform parents), crossover (child = parent 1; m_x
 // times a random device that parent 2 keeps in another stage is swapped with the device at a
-// random slot of that stage), mutation (m_m random transpositions). Copies and inversions are
-// done by all lanes, the dependent steps by lane 0 in LDS.
+// random slot of that stage), mutation (m_m random transpositions). Copies, inversions and the
+// random draws (two steps per Philox block) are done by all lanes, DTFM_DRAW_CHUNK steps at a time;
+// the dependent swaps by lane 0 in LDS.
+#define DTFM_DRAW_CHUNK 128
 __global__ void k_make_offspring(uint32_t k0, uint32_t k1, uint32_t g, const int32_t *__restrict__ pop,
                                  int P, int N, int D_dp, int m_x, int m_m, int32_t *__restrict__ off)
 {
     extern __shared__ int32_t sm[];
-    int32_t *child = sm, *pos_child = sm + N, *pos_par2 = sm + 2 * N;
+    int32_t *child = sm, *pos_child = sm + N, *pos_par2 = sm + 2 * N, *stage_of = sm + 3 * N;
+    int32_t *draw_a = sm + 4 * N, *draw_b = draw_a + DTFM_DRAW_CHUNK;
     uint32_t k = blockIdx.x;
     philox_out sel = philox4x32_10(0u, k, g, STREAM_SELECT, k0, k1);
     int p1 = (int)randint(sel.w[0], (uint32_t)P), p2 = (int)randint(sel.w[1], (uint32_t)P);
@@ -520,31 +523,52 @@ __global__ void k_make_offspring(uint32_t k0, uint32_t k1, uint32_t g, const int
         child[q] = d;
         pos_child[d] = q;
         pos_par2[par2[q]] = q;
+        stage_of[q] = q / D_dp;
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        philox_out o;
-        for (int t = 0; t < m_x; t++) {
-            if ((t & 1) == 0) o = philox4x32_10((uint32_t)(t >> 1), k, g, STREAM_CROSSOVER, k0, k1);
-            int d = (int)randint(o.w[2 * (t & 1)], (uint32_t)N);
-            int slot = (int)randint(o.w[2 * (t & 1) + 1], (uint32_t)D_dp);
-            int qa = pos_child[d];
-            int s1 = qa / D_dp, s2 = pos_par2[d] / D_dp;
-            if (s1 == s2) continue;
-            int qb = s2 * D_dp + slot;
-            int e = child[qb];
-            child[qa] = e;
-            child[qb] = d;
-            pos_child[e] = qa;
-            pos_child[d] = qb;
+    for (int t0 = 0; t0 < m_x; t0 += DTFM_DRAW_CHUNK) {
+        const int steps = min(DTFM_DRAW_CHUNK, m_x - t0);   // t0 is even: step t0 + 2 b + h uses words 2 h, 2 h + 1 of block (t0 / 2 + b)
+        __syncthreads();
+        for (int blk = threadIdx.x; 2 * blk < steps; blk += blockDim.x) {
+            const philox_out o = philox4x32_10((uint32_t)(t0 / 2 + blk), k, g, STREAM_CROSSOVER, k0, k1);
+            for (int h = 0; h < 2; h++) {
+                draw_a[2 * blk + h] = (int32_t)randint(o.w[2 * h], (uint32_t)N);          // device
+                draw_b[2 * blk + h] = (int32_t)randint(o.w[2 * h + 1], (uint32_t)D_dp);   // slot
+            }
         }
-        for (int t = 0; t < m_m; t++) {
-            if ((t & 1) == 0) o = philox4x32_10((uint32_t)(t >> 1), k, g, STREAM_MUTATION, k0, k1);
-            int a = (int)randint(o.w[2 * (t & 1)], (uint32_t)N);
-            int b = (int)randint(o.w[2 * (t & 1) + 1], (uint32_t)N);
-            int32_t x = child[a];
-            child[a] = child[b];
-            child[b] = x;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int t = 0; t < steps; t++) {
+                const int d = draw_a[t], slot = draw_b[t];
+                const int qa = pos_child[d];
+                const int s1 = stage_of[qa], s2 = stage_of[pos_par2[d]];
+                if (s1 == s2) continue;
+                const int qb = s2 * D_dp + slot;
+                const int e = child[qb];
+                child[qa] = e;
+                child[qb] = d;
+                pos_child[e] = qa;
+                pos_child[d] = qb;
+            }
+        }
+    }
+    for (int t0 = 0; t0 < m_m; t0 += DTFM_DRAW_CHUNK) {
+        const int steps = min(DTFM_DRAW_CHUNK, m_m - t0);
+        __syncthreads();
+        for (int blk = threadIdx.x; 2 * blk < steps; blk += blockDim.x) {
+            const philox_out o = philox4x32_10((uint32_t)(t0 / 2 + blk), k, g, STREAM_MUTATION, k0, k1);
+            for (int h = 0; h < 2; h++) {
+                draw_a[2 * blk + h] = (int32_t)randint(o.w[2 * h], (uint32_t)N);
+                draw_b[2 * blk + h] = (int32_t)randint(o.w[2 * h + 1], (uint32_t)N);
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int t = 0; t < steps; t++) {
+                const int a = draw_a[t], b = draw_b[t];
+                const int32_t x = child[a];
+                child[a] = child[b];
+                child[b] = x;
+            }
         }
     }
     __syncthreads();
@@ -665,7 +689,7 @@ int dtfm_ga_enqueue(const dtfm_problem *pr, const dtfm_ga_bufs &b, uint64_t seed
     int32_t *pop_cur = population, *pop_next = b.next;
     double *cost_cur = cost, *cost_next = b.next_cost;
     for (int g = 0; g < generations; g++) {
-        hipLaunchKernelGGL(k_make_offspring, dim3(L), dim3(DTFM_WAVE), 3 * N * sizeof(int32_t), st, k0, k1,
+        hipLaunchKernelGGL(k_make_offspring, dim3(L), dim3(DTFM_WAVE), (4 * N + 2 * DTFM_DRAW_CHUNK) * sizeof(int32_t), st, k0, k1,
                            (uint32_t)g, pop_cur, P, N, pr->D_dp, prm.m_x, prm.m_m, b.off);
         DTFM_HIP(hipGetLastError());
         rc = dtfm_ls_enqueue(pr, b.ls, b.off, L, prm.ls_moves, prm.neighbourhood, b.off_cost, nullptr, st);

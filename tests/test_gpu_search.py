@@ -245,6 +245,12 @@ def test_evolve_replacement_across_key_chunks():
     _evolve_parity(workloads.config("C3h"), 23, 2, 130, lam=140, ls_moves=1, neighbourhood=dtfm.GAIN4)
 
 
+def test_evolve_many_crossover_and_mutation_draws():
+    # more draws per offspring than the offspring kernel generates at a time (128), odd counts
+    _evolve_parity(workloads.config("C2"), 31, 2, 10, m_x=131, m_m=129, ls_moves=0)
+    _evolve_parity(workloads.config("C1"), 32, 3, 6, m_x=257, m_m=1, ls_moves=1, neighbourhood=dtfm.GAIN4)
+
+
 def test_evolve_config5_shape_small_population():
     w = workloads.config("C5")
     _evolve_parity(w, 7, 2, 5, ls_moves=2, neighbourhood=dtfm.GAIN4)
