@@ -197,14 +197,19 @@ __device__ __forceinline__ void eval_group(const wave_ctx &cx, double *__restric
     for (int h = 0; h < HPASSES; h++) {
         const int hc = (8 * h + (lane >> 3)) % NC;
         // ---- a5: winning ranks -> fp64 weights; Held-Karp in registers ----
+        // With four candidates the upper half of the wavefront shares the work of the lower half: its
+        // lanes stand for the stages with bits 0 and 1 swapped (see hk_registers).
+        constexpr bool SPLIT = NC == 4;
+        const bool relabel = SPLIT && lane >= 32;
+        const int v = relabel ? hk_swap01(cx.hv) : cx.hv;
         double G[8];
         G[0] = 0.0;
 #pragma unroll
         for (int d = 1; d < 8; d++) {
-            const int u = cx.hv ^ d;
-            G[d] = cx.rank_val[ghr16[hc * 28 + pair_index(u < cx.hv ? u : cx.hv, u < cx.hv ? cx.hv : u)]];
+            const int u = v ^ (relabel ? hk_swap01(d) : d);
+            G[d] = cx.rank_val[ghr16[hc * 28 + pair_index(u < v ? u : v, u < v ? v : u)]];
         }
-        const double pp = hk_registers(G);
+        const double pp = hk_registers<SPLIT>(G, lane);
         // ---- a2/a3: DataP of stage hv of candidate hc, then max over the candidate's 8 lanes ----
         double dp = stage_datap(cx.Wdp, *reinterpret_cast<const uint2 *>(wl + OFF_PB + hc * 64 + 8 * cx.hv));
         dp = fmax(dp, dpp_move<DPP_XOR1>(dp));

@@ -201,7 +201,7 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
                     e = ((vj && ujp) || (vjp && uj)) ? ((batch & 1) ? AP_EDGE_SCR_ODD : AP_EDGE_SCR) + mv : e;
                     G[d] = rank_val[edge[e]];
                 }
-                const double pp = hk_registers(G);
+                const double pp = hk_registers<false>(G, lane);
                 if (it == 0) {
                     pp_base = pp;
                 } else {

@@ -114,6 +114,39 @@ constexpr hk_program make_hk_program()
 }
 constexpr hk_program HKP = make_hk_program();
 
+// Sharing one candidate's Held-Karp between two groups of 8 lanes. Relabelling the stages by the
+// linear map A of Z_2^3 that swaps bits 0 and 1 (offsets 1 <-> 2, 5 <-> 6; 3, 4, 7 fixed) maps a path
+// to a path, and offsets to offsets: a second group of lanes whose lane position q stands for stage
+// A(q), and whose G[d] holds the edge to stage A(q) xor A(d), runs the same register programme and
+// has in the register of class D the entry of class A(D). Each group then only computes the classes
+// D <= A(D) (as masks) of every layer, 280 of the 448 relaxations, and gets the others from the
+// register of A(D) of the other group (at the lane position A(q)).
+constexpr int hk_swap01(int d) { return (d & 4) | ((d & 1) << 1) | ((d >> 1) & 1); }
+constexpr int hk_class_image(int D)
+{
+    int out = 0;
+    for (int e = 1; e < 8; e++)
+        if ((D >> e) & 1) out |= 1 << hk_swap01(e);
+    return out;
+}
+// HKS.keep[J][i]: class i of layer J is computed by the group itself; HKS.image[J][i]: index of A(class i)
+struct hk_split_table {
+    bool keep[8][35];
+    unsigned char image[8][35];
+};
+constexpr hk_split_table make_hk_split()
+{
+    hk_split_table t = {};
+    for (int J = 0; J <= 7; J++)
+        for (int i = 0; i < BINOM7[J]; i++) {
+            const int D = HKC.cls[J][i], AD = hk_class_image(D);
+            t.keep[J][i] = D <= AD;
+            t.image[J][i] = HKC.idx[AD];
+        }
+    return t;
+}
+constexpr hk_split_table HKS = make_hk_split();
+
 // ---- LDS tables shared by a workgroup of the fused kernels ----
 constexpr int LDS_RANK_BYTES = ((NDEV * RSTRIDE * 2 + 15) / 16) * 16;   // 8.25 KiB: u16 rank of W_pp
 constexpr int LDS_RVAL_BYTES = NDEV * NDEV * 8;                         // 32 KiB: rank -> weight
@@ -203,9 +236,11 @@ __device__ __forceinline__ double lane_xor_swizzle(double x, int d)
 #endif
 
 // One layer of Held-Karp: classes with J elements from the classes with J - 1. Source-major order, so
-// that the mirrored copy of a source serves all its relaxations through d = 4, 5, 6.
-template <int J>
-__device__ __forceinline__ void hk_layer(const double (&prev)[35], double (&cur)[35], const double (&G)[8])
+// that the mirrored copy of a source serves all its relaxations through d = 4, 5, 6. With SPLIT only
+// the classes the group keeps (HKS.keep) are computed; the others then come from the other group of
+// the candidate through `cross`, the byte address of the lane that holds them (ds_bpermute).
+template <int J, bool SPLIT>
+__device__ __forceinline__ void hk_layer(const double (&prev)[35], double (&cur)[35], const double (&G)[8], int cross)
 {
 #pragma unroll
     for (int s = 0; s < BINOM7[J - 1]; s++) {
@@ -220,6 +255,7 @@ __device__ __forceinline__ void hk_layer(const double (&prev)[35], double (&cur)
             const int step = HKP.step[J][s][d];
             if (step == 0xFF) continue;
             const int i = step & 0x7F;
+            if (SPLIT && !HKS.keep[J][i]) continue;
             // tab[S \ v][u] at u = v xor d, then + Ghat[u][v]
             double moved;
             if ((HK_SWIZZLE_SET >> d) & 1) moved = lane_xor_swizzle(x, d);
@@ -228,22 +264,36 @@ __device__ __forceinline__ void hk_layer(const double (&prev)[35], double (&cur)
             cur[i] = (step & 0x80) ? t : fmin(cur[i], t);
         }
     }
+    if (SPLIT && J < 7) {
+#pragma unroll
+        for (int i = 0; i < BINOM7[J]; i++) {
+            if (HKS.keep[J][i]) continue;
+            const uint64_t b = __builtin_bit_cast(uint64_t, cur[HKS.image[J][i]]);
+            const int lo = __builtin_amdgcn_ds_bpermute(cross, (int)(uint32_t)b);
+            const int hi = __builtin_amdgcn_ds_bpermute(cross, (int)(uint32_t)(b >> 32));
+            cur[i] = __builtin_bit_cast(double, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+        }
+    }
 }
 
 // Eq. 4 for the candidate of this lane's 8-lane group; G[d] = Ghat[v][v xor d] of the lane's stage v.
-// Every lane of the group returns the optimum.
-__device__ __forceinline__ double hk_registers(const double (&G)[8])
+// Every lane of the group returns the optimum. With SPLIT the candidate has two groups, lanes l and
+// l xor 32; the upper one is relabelled (stage hk_swap01(l & 7), G[d] = Ghat[v][v xor hk_swap01(d)]).
+template <bool SPLIT>
+__device__ __forceinline__ double hk_registers(const double (&G)[8], int lane)
 {
+    const int other = lane ^ 32;
+    const int cross = 4 * ((other & ~3) | ((other & 1) << 1) | ((other >> 1) & 1));
     double a[35], b[35];
     // one stage: 0; two stages {v, v xor d}: 0 + Ghat
 #pragma unroll
     for (int d = 1; d < 8; d++) b[HKC.idx[1 << d]] = G[d];
-    hk_layer<2>(b, a, G);
-    hk_layer<3>(a, b, G);
-    hk_layer<4>(b, a, G);
-    hk_layer<5>(a, b, G);
-    hk_layer<6>(b, a, G);
-    hk_layer<7>(a, b, G);
+    hk_layer<2, SPLIT>(b, a, G, cross);
+    hk_layer<3, SPLIT>(a, b, G, cross);
+    hk_layer<4, SPLIT>(b, a, G, cross);
+    hk_layer<5, SPLIT>(a, b, G, cross);
+    hk_layer<6, SPLIT>(b, a, G, cross);
+    hk_layer<7, SPLIT>(a, b, G, cross);
     double pp = b[0];   // all eight stages, ending in v: min over v
     pp = fmin(pp, dpp_move<DPP_XOR1>(pp));
     pp = fmin(pp, dpp_move<DPP_XOR2>(pp));
