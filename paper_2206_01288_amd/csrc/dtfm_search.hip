@@ -577,9 +577,10 @@ __global__ void k_make_offspring(uint32_t k0, uint32_t k1, uint32_t g, const int
 
 // Replacement: rank of element i among parents (origin 0..P-1) and offspring (origin P..P+L-1)
 // under the order (cost, origin); the P lowest survive, placed at their rank. The count over the
-// P+L keys is split: block (x, y) counts, for 256 elements i, the keys of chunk y (staged in LDS)
-// that precede them, and adds the partial count to rank[i].
-#define DTFM_RANK_CHUNK 256
+// P+L keys is split: block (x, y) counts, for 256 elements i, the keys of chunk y that precede them,
+// and adds the partial count to rank[i]. A wavefront walks its chunk in dependent steps of sixteen
+// keys, each a round trip to the scalar cache: short chunks (many blocks) keep that chain short.
+#define DTFM_RANK_CHUNK 64
 // counts the keys key[0..m) that precede element (ci, i); j_first = index of key[0] among all keys.
 // MODE 0: key <= ci (the keys all have lower indices), 1: key < ci (all higher), 2: index compared.
 // The key address is the same for every lane: the loads go through the scalar cache, sixteen keys at a time.
@@ -604,17 +605,39 @@ __device__ __forceinline__ int count_before(const double *__restrict__ key, int 
     return cnt;
 }
 
+// With parents_sorted the parents are in (cost, origin) order already (every generation but the first:
+// the previous replacement placed them by rank): parent i has i parents before it, an offspring as
+// many as have a cost <= its own (binary search), and only the offspring keys are counted.
 __global__ void k_rank_count(const double *__restrict__ cost, const double *__restrict__ off_cost, int P, int L,
-                             int32_t *__restrict__ rank)
+                             int parents_sorted, int32_t *__restrict__ rank)
 {
     const int n = P + L;
     const int j0 = blockIdx.y * DTFM_RANK_CHUNK;
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    const double ci = i < P ? cost[i] : off_cost[i - P];
     const int j1 = j0 + DTFM_RANK_CHUNK < n ? j0 + DTFM_RANK_CHUNK : n;
+    if (parents_sorted && blockIdx.y != 0 && j1 <= P) return;
+    const double ci = i < P ? cost[i] : off_cost[i - P];
     // the chunk's keys: [ja, jb) among the parents, [jc, jd) among the offspring
-    const int ja = j0 < P ? j0 : P, jb = j1 < P ? j1 : P, jc = j0 > P ? j0 : P, jd = j1 > P ? j1 : P;
+    int ja = j0 < P ? j0 : P, jb = j1 < P ? j1 : P;
+    const int jc = j0 > P ? j0 : P, jd = j1 > P ? j1 : P;
+    int base = 0;
+    if (parents_sorted) {
+        if (blockIdx.y == 0) {
+            if (i < P) {
+                base = i;
+            } else {
+                int lo = 0, hi = P;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (cost[mid] <= ci) lo = mid + 1;
+                    else hi = mid;
+                }
+                base = lo;
+            }
+        }
+        ja = jb = P;   // no parent keys
+    }
     // A chunk that lies wholly before (after) this block's elements needs no index comparison: ties go
     // to the key (to the element).
     const int i0 = blockIdx.x * blockDim.x;
@@ -625,6 +648,7 @@ __global__ void k_rank_count(const double *__restrict__ cost, const double *__re
         cnt = count_before<1>(cost + ja, jb - ja, ja, ci, i) + count_before<1>(off_cost + (jc - P), jd - jc, jc, ci, i);
     else
         cnt = count_before<2>(cost + ja, jb - ja, ja, ci, i) + count_before<2>(off_cost + (jc - P), jd - jc, jc, ci, i);
+    cnt += base;
     if (cnt) atomicAdd(&rank[i], cnt);
 }
 
@@ -695,7 +719,7 @@ int dtfm_ga_enqueue(const dtfm_problem *pr, const dtfm_ga_bufs &b, uint64_t seed
         rc = dtfm_ls_enqueue(pr, b.ls, b.off, L, prm.ls_moves, prm.neighbourhood, b.off_cost, nullptr, st);
         if (rc != DTFM_OK) return rc;
         hipLaunchKernelGGL(k_rank_count, dim3((nk + 255) / 256, (nk + DTFM_RANK_CHUNK - 1) / DTFM_RANK_CHUNK), dim3(256), 0,
-                           st, cost_cur, b.off_cost, P, L, b.rank);
+                           st, cost_cur, b.off_cost, P, L, g > 0 ? 1 : 0, b.rank);
         DTFM_HIP(hipGetLastError());
         hipLaunchKernelGGL(k_rank_place, dim3(nk), dim3(DTFM_WAVE), 0, st, pop_cur, b.off, cost_cur, b.off_cost, P, L, N,
                            b.rank, pop_next, cost_next, best_trace + g);

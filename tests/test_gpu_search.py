@@ -236,7 +236,7 @@ def test_evolve_config2_shape():
 
 
 def test_evolve_replacement_across_key_chunks():
-    # populations and offspring counts that are not multiples of the rank kernel's 256-key chunks, with the
+    # populations and offspring counts that are not multiples of the rank kernel's 64-key chunks and 256-element blocks, with the
     # parents/offspring boundary inside a chunk; odd and even generation counts (the population alternates
     # between two buffers); the homogeneous network makes every cost tie, so only origin indices decide
     w = workloads.config("C1")
