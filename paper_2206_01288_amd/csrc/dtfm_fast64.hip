@@ -43,7 +43,7 @@ constexpr int wave_lds_bytes(int nc, bool ls) { return ((ls ? off_ghrcur(nc) + n
 // the local-search kernels also keep W_pp in LDS (for the proposals), except with 32 candidates per
 // wavefront, where the slices need the room and two wavefronts per SIMD hide the latency of L2
 constexpr bool wpp_in_lds(int nc, bool ls) { return ls && nc < 32; }
-constexpr int lds_total(int nc, bool ls) { return LDS_TABLES + (wpp_in_lds(nc, ls) ? LDS_WDP_BYTES : 0) + WAVES_PER_BLOCK * wave_lds_bytes(nc, ls); }
+constexpr int lds_total(int nc, bool ls, int waves = WAVES_PER_BLOCK) { return LDS_TABLES + (wpp_in_lds(nc, ls) ? LDS_WDP_BYTES : 0) + waves * wave_lds_bytes(nc, ls); }
 static_assert(lds_total(MAXC, true) <= 160 * 1024, "LDS budget of a CU");
 
 // Per-wavefront context: LDS pointers and the lane's fixed roles.
@@ -232,9 +232,10 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
     extern __shared__ __align__(16) unsigned char smem[];
     const wave_ctx cx = wave_setup<NC, false>(smem, rank_tab, rank_val, W_dp, nullptr);
     const int lane = cx.lane, wave = threadIdx.x >> 6;
-    const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
+    const int wpb = blockDim.x >> 6;   // wavefronts per workgroup: WAVES_PER_BLOCK, fewer for small populations
+    const size_t nwaves = (size_t)gridDim.x * wpb;
     const size_t ngroups = (P + NC - 1) / NC;
-    for (size_t grp = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; grp < ngroups; grp += nwaves) {
+    for (size_t grp = (size_t)blockIdx.x * wpb + wave; grp < ngroups; grp += nwaves) {
         // ---- a1: NC candidate rows; position = lane: stage = lane / 8, slot = lane % 8 ----
 #pragma unroll 8
         for (int c = 0; c < NC; c++) {
@@ -343,9 +344,10 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
     const double *res = reinterpret_cast<const double *>(wl + off_res(NC));
     double *curc = reinterpret_cast<double *>(wl + off_curc(NC));
     uint32_t *ghr32 = reinterpret_cast<uint32_t *>(wl + off_ghr(NC)), *ghrcur32 = reinterpret_cast<uint32_t *>(wl + off_ghrcur(NC));
-    const size_t nwaves = (size_t)gridDim.x * WAVES_PER_BLOCK;
+    const int wpb = blockDim.x >> 6;   // wavefronts per workgroup: WAVES_PER_BLOCK, fewer for small populations
+    const size_t nwaves = (size_t)gridDim.x * wpb;
     const size_t ngroups = (P + NC - 1) / NC;
-    for (size_t grp = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; grp < ngroups; grp += nwaves) {
+    for (size_t grp = (size_t)blockIdx.x * wpb + wave; grp < ngroups; grp += nwaves) {
 #pragma unroll 8
         for (int c = 0; c < NC; c++) {
             size_t cand = grp * NC + c;
@@ -486,14 +488,25 @@ static int group_size(const dtfm_problem *pr, size_t rows)
     return rows <= 4 * simds ? 4 : 8;
 }
 
+// Wavefronts per workgroup. The LDS tables allow one workgroup per CU, so a launch with fewer
+// workgroups than CUs leaves CUs idle: with few passes the workgroups get fewer wavefronts (down to
+// two, which still load the tables in reasonable time) so that every CU has one.
+static int waves_per_block(const dtfm_problem *pr, size_t passes)
+{
+    int w = WAVES_PER_BLOCK;
+    while (w > 2 && passes < (size_t)w * pr->f64_grid) w >>= 1;
+    return w;
+}
+
 template <int NC>
 static void launch_eval(const dtfm_problem *pr, const int32_t *perm, size_t rows, double *cost, double *ghat,
                         double *datap, hipStream_t st)
 {
     size_t passes = (rows + NC - 1) / NC;
-    size_t blocks = (passes + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    const int wpb = waves_per_block(pr, passes);
+    size_t blocks = (passes + wpb - 1) / wpb;
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    hipLaunchKernelGGL(k_eval_fast64<NC>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), lds_total(NC, false), st,
+    hipLaunchKernelGGL(k_eval_fast64<NC>, dim3((unsigned)blocks), dim3(wpb * 64), lds_total(NC, false, wpb), st,
                        pr->W_dp, pr->f64_rank, pr->f64_rank_val, perm, rows, cost, ghat, datap);
 }
 
@@ -515,9 +528,10 @@ static void launch_ls(const dtfm_problem *pr, int32_t *perm, size_t rows, int mo
                       hipStream_t st)
 {
     size_t passes = (rows + NC - 1) / NC;
-    size_t blocks = (passes + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    const int wpb = waves_per_block(pr, passes);
+    size_t blocks = (passes + wpb - 1) / wpb;
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    hipLaunchKernelGGL(k_ls_gain4_fast64<NC>, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), lds_total(NC, true), st,
+    hipLaunchKernelGGL(k_ls_gain4_fast64<NC>, dim3((unsigned)blocks), dim3(wpb * 64), lds_total(NC, true, wpb), st,
                        pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied);
 }
 

@@ -95,7 +95,8 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
     double *dpb = reinterpret_cast<double *>(wl + AP_OFF_DPB);
     const int hm = lane >> 3, hv = lane & 7;   // Held-Karp role: swap slot within the pass, stage
 
-    for (size_t cand = (size_t)blockIdx.x * WAVES_PER_BLOCK + wave; cand < P; cand += (size_t)gridDim.x * WAVES_PER_BLOCK) {
+    const int wpb = blockDim.x >> 6;   // wavefronts per workgroup: WAVES_PER_BLOCK, fewer when there are few rows
+    for (size_t cand = (size_t)blockIdx.x * wpb + wave; cand < P; cand += (size_t)gridDim.x * wpb) {
         cur[lane] = (unsigned char)perm[cand * NDEV + lane];
         WAVE_LDS_SYNC();
         double cur_cost = 0.0;
@@ -276,15 +277,25 @@ int dtfm_fast64_allpairs_prepare()
     return DTFM_OK;
 }
 
+// Wavefronts per workgroup: one workgroup fits a CU, so with few rows the workgroups get fewer
+// wavefronts (down to two) and every CU gets one.
+static int ap_waves_per_block(const dtfm_problem *pr, size_t rows)
+{
+    int w = WAVES_PER_BLOCK;
+    while (w > 2 && rows < (size_t)w * pr->f64_grid) w >>= 1;
+    return w;
+}
+
 // All `moves` >= 1 rounds of the ALL_PAIRS local search in one launch; perm in/out, cost out (the cost of
 // the final rows), applied (rows * moves move indices or -1) may be null.
 int dtfm_fast64_ls_allpairs_enqueue(const dtfm_problem *pr, int32_t *perm, size_t rows, int moves, double *cost,
                                     int64_t *applied, hipStream_t st)
 {
     if (rows == 0 || moves <= 0) return DTFM_OK;
-    size_t blocks = (rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    const int wpb = ap_waves_per_block(pr, rows);
+    size_t blocks = (rows + wpb - 1) / wpb;
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    hipLaunchKernelGGL(k_ls_allpairs_fast64, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), AP_LDS_TOTAL, st, pr->W_dp,
+    hipLaunchKernelGGL(k_ls_allpairs_fast64, dim3((unsigned)blocks), dim3(wpb * 64), LDS_TABLES + wpb * AP_WAVE_BYTES, st, pr->W_dp,
                        pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied, (double *)nullptr);
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
@@ -295,9 +306,10 @@ int dtfm_fast64_move_costs_enqueue(const dtfm_problem *pr, const int32_t *perm, 
                                    hipStream_t st)
 {
     if (rows == 0) return DTFM_OK;
-    size_t blocks = (rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    const int wpb = ap_waves_per_block(pr, rows);
+    size_t blocks = (rows + wpb - 1) / wpb;
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    hipLaunchKernelGGL(k_ls_allpairs_fast64, dim3((unsigned)blocks), dim3(WAVES_PER_BLOCK * 64), AP_LDS_TOTAL, st, pr->W_dp,
+    hipLaunchKernelGGL(k_ls_allpairs_fast64, dim3((unsigned)blocks), dim3(wpb * 64), LDS_TABLES + wpb * AP_WAVE_BYTES, st, pr->W_dp,
                        pr->f64_rank, pr->f64_rank_val, const_cast<int32_t *>(perm), rows, 1, (double *)nullptr,
                        (int64_t *)nullptr, move_cost);
     DTFM_HIP(hipGetLastError());
