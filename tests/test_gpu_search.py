@@ -128,9 +128,10 @@ def test_gain4_config2():
     assert (applied >= 0).any()
 
 
-@pytest.mark.parametrize("P", [16500, 65573])
+@pytest.mark.parametrize("P", [9001, 16500, 65573])
 def test_gain4_large_population_variants(P):
-    # 16500: eight candidates per wavefront pass; 65573: thirty-two, with a ragged last group
+    # 9001, 16500: eight candidates per wavefront pass (workgroups of four and of eight wavefronts);
+    # 65573: thirty-two, with a ragged last group
     w = workloads.config("C2")
     o, g = both(w)
     perms = workloads.random_population(P, 64, seed=12)
