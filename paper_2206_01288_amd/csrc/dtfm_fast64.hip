@@ -489,12 +489,13 @@ static int group_size(const dtfm_problem *pr, size_t rows)
 }
 
 // Wavefronts per workgroup. The LDS tables allow one workgroup per CU, so a launch with fewer
-// workgroups than CUs leaves CUs idle: with few passes the workgroups get fewer wavefronts (down to
-// two, which still load the tables in reasonable time) so that every CU has one.
+// workgroups than CUs leaves CUs idle: the workgroups get as few wavefronts (two at least, which
+// still load the tables in reasonable time) as give every pass a wavefront of its own on the chip's
+// CUs; beyond 8 per CU the wavefronts take several passes each.
 static int waves_per_block(const dtfm_problem *pr, size_t passes)
 {
-    int w = WAVES_PER_BLOCK;
-    while (w > 2 && passes < (size_t)w * pr->f64_grid) w >>= 1;
+    int w = 2;
+    while (w < WAVES_PER_BLOCK && (passes + w - 1) / w > (size_t)pr->f64_grid) w <<= 1;
     return w;
 }
 

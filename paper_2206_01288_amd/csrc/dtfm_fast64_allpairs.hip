@@ -277,12 +277,12 @@ int dtfm_fast64_allpairs_prepare()
     return DTFM_OK;
 }
 
-// Wavefronts per workgroup: one workgroup fits a CU, so with few rows the workgroups get fewer
-// wavefronts (down to two) and every CU gets one.
+// Wavefronts per workgroup: one workgroup fits a CU, so the workgroups get as few wavefronts (two at
+// least) as give every row a wavefront of its own on the chip's CUs.
 static int ap_waves_per_block(const dtfm_problem *pr, size_t rows)
 {
-    int w = WAVES_PER_BLOCK;
-    while (w > 2 && rows < (size_t)w * pr->f64_grid) w >>= 1;
+    int w = 2;
+    while (w < WAVES_PER_BLOCK && (rows + w - 1) / w > (size_t)pr->f64_grid) w <<= 1;
     return w;
 }
 
