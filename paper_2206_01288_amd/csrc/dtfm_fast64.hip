@@ -511,10 +511,27 @@ static void launch_eval(const dtfm_problem *pr, const int32_t *perm, size_t rows
                        pr->W_dp, pr->f64_rank, pr->f64_rank_val, perm, rows, cost, ghat, datap);
 }
 
+// With 32 candidates per pass the chip's wavefront slots (two per SIMD) take 65,536 candidates per
+// round of passes. What is left after the last full round, if it is not nearly a round itself, goes to
+// a launch of its own with a smaller group size instead of costing a whole further round.
+static size_t full_rounds_rows(const dtfm_problem *pr, size_t rows)
+{
+    const size_t round = 32 * 2 * 4 * (size_t)pr->f64_grid;
+    const size_t rest = rows % round;
+    return (rows >= round && rest != 0 && rest <= round * 3 / 4) ? rows - rest : rows;
+}
+
 int dtfm_fast64_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows, double *cost, double *ghat,
                         double *datap, hipStream_t st)
 {
     if (rows == 0) return DTFM_OK;
+    const size_t head = full_rounds_rows(pr, rows);
+    if (head < rows) {
+        int rc = dtfm_fast64_enqueue(pr, perm, head, cost, ghat, datap, st);
+        if (rc != DTFM_OK) return rc;
+        return dtfm_fast64_enqueue(pr, perm + head * NDEV, rows - head, cost ? cost + head : nullptr,
+                                   ghat ? ghat + head * 64 : nullptr, datap ? datap + head : nullptr, st);
+    }
     switch (group_size(pr, rows)) {
     case 32: launch_eval<32>(pr, perm, rows, cost, ghat, datap, st); break;
     case 8: launch_eval<8>(pr, perm, rows, cost, ghat, datap, st); break;
@@ -540,6 +557,13 @@ int dtfm_fast64_ls_gain4_enqueue(const dtfm_problem *pr, int32_t *perm, size_t r
                                  int64_t *applied, hipStream_t st)
 {
     if (rows == 0) return DTFM_OK;
+    const size_t head = full_rounds_rows(pr, rows);
+    if (head < rows) {
+        int rc = dtfm_fast64_ls_gain4_enqueue(pr, perm, head, moves, cost, applied, st);
+        if (rc != DTFM_OK) return rc;
+        return dtfm_fast64_ls_gain4_enqueue(pr, perm + head * NDEV, rows - head, moves, cost + head,
+                                            applied ? applied + head * (size_t)moves : nullptr, st);
+    }
     switch (group_size(pr, rows)) {
     case 32: launch_ls<32>(pr, perm, rows, moves, cost, applied, st); break;
     case 8: launch_ls<8>(pr, perm, rows, moves, cost, applied, st); break;

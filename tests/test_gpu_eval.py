@@ -73,12 +73,13 @@ def test_config2_population_eight_candidates_per_wavefront():
         assert np.array_equal(ghat[p], o.coarsen(perms[p])) and datap[p] == o.datap(perms[p])
 
 
-def test_config2_population_thirty_two_candidates_per_wavefront():
-    # 65536 candidates and more: 32 per wavefront pass (7 full matching passes, 4 Held-Karp passes);
-    # 65573 = 2049 groups of 32 with a ragged last group of 5
+@pytest.mark.parametrize("P", [65573, 114693])
+def test_config2_population_thirty_two_candidates_per_wavefront(P):
+    # 65536 candidates and more: 32 per wavefront pass (7 full matching passes, 4 Held-Karp passes).
+    # 65573: one full round of 65536 and a launch of its own for the other 37;
+    # 114693 = 3585 groups of 32 in one launch, with a ragged last group of 5
     w = workloads.config("C2")
     o, g = both(w)
-    P = 65573
     perms = workloads.random_population(P, 64, seed=13)
     dperm = dev(perms)
     c = host(dtfm.eval_population(g, dperm))

@@ -128,10 +128,17 @@ def test_gain4_config2():
     assert (applied >= 0).any()
 
 
-@pytest.mark.parametrize("P", [9001, 16500, 65573])
+@pytest.mark.parametrize("P", [1, 2, 3, 5, 7])
+def test_gain4_config2_ragged_small_populations(P):
+    # fewer candidates than one wavefront pass holds, more rounds than there are stage pairs
+    _ls_parity(workloads.config("C2"), workloads.random_population(P, 64, seed=20 + P), 31, dtfm.GAIN4)
+
+
+@pytest.mark.parametrize("P", [9001, 16500, 65573, 114693])
 def test_gain4_large_population_variants(P):
     # 9001, 16500: eight candidates per wavefront pass (workgroups of four and of eight wavefronts);
-    # 65573: thirty-two, with a ragged last group
+    # 65573: thirty-two for the first 65536, a launch of its own for the rest; 114693: thirty-two, with a
+    # ragged last group
     w = workloads.config("C2")
     o, g = both(w)
     perms = workloads.random_population(P, 64, seed=12)
