@@ -531,19 +531,21 @@ __global__ void k_make_offspring(uint32_t k0, uint32_t k1, uint32_t g, const int
         for (int blk = threadIdx.x; 2 * blk < steps; blk += blockDim.x) {
             const philox_out o = philox4x32_10((uint32_t)(t0 / 2 + blk), k, g, STREAM_CROSSOVER, k0, k1);
             for (int h = 0; h < 2; h++) {
-                draw_a[2 * blk + h] = (int32_t)randint(o.w[2 * h], (uint32_t)N);          // device
-                draw_b[2 * blk + h] = (int32_t)randint(o.w[2 * h + 1], (uint32_t)D_dp);   // slot
+                // the device, and the position it would go to: the drawn slot of the stage parent 2 keeps it in
+                // (parent 2 does not change, so this is known before the dependent steps)
+                const int d = (int)randint(o.w[2 * h], (uint32_t)N);
+                const int slot = (int)randint(o.w[2 * h + 1], (uint32_t)D_dp);
+                draw_a[2 * blk + h] = d;
+                draw_b[2 * blk + h] = stage_of[pos_par2[d]] * D_dp + slot;
             }
         }
         __syncthreads();
         if (threadIdx.x == 0) {
             for (int t = 0; t < steps; t++) {
-                const int d = draw_a[t], slot = draw_b[t];
+                const int d = draw_a[t], qb = draw_b[t];
                 const int qa = pos_child[d];
-                const int s1 = stage_of[qa], s2 = stage_of[pos_par2[d]];
-                if (s1 == s2) continue;
-                const int qb = s2 * D_dp + slot;
                 const int e = child[qb];
+                if (stage_of[qa] == stage_of[qb]) continue;
                 child[qa] = e;
                 child[qb] = d;
                 pos_child[e] = qa;
