@@ -317,3 +317,26 @@ def test_config5_full_size_generations():
     assert_costs_equal(cost[idx], o.eval_population(pop[idx]))
     rand = o.eval_population(workloads.random_population(3, 1024, seed=1))
     assert cost[0] < rand.min()
+
+
+def test_search_calls_are_ordered_on_a_side_stream():
+    # local_search, evolve and move_costs enqueue on the caller's current stream: work queued behind them
+    # on that stream sees their results, and the results equal those of the default stream
+    w = workloads.config("C2")
+    o, g = both(w)
+    perms = workloads.random_population(200, 64, seed=41)
+    ref = dev(perms)
+    ref_cost, _ = dtfm.local_search(g, ref, 5, dtfm.GAIN4)
+    ref_pop, ref_pc, ref_tr = dtfm.evolve(g, 9, 3, 64, ls_moves=2)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        d = dev(perms)
+        cost, _ = dtfm.local_search(g, d, 5, dtfm.GAIN4)
+        again = dtfm.eval_population(g, d)          # queued behind the search on the same stream
+        pop, pc, tr = dtfm.evolve(g, 9, 3, 64, ls_moves=2)
+        mc = dtfm.move_costs(g, d[:3].contiguous())
+    s.synchronize()
+    assert torch.equal(d, ref) and torch.equal(cost, ref_cost) and torch.equal(again, cost)
+    assert torch.equal(pop, ref_pop) and torch.equal(pc, ref_pc) and torch.equal(tr, ref_tr)
+    assert torch.equal(mc, dtfm.move_costs(g, ref[:3].contiguous()))
