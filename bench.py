@@ -249,6 +249,14 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    # the timed GA step against the same peak, counting every evaluation as a full one (a trial
+    # evaluation of the local search re-matches only 13 of the 28 stage pairs)
+    equiv = total_ops * evals / elapsed / 1e12
+    roofline["timed_step"] = {"kernel": "k_ls_gain4_fast64 (83 % of a generation)", "population": P,
+                              "full_evaluation_equivalent_Tops_per_s": equiv, "frac_of_peak": equiv / peak,
+                              "note": "4096 offspring give one wavefront of four candidates per SIMD: the "
+                                      "step is bound by that wavefront's instruction stream, not by the "
+                                      "chip's issue rate"}
     print(json.dumps(line))
 
 
