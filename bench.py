@@ -213,7 +213,7 @@ def main():
         import oracle
         opr = oracle.Problem(w.latency, w.bandwidth, w.c_dp, w.c_pp, w.D_dp, w.D_pp)
         threads = max(1, min(16, os.cpu_count() or 1))
-        sample = workloads.random_population(8 * P, N, seed=3)
+        sample = workloads.random_population(32 * P, N, seed=3)
         chunks = np.array_split(sample, threads * 4)
         c0 = time.perf_counter()
         with ThreadPoolExecutor(threads) as ex:
@@ -222,6 +222,21 @@ def main():
         cpu = {"value": sample.shape[0] / (c1 - c0), "unit": "candidates/s", "cores": threads, "kind": "oracle",
                "sample": "%d random C2 candidates, full cost evaluation each (oracle eval_population), "
                          "%d threads over contiguous chunks" % (sample.shape[0], threads)}
+        # the same on one core, and the oracle's evolutionary step (sequential C, one thread) on a
+        # population of 512: evaluations per second inside it, and what that makes per generation of
+        # the bench's size
+        c0 = time.perf_counter()
+        opr.eval_population(sample[:P])
+        c1 = time.perf_counter()
+        cpu["single_core_value"] = P / (c1 - c0)
+        Pg = 512
+        c0 = time.perf_counter()
+        opr.evolve(2, 1, Pg, ls_moves=ls_moves, neighbourhood=oracle.GAIN4)
+        c1 = time.perf_counter()
+        ga_evals = Pg + Pg * (1 + ls_moves)
+        cpu["ga_step"] = {"evaluations_per_s": ga_evals / (c1 - c0), "cores": 1,
+                          "generations_per_s_at_population_%d" % P: ga_evals / (c1 - c0) / (P * (1 + ls_moves)),
+                          "sample": "oracle evolve, 1 generation, population %d, %d GAIN4 rounds" % (Pg, ls_moves)}
         # the GPU result on the same rows must agree with what was just timed
         g = dtfm.eval_population(prob, torch.from_numpy(sample[:P]).cuda()).cpu().numpy()
         assert np.array_equal(g, np.concatenate(res)[:P]), "GPU and oracle disagree"
