@@ -110,6 +110,19 @@ def test_population_sizes_where_the_group_size_changes(P):
         assert np.array_equal(c[lo:lo + 1500], host(dtfm.eval_population(g, dperm[lo:lo + 1500].contiguous())))
 
 
+def test_config2_roofline_launch_size_sampled():
+    # the launch bench.py's roofline is taken on: 2^20 candidates (the 65,536 distinct rows repeated 16 times, as
+    # there); oracle costs on sampled rows, and every repeat of a row must give the same bits
+    w = workloads.config("C2")
+    o, g = both(w)
+    base = workloads.random_population(1 << 16, 64, seed=3)
+    dperm = dev(base).repeat(16, 1).contiguous()
+    c = host(dtfm.eval_population(g, dperm)).reshape(16, 1 << 16)
+    assert np.all(c == c[0])
+    idx = np.random.default_rng(5).choice(1 << 16, size=768, replace=False)
+    assert_costs_equal(c[7, idx], o.eval_population(base[idx]))
+
+
 def test_config4_full_population_sampled():
     w = workloads.config("C4")
     o, g = both(w)

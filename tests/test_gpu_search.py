@@ -304,6 +304,12 @@ def test_config3_full_size_twenty_rounds():
         assert_costs_equal(cost[p:p + 1], rc)
 
 
+def test_config2_bench_step_two_generations():
+    # the step bench.py times (population 4096, 4096 offspring, 8 GAIN4 rounds), two generations, against the
+    # oracle in full: populations, costs and trace bit for bit
+    _evolve_parity(workloads.config("C2"), 2, 2, 4096, ls_moves=8, neighbourhood=dtfm.GAIN4)
+
+
 def test_config5_full_size_generations():
     # the search of configuration 5 at its population (fewer generations than its 100): properties on
     # everything, oracle costs on sampled survivors
