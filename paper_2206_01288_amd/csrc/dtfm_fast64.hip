@@ -145,12 +145,14 @@ __device__ __forceinline__ void eval_group(const wave_ctx &cx, double *__restric
     double *res = reinterpret_cast<double *>(wl + off_res(NC));
     // ---- a4: matchings on ranks; the winning ranks of stage pair (a, b) of candidate c go to [c][index of (a, b)] ----
     const bool inc = INC && sj >= 0;
-    // 28 couples or fewer: two lanes per couple, each matching half of the rows
-    const bool halves = inc && NC * 7 <= 32;
+    // a pass with 32 couples or fewer (the only pass with 4 candidates, the last of four with 32):
+    // two lanes per couple, each matching half of the rows
+    constexpr bool HALVES = INC && (NC * 7) % 64 != 0 && (NC * 7) % 64 <= 32;
     const int per_cand = inc ? 7 : 14, items = NC * per_cand, mpasses = (items + 63) / 64;
 #pragma nounroll
     for (int pass = 0; pass < mpasses; pass++) {
-        int t = halves ? lane >> 1 : pass * 64 + lane;
+        const bool halves = HALVES && inc && items - pass * 64 <= 32;   // wave-uniform
+        int t = pass * 64 + (halves ? lane >> 1 : lane);
         const bool valid = t < items && !(halves && (lane & 1));
         if (t >= items) t = items - 1;   // idle lanes repeat the last item and write nothing
         const int mc = t / per_cand, q = t - per_cand * mc;
@@ -178,7 +180,7 @@ __device__ __forceinline__ void eval_group(const wave_ctx &cx, double *__restric
             }
         }
         uint32_t gfull;
-        if (INC && NC * 7 <= 32 && halves) gfull = match_couple_halves(cx, wl + OFF_PB + mc * 64, j1, j2);
+        if (HALVES && halves) gfull = match_couple_halves(cx, wl + OFF_PB + mc * 64, j1, j2);
         else gfull = match_couple(cx, wl + OFF_PB + mc * 64, j1, j2);
         if (valid) {
             ghr16[mc * 28 + pair_index(j1[0], j2[0])] = (uint16_t)gfull;
