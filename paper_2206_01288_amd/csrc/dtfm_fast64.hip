@@ -70,8 +70,9 @@ __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16
     cx.Wdp = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES + LDS_RVAL_BYTES);
     cx.Wpp = wpp_in_lds(NC, LS) ? reinterpret_cast<const double *>(smem + LDS_TABLES) : W_pp;
     cx.wl = smem + LDS_TABLES + (wpp_in_lds(NC, LS) ? LDS_WDP_BYTES : 0) + wave * wave_lds_bytes(NC, LS);
-    stage_tables(smem, rank_tab, rank_val, W_dp);
-    if (wpp_in_lds(NC, LS))
+    stage_tables<(NC < 32)>(smem, rank_tab, rank_val, W_dp);
+    if (wpp_in_lds(NC, LS))   // NC < 32
+#pragma unroll 8
         for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x)
             reinterpret_cast<double2 *>(smem + LDS_TABLES)[i] = reinterpret_cast<const double2 *>(W_pp)[i];
     cx.hv = cx.lane & 7;

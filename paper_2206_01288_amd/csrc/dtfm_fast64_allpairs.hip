@@ -81,7 +81,7 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
                      double *__restrict__ cost, int64_t *__restrict__ applied, double *__restrict__ move_cost)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    stage_tables(smem, rank_tab, rank_val_g, W_dp);
+    stage_tables<false>(smem, rank_tab, rank_val_g, W_dp);
     __syncthreads();
     const uint16_t *R = reinterpret_cast<const uint16_t *>(smem);
     const double *rank_val = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES);

@@ -411,17 +411,33 @@ __device__ __forceinline__ void match_rows(const uint16_t *R, const uint2 (&rowd
 }
 
 // Copies the rank table (rows re-strided), the rank values and W_dp into the workgroup's LDS; the
-// caller ends the set-up with a workgroup barrier.
+// caller ends the set-up with a workgroup barrier. EAGER unrolls the copy loops so that a thread's
+// loads are all in flight before its first LDS write waits for one: worth 0.5 us of a launch's 3 us
+// set-up where that matters (small populations); the long-running kernels keep the plain loops.
+template <bool EAGER>
 __device__ __forceinline__ void stage_tables(unsigned char *smem, const uint16_t *rank_tab, const double *rank_val,
                                              const double *W_dp)
 {
-    for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
-        const int row = i / (NDEV / 2), col2 = i - row * (NDEV / 2);
-        reinterpret_cast<uint32_t *>(smem)[row * (RSTRIDE / 2) + col2] = reinterpret_cast<const uint32_t *>(rank_tab)[i];
-    }
-    for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
-        reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES)[i] = reinterpret_cast<const double2 *>(rank_val)[i];
-        reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES + LDS_RVAL_BYTES)[i] = reinterpret_cast<const double2 *>(W_dp)[i];
+    if (EAGER) {
+#pragma unroll 8
+        for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
+            const int row = i / (NDEV / 2), col2 = i - row * (NDEV / 2);
+            reinterpret_cast<uint32_t *>(smem)[row * (RSTRIDE / 2) + col2] = reinterpret_cast<const uint32_t *>(rank_tab)[i];
+        }
+#pragma unroll 8
+        for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
+            reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES)[i] = reinterpret_cast<const double2 *>(rank_val)[i];
+            reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES + LDS_RVAL_BYTES)[i] = reinterpret_cast<const double2 *>(W_dp)[i];
+        }
+    } else {
+        for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
+            const int row = i / (NDEV / 2), col2 = i - row * (NDEV / 2);
+            reinterpret_cast<uint32_t *>(smem)[row * (RSTRIDE / 2) + col2] = reinterpret_cast<const uint32_t *>(rank_tab)[i];
+        }
+        for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
+            reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES)[i] = reinterpret_cast<const double2 *>(rank_val)[i];
+            reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES + LDS_RVAL_BYTES)[i] = reinterpret_cast<const double2 *>(W_dp)[i];
+        }
     }
 }
 
