@@ -25,6 +25,7 @@
 //                      devices summed in slot order (the device's own slot adds the zero diagonal),
 //                      max over the stage, then over the 8 lanes of the candidate.
 #include "dtfm_fast64_device.h"
+#include "dtfm_philox.h"
 
 namespace {
 
@@ -39,7 +40,12 @@ constexpr int off_curc(int nc) { return off_res(nc) + 2 * nc * 8; }            /
 constexpr int off_pbcur(int nc) { return off_curc(nc) + nc * 8; }              // u8 [NC][64]: current rows (local search)
 constexpr int off_prop(int nc) { return off_pbcur(nc) + nc * 64; }             // u8 [NC][2]: proposed positions (local search)
 constexpr int off_ghrcur(int nc) { return (off_prop(nc) + nc * 2 + 3) / 4 * 4; }   // u16 [NC][28]: coarsened graphs of the current rows
-constexpr int wave_lds_bytes(int nc, bool ls) { return ((ls ? off_ghrcur(nc) + nc * 28 * 2 : off_curc(nc)) + 15) / 16 * 16; }
+// with 4 candidates the local-search kernel can make its rows itself (offspring of the evolutionary search):
+// u8 [4][64] position of each device in the child, u8 [4][64] the same in parent 2, u8 [2][4][32] draws
+constexpr int MK_STEPS = 32;                                                    // crossover / mutation steps drawn at a time
+constexpr int off_mk(int nc) { return (off_ghrcur(nc) + nc * 28 * 2 + 3) / 4 * 4; }
+constexpr int mk_bytes(int nc) { return nc == 4 ? 2 * nc * 64 + 2 * nc * MK_STEPS : 0; }
+constexpr int wave_lds_bytes(int nc, bool ls) { return ((ls ? off_mk(nc) + mk_bytes(nc) : off_curc(nc)) + 15) / 16 * 16; }
 // the local-search kernels also keep W_pp in LDS (for the proposals), except with 32 candidates per
 // wavefront, where the slices need the room and two wavefronts per SIMD hide the latency of L2
 constexpr bool wpp_in_lds(int nc, bool ls) { return ls && nc < 32; }
@@ -332,14 +338,123 @@ __device__ __forceinline__ void propose_gain4(const wave_ctx &cx, const unsigned
 // each of the round's two stages, the four end-point swaps ranked by the paper's Gain), evaluate the
 // swapped allocation with eval_group, keep it iff strictly cheaper. The fastest link is found on the
 // ranks (same order and same ties as the weights); the Gain sums use the fp64 weights in slot order.
-template <int NC>
+// Sec. 3.4 selection, crossover and mutation for the four offspring cand0 .. cand0 + 3 of a wavefront (16
+// lanes each), the rows left as bytes at `rows` (4 x 64, stage-major). Same draws and steps as
+// k_make_offspring: two uniform parents; the child starts as parent 1; m_x times a random device that parent
+// 2 keeps in another stage is swapped with the device at a random slot of that stage; m_m random
+// transpositions. The draws of MK_STEPS steps are made by the 16 lanes (two steps per Philox block), the
+// dependent swaps by the first lane of each candidate.
+// The lane's share of the two parents' rows (positions sub, sub + 16, sub + 32, sub + 48 of the lane's
+// candidate): loaded ahead of the table set-up, which hides the selection draw and the loads.
+struct parent_rows {
+    int d1[4], d2[4];
+};
+__device__ __forceinline__ parent_rows load_parents4(const dtfm_offspring_src &src, size_t cand0, size_t L, int lane)
+{
+    size_t kk = cand0 + (lane >> 4);
+    if (kk >= L) kk = L - 1;
+    const philox_out sel = philox4x32_10(0u, (uint32_t)kk, src.g, STREAM_SELECT, src.k0, src.k1);
+    const int32_t *par1 = src.pop + (size_t)randint(sel.w[0], (uint32_t)src.P) * NDEV;
+    const int32_t *par2 = src.pop + (size_t)randint(sel.w[1], (uint32_t)src.P) * NDEV;
+    parent_rows r;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        r.d1[i] = par1[(lane & 15) + 16 * i];
+        r.d2[i] = par2[(lane & 15) + 16 * i];
+    }
+    return r;
+}
+
+__device__ __forceinline__ void make_offspring4(const wave_ctx &cx, const dtfm_offspring_src &src, const parent_rows &par,
+                                                size_t cand0, size_t L, unsigned char *rows, unsigned char *scratch)
+{
+    const int lane = cx.lane, c = lane >> 4, sub = lane & 15;
+    size_t kk = cand0 + c;
+    if (kk >= L) kk = L - 1;   // ragged tail: the last offspring again, never stored
+    const uint32_t k = (uint32_t)kk;
+    unsigned char *child = rows + c * 64, *pos_child = scratch + c * 64, *pos_par2 = scratch + 4 * 64 + c * 64;
+    unsigned char *draw_a = scratch + 8 * 64 + c * MK_STEPS, *draw_b = draw_a + 4 * MK_STEPS;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int q = sub + 16 * i;
+        const int d = par.d1[i];
+        child[q] = (unsigned char)d;
+        pos_child[d] = (unsigned char)q;
+        pos_par2[par.d2[i]] = (unsigned char)q;
+    }
+    WAVE_LDS_SYNC();
+    for (int t0 = 0; t0 < src.m_x; t0 += MK_STEPS) {
+        const int steps = min(MK_STEPS, src.m_x - t0);
+        if (2 * sub < steps) {
+            const philox_out o = philox4x32_10((uint32_t)(t0 / 2 + sub), k, src.g, STREAM_CROSSOVER, src.k0, src.k1);
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const int d = (int)randint(o.w[2 * h], (uint32_t)NDEV);
+                const int slot = (int)randint(o.w[2 * h + 1], 8u);
+                draw_a[2 * sub + h] = (unsigned char)d;
+                draw_b[2 * sub + h] = (unsigned char)((pos_par2[d] & ~7) + slot);   // the slot of the stage parent 2 keeps d in
+            }
+        }
+        WAVE_LDS_SYNC();
+        if (sub == 0) {
+            // all draws of the chunk into registers first: a step then waits for one LDS round trip only
+            uint32_t da[MK_STEPS / 4], db[MK_STEPS / 4];
+#pragma unroll
+            for (int w = 0; w < MK_STEPS / 4; w++) {
+                da[w] = reinterpret_cast<const uint32_t *>(draw_a)[w];
+                db[w] = reinterpret_cast<const uint32_t *>(draw_b)[w];
+            }
+#pragma unroll
+            for (int t = 0; t < MK_STEPS; t++) {
+                if (t < steps) {
+                    const int d = (da[t >> 2] >> (8 * (t & 3))) & 0xFF, qb = (db[t >> 2] >> (8 * (t & 3))) & 0xFF;
+                    const int qa = pos_child[d];
+                    const int e = child[qb];
+                    if ((qa >> 3) != (qb >> 3)) {
+                        child[qa] = (unsigned char)e;
+                        child[qb] = (unsigned char)d;
+                        pos_child[e] = (unsigned char)qa;
+                        pos_child[d] = (unsigned char)qb;
+                    }
+                }
+            }
+        }
+        WAVE_LDS_SYNC();
+    }
+    for (int t0 = 0; t0 < src.m_m; t0 += MK_STEPS) {
+        const int steps = min(MK_STEPS, src.m_m - t0);
+        if (2 * sub < steps) {
+            const philox_out o = philox4x32_10((uint32_t)(t0 / 2 + sub), k, src.g, STREAM_MUTATION, src.k0, src.k1);
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                draw_a[2 * sub + h] = (unsigned char)randint(o.w[2 * h], (uint32_t)NDEV);
+                draw_b[2 * sub + h] = (unsigned char)randint(o.w[2 * h + 1], (uint32_t)NDEV);
+            }
+        }
+        WAVE_LDS_SYNC();
+        if (sub == 0) {
+            for (int t = 0; t < steps; t++) {
+                const int a = draw_a[t], b = draw_b[t];
+                const unsigned char x = child[a];
+                child[a] = child[b];
+                child[b] = x;
+            }
+        }
+        WAVE_LDS_SYNC();
+    }
+}
+
+template <int NC, bool MAKE>
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
 k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_pp,
                   const uint16_t *__restrict__ rank_tab, const double *__restrict__ rank_val,
                   int32_t *__restrict__ perm, size_t P, int moves, double *__restrict__ cost,
-                  int64_t *__restrict__ applied)
+                  int64_t *__restrict__ applied, dtfm_offspring_src src)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    parent_rows par = {};
+    if (MAKE && NC == 4)   // the first group's parents, in flight during the table set-up
+        par = load_parents4(src, ((size_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * NC, P, threadIdx.x & 63);
     const wave_ctx cx = wave_setup<NC, true>(smem, rank_tab, rank_val, W_dp, W_pp);
     const int lane = cx.lane, wave = threadIdx.x >> 6;
     unsigned char *wl = cx.wl;
@@ -351,13 +466,20 @@ k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_
     const size_t nwaves = (size_t)gridDim.x * wpb;
     const size_t ngroups = (P + NC - 1) / NC;
     for (size_t grp = (size_t)blockIdx.x * wpb + wave; grp < ngroups; grp += nwaves) {
+        if (MAKE && NC == 4) {
+            if (grp >= nwaves) par = load_parents4(src, grp * NC, P, lane);   // later groups of a wavefront
+            make_offspring4(cx, src, par, grp * NC, P, wl + OFF_PB, wl + off_mk(NC));
+#pragma unroll
+            for (int c = 0; c < NC; c++) pbcur[c * 64 + lane] = wl[OFF_PB + c * 64 + lane];
+        } else {
 #pragma unroll 8
-        for (int c = 0; c < NC; c++) {
-            size_t cand = grp * NC + c;
-            if (cand >= P) cand = P - 1;
-            const unsigned char d = (unsigned char)perm[cand * NDEV + lane];
-            wl[OFF_PB + c * 64 + lane] = d;
-            pbcur[c * 64 + lane] = d;
+            for (int c = 0; c < NC; c++) {
+                size_t cand = grp * NC + c;
+                if (cand >= P) cand = P - 1;
+                const unsigned char d = (unsigned char)perm[cand * NDEV + lane];
+                wl[OFF_PB + c * 64 + lane] = d;
+                pbcur[c * 64 + lane] = d;
+            }
         }
         WAVE_LDS_SYNC();
         // round -1 prices the rows as they are; each later round prices the rows with the proposed swap
@@ -459,11 +581,13 @@ int dtfm_fast64_prepare(dtfm_problem *pr)
                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(8, false)));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64<4>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(4, false)));
-    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<32>),
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<32, false>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(32, true)));
-    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<8>),
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<8, false>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(8, true)));
-    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<4>),
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<4, false>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(4, true)));
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<4, true>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(4, true)));
     int rc = dtfm_fast64_allpairs_prepare();
     if (rc != DTFM_OK) return rc;
@@ -552,8 +676,29 @@ static void launch_ls(const dtfm_problem *pr, int32_t *perm, size_t rows, int mo
     const int wpb = waves_per_block(pr, passes);
     size_t blocks = (passes + wpb - 1) / wpb;
     if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
-    hipLaunchKernelGGL(k_ls_gain4_fast64<NC>, dim3((unsigned)blocks), dim3(wpb * 64), lds_total(NC, true, wpb), st,
-                       pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied);
+    hipLaunchKernelGGL((k_ls_gain4_fast64<NC, false>), dim3((unsigned)blocks), dim3(wpb * 64), lds_total(NC, true, wpb), st,
+                       pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, applied,
+                       dtfm_offspring_src{});
+}
+
+bool dtfm_fast64_ls_makes_offspring(const dtfm_problem *pr, size_t rows, int moves)
+{
+    return rows > 0 && moves >= 0 && full_rounds_rows(pr, rows) == rows && group_size(pr, rows) == 4;
+}
+
+int dtfm_fast64_offspring_ls_gain4_enqueue(const dtfm_problem *pr, const dtfm_offspring_src &src, int32_t *perm,
+                                           size_t rows, int moves, double *cost, hipStream_t st)
+{
+    if (!dtfm_fast64_ls_makes_offspring(pr, rows, moves)) return DTFM_ERR_ARG;
+    size_t passes = (rows + 3) / 4;
+    const int wpb = waves_per_block(pr, passes);
+    size_t blocks = (passes + wpb - 1) / wpb;
+    if (blocks > (size_t)pr->f64_grid) blocks = pr->f64_grid;
+    hipLaunchKernelGGL((k_ls_gain4_fast64<4, true>), dim3((unsigned)blocks), dim3(wpb * 64), lds_total(4, true, wpb), st,
+                       pr->W_dp, pr->W_pp, pr->f64_rank, pr->f64_rank_val, perm, rows, moves, cost, (int64_t *)nullptr,
+                       src);
+    DTFM_HIP(hipGetLastError());
+    return DTFM_OK;
 }
 
 int dtfm_fast64_ls_gain4_enqueue(const dtfm_problem *pr, int32_t *perm, size_t rows, int moves, double *cost,

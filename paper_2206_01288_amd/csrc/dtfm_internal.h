@@ -111,6 +111,20 @@ int dtfm_fast64_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows
 int dtfm_fast64_ls_gain4_enqueue(const dtfm_problem *pr, int32_t *perm, size_t rows, int moves, double *cost,
                                  int64_t *applied, hipStream_t st);
 
+// What the evolutionary search needs to make offspring k of generation g (Sec. 3.4: selection, crossover,
+// mutation): the Philox key, the generation-start population (rows of N) and the operator counts.
+struct dtfm_offspring_src {
+    uint32_t k0, k1, g;
+    const int32_t *pop;
+    int P, m_x, m_m;
+};
+// True when the GAIN4 launch for `rows` offspring can make them itself (small populations, where a launch of
+// its own for that step costs as much as a tenth of the generation).
+bool dtfm_fast64_ls_makes_offspring(const dtfm_problem *pr, size_t rows, int moves);
+// As dtfm_fast64_ls_gain4_enqueue, the rows made in the kernel from `src` instead of read: perm is only written.
+int dtfm_fast64_offspring_ls_gain4_enqueue(const dtfm_problem *pr, const dtfm_offspring_src &src, int32_t *perm,
+                                           size_t rows, int moves, double *cost, hipStream_t st);
+
 // all `moves` >= 1 rounds of the ALL_PAIRS local search with incremental move evaluation in one launch
 // (dtfm_fast64_allpairs.hip); perm in/out, cost out, applied may be null
 int dtfm_fast64_allpairs_prepare();

@@ -3,6 +3,7 @@
 // replacement), general shapes. Every cost they compare is the full cost of Eq. 1 as produced by
 // the evaluation kernels, so a move's cost is bit-identical to evaluating the swapped allocation.
 #include "dtfm_internal.h"
+#include "dtfm_philox.h"
 
 #include <math.h>
 
@@ -421,39 +422,6 @@ int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm
 }
 
 // ------------------------------------------------------------------------------------------------
-// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds; each round multiplies counter
-// words 0 and 2 by the two round multipliers, mixes the high halves with words 1, 3 and the key,
-// and the key advances by the two Weyl increments.
-struct philox_out {
-    uint32_t w[4];
-};
-
-__device__ __forceinline__ philox_out philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                                    uint32_t k0, uint32_t k1)
-{
-#pragma unroll
-    for (int i = 0; i < 10; i++) {
-        uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-        c0 = hi1 ^ c1 ^ k0;
-        c1 = lo1;
-        c2 = hi0 ^ c3 ^ k1;
-        c3 = lo0;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    philox_out o;
-    o.w[0] = c0;
-    o.w[1] = c1;
-    o.w[2] = c2;
-    o.w[3] = c3;
-    return o;
-}
-
-enum { STREAM_INIT = 0, STREAM_SELECT = 1, STREAM_CROSSOVER = 2, STREAM_MUTATION = 3 };
-
-__device__ __forceinline__ uint32_t randint(uint32_t x, uint32_t n) { return __umulhi(x, n); }
-
 __global__ void k_philox_blocks(uint32_t k0, uint32_t k1, uint32_t stream, uint32_t g, uint32_t k,
                                 uint32_t first_block, int n_blocks, uint32_t *__restrict__ out)
 {
@@ -715,11 +683,18 @@ int dtfm_ga_enqueue(const dtfm_problem *pr, const dtfm_ga_bufs &b, uint64_t seed
     int32_t *pop_cur = population, *pop_next = b.next;
     double *cost_cur = cost, *cost_next = b.next_cost;
     for (int g = 0; g < generations; g++) {
-        hipLaunchKernelGGL(k_make_offspring, dim3(L), dim3(DTFM_WAVE), (4 * N + 2 * DTFM_DRAW_CHUNK) * sizeof(int32_t), st, k0, k1,
-                           (uint32_t)g, pop_cur, P, N, pr->D_dp, prm.m_x, prm.m_m, b.off);
-        DTFM_HIP(hipGetLastError());
-        rc = dtfm_ls_enqueue(pr, b.ls, b.off, L, prm.ls_moves, prm.neighbourhood, b.off_cost, nullptr, st);
-        if (rc != DTFM_OK) return rc;
+        if (pr->fast64 && prm.neighbourhood == DTFM_GAIN4 && dtfm_fast64_ls_makes_offspring(pr, L, prm.ls_moves)) {
+            // one launch makes the offspring and carries them through the local search
+            const dtfm_offspring_src src = {k0, k1, (uint32_t)g, pop_cur, P, prm.m_x, prm.m_m};
+            rc = dtfm_fast64_offspring_ls_gain4_enqueue(pr, src, b.off, L, prm.ls_moves, b.off_cost, st);
+            if (rc != DTFM_OK) return rc;
+        } else {
+            hipLaunchKernelGGL(k_make_offspring, dim3(L), dim3(DTFM_WAVE), (4 * N + 2 * DTFM_DRAW_CHUNK) * sizeof(int32_t), st,
+                               k0, k1, (uint32_t)g, pop_cur, P, N, pr->D_dp, prm.m_x, prm.m_m, b.off);
+            DTFM_HIP(hipGetLastError());
+            rc = dtfm_ls_enqueue(pr, b.ls, b.off, L, prm.ls_moves, prm.neighbourhood, b.off_cost, nullptr, st);
+            if (rc != DTFM_OK) return rc;
+        }
         hipLaunchKernelGGL(k_rank_count, dim3((nk + 255) / 256, (nk + DTFM_RANK_CHUNK - 1) / DTFM_RANK_CHUNK), dim3(256), 0,
                            st, cost_cur, b.off_cost, P, L, g > 0 ? 1 : 0, b.rank);
         DTFM_HIP(hipGetLastError());
