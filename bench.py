@@ -156,6 +156,9 @@ def main():
 
     # ---- the timed steps: K generations of the evolutionary search ---------------------------
     pop = pop0.clone()
+    # an idle part needs some tens of milliseconds of work to reach its clocks: spin it up (untimed,
+    # on a copy) before the W warm-up steps, so that a small W does not time the ramp
+    dtfm.evolve(prob, seed=3, generations=400, P=P, ls_moves=ls_moves, neighbourhood=nb, population=pop0.clone())
     if args.warmup > 0:
         pop, _, _ = dtfm.evolve(prob, seed=1, generations=args.warmup, P=P, ls_moves=ls_moves,
                                 neighbourhood=nb, population=pop)
