@@ -83,8 +83,8 @@ def main():
                          "rocprofv3 runs of the incremental move-evaluation kernel)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (candidates are independent; see DESIGN.md "
-              "for how the path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (candidates are independent and would shard "
+              "without exchange; no multi-GPU path is built); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
