@@ -579,13 +579,13 @@ __device__ __forceinline__ int count_before(const double *__restrict__ key, int 
 // the previous replacement placed them by rank): parent i has i parents before it, an offspring as
 // many as have a cost <= its own (binary search), and only the offspring keys are counted.
 __global__ void k_rank_count(const double *__restrict__ cost, const double *__restrict__ off_cost, int P, int L,
-                             int parents_sorted, int32_t *__restrict__ rank)
+                             int parents_sorted, int chunk, int32_t *__restrict__ rank)
 {
     const int n = P + L;
-    const int j0 = blockIdx.y * DTFM_RANK_CHUNK;
+    const int j0 = blockIdx.y * chunk;
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    const int j1 = j0 + DTFM_RANK_CHUNK < n ? j0 + DTFM_RANK_CHUNK : n;
+    const int j1 = j0 + chunk < n ? j0 + chunk : n;
     if (parents_sorted && blockIdx.y != 0 && j1 <= P) return;
     const double ci = i < P ? cost[i] : off_cost[i - P];
     // the chunk's keys: [ja, jb) among the parents, [jc, jd) among the offspring
@@ -695,8 +695,10 @@ int dtfm_ga_enqueue(const dtfm_problem *pr, const dtfm_ga_bufs &b, uint64_t seed
             rc = dtfm_ls_enqueue(pr, b.ls, b.off, L, prm.ls_moves, prm.neighbourhood, b.off_cost, nullptr, st);
             if (rc != DTFM_OK) return rc;
         }
-        hipLaunchKernelGGL(k_rank_count, dim3((nk + 255) / 256, (nk + DTFM_RANK_CHUNK - 1) / DTFM_RANK_CHUNK), dim3(256), 0,
-                           st, cost_cur, b.off_cost, P, L, g > 0 ? 1 : 0, b.rank);
+        int chunk = DTFM_RANK_CHUNK;   // longer chunks when the grid's second dimension would not hold the short ones
+        while ((nk + chunk - 1) / chunk > 65535) chunk *= 2;
+        hipLaunchKernelGGL(k_rank_count, dim3((nk + 255) / 256, (nk + chunk - 1) / chunk), dim3(256), 0,
+                           st, cost_cur, b.off_cost, P, L, g > 0 ? 1 : 0, chunk, b.rank);
         DTFM_HIP(hipGetLastError());
         hipLaunchKernelGGL(k_rank_place, dim3(nk), dim3(DTFM_WAVE), 0, st, pop_cur, b.off, cost_cur, b.off_cost, P, L, N,
                            b.rank, pop_next, cost_next, best_trace + g);
