@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--general-shapes", action="store_true",
                     help="only population evaluations at configurations C4 and C5 (for rocprofv3 runs of the "
                          "general-shape kernels)")
+    ap.add_argument("--ls-throughput", action="store_true",
+                    help="only the GAIN4 local search, 8 rounds on 2^20 candidates (for rocprofv3 runs of the fused "
+                         "local-search kernel at a chip-filling population)")
     ap.add_argument("--all-pairs", action="store_true",
                     help="only configuration 3: 20 rounds of the ALL_PAIRS local search on 4096 candidates (for "
                          "rocprofv3 runs of the incremental move-evaluation kernel)")
@@ -111,6 +114,26 @@ def main():
             res[name] = {"population": Pg, "ms_per_eval_population": (time.perf_counter() - t0) / 3 * 1e3}
             dtfm.destroy_problem(pg)
         print(json.dumps({"general_shapes": res}))
+        return
+
+    if args.ls_throughput:
+        # the GAIN4 local search at a chip-filling population: 8 rounds on 2^20 candidates (for rocprofv3 runs of
+        # k_ls_gain4_fast64<32>)
+        w2 = workloads.config("C2")
+        p2 = dtfm.create_problem(w2.latency, w2.bandwidth, w2.c_dp, w2.c_pp, w2.D_dp, w2.D_pp)
+        base = torch.from_numpy(workloads.random_population(1 << 16, w2.N, seed=3)).cuda().repeat(16, 1).contiguous()
+        rounds = 8
+        d = base.clone()
+        for _ in range(5):
+            dtfm.local_search(p2, d, rounds, dtfm.GAIN4)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            dtfm.local_search(p2, d, rounds, dtfm.GAIN4)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / 10 * 1e3
+        print(json.dumps({"ls_throughput": {"candidates": int(base.shape[0]), "rounds": rounds, "ms": ms,
+                                            "trial_evaluations_per_s": base.shape[0] * (rounds + 1) / (ms * 1e-3)}}))
         return
 
     if args.all_pairs:
