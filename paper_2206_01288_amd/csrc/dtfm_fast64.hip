@@ -47,7 +47,7 @@ constexpr int off_mk(int nc) { return (off_ghrcur(nc) + nc * 28 * 2 + 3) / 4 * 4
 constexpr int mk_bytes(int nc) { return nc == 4 ? 2 * nc * 64 + 2 * nc * MK_STEPS : 0; }
 constexpr int wave_lds_bytes(int nc, bool ls) { return ((ls ? off_mk(nc) + mk_bytes(nc) : off_curc(nc)) + 15) / 16 * 16; }
 // the local-search kernels also keep W_pp in LDS (for the proposals), except with 32 candidates per
-// wavefront, where the slices need the room and two wavefronts per SIMD hide the latency of L2
+// wavefront, where the slices need the room and the proposals go through the rank tables instead
 constexpr bool wpp_in_lds(int nc, bool ls) { return ls && nc < 32; }
 constexpr int lds_total(int nc, bool ls, int waves = WAVES_PER_BLOCK) { return LDS_TABLES + (wpp_in_lds(nc, ls) ? LDS_WDP_BYTES : 0) + waves * wave_lds_bytes(nc, ls); }
 static_assert(lds_total(MAXC, true) <= 160 * 1024, "LDS budget of a CU");
@@ -58,7 +58,7 @@ struct wave_ctx {
     const uint16_t *R;       // rank table (LDS)
     const double *rank_val;  // rank -> weight (LDS)
     const double *Wdp;       // W_dp (LDS)
-    const double *Wpp;       // W_pp (local-search kernels only; LDS copy or the global table)
+    const double *Wpp;       // W_pp (local-search kernels with fewer than 32 candidates per wavefront: LDS copy)
     int lane;
     int hv;                  // Held-Karp / DataP role: stage; the candidate slot is 8 * pass + lane / 8
 };
@@ -74,7 +74,7 @@ __device__ __forceinline__ wave_ctx wave_setup(unsigned char *smem, const uint16
     cx.R = reinterpret_cast<const uint16_t *>(smem);
     cx.rank_val = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES);
     cx.Wdp = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES + LDS_RVAL_BYTES);
-    cx.Wpp = wpp_in_lds(NC, LS) ? reinterpret_cast<const double *>(smem + LDS_TABLES) : W_pp;
+    cx.Wpp = wpp_in_lds(NC, LS) ? reinterpret_cast<const double *>(smem + LDS_TABLES) : nullptr;
     cx.wl = smem + LDS_TABLES + (wpp_in_lds(NC, LS) ? LDS_WDP_BYTES : 0) + wave * wave_lds_bytes(NC, LS);
     stage_tables<(NC < 32)>(smem, rank_tab, rank_val, W_dp);
     if (wpp_in_lds(NC, LS))   // NC < 32
@@ -264,6 +264,15 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
     }
 }
 
+// W_pp[a][b], a != b, for the proposals: from the LDS copy where there is one; with 32 candidates per
+// wavefront (no room for it) through the rank tables, rank_val[rank[a][b]] being the same bits.
+template <int NC>
+__device__ __forceinline__ double wpp(const wave_ctx &cx, uint32_t a, uint32_t b)
+{
+    if (wpp_in_lds(NC, true)) return cx.Wpp[a * NDEV + b];
+    return cx.rank_val[cx.R[a * RSTRIDE + b]];
+}
+
 // The round's proposal for every candidate slot (Sec. 3.4, "Improving Local Search Strategy"): the fastest
 // link inside stage j and inside stage jp of the current row, and of the four swaps of their end points
 // the one of largest Gain; its two positions (first < second) go to prop[2 c], prop[2 c + 1].
@@ -306,11 +315,11 @@ __device__ __forceinline__ void propose_gain4(const wave_ctx &cx, const unsigned
             const uint2 other = cdev[side ^ 1];
             double sum = 0.0;
 #pragma unroll
-            for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, cx.Wpp[dv * NDEV + byte_of(other, i)]);
+            for (int i = 0; i < 8; i++) sum = __dadd_rn(sum, wpp<NC>(cx, dv, byte_of(other, i)));
             mean = sum * 0.125;   // the mean over 8 entries; exact scaling, the same bits as the division
         }
-        const double link0 = cx.Wpp[byte_at(cdev[0], slot[0][0]) * NDEV + byte_at(cdev[0], slot[0][1])];
-        const double link1 = cx.Wpp[byte_at(cdev[1], slot[1][0]) * NDEV + byte_at(cdev[1], slot[1][1])];
+        const double link0 = wpp<NC>(cx, byte_at(cdev[0], slot[0][0]), byte_at(cdev[0], slot[0][1]));
+        const double link1 = wpp<NC>(cx, byte_at(cdev[1], slot[1][0]), byte_at(cdev[1], slot[1][1]));
         const double mx[2] = {dpp_move<0x00>(mean), dpp_move<0x55>(mean)};   // lane 0 / lane 1 of the quad
         const double my[2] = {dpp_move<0xAA>(mean), dpp_move<0xFF>(mean)};   // lane 2 / lane 3
         double bestg = 0.0;
