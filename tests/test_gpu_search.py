@@ -346,3 +346,38 @@ def test_search_calls_are_ordered_on_a_side_stream():
     assert torch.equal(d, ref) and torch.equal(cost, ref_cost) and torch.equal(again, cost)
     assert torch.equal(pop, ref_pop) and torch.equal(pc, ref_pc) and torch.equal(tr, ref_tr)
     assert torch.equal(mc, dtfm.move_costs(g, ref[:3].contiguous()))
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_every_call(seed):
+    # a seeded sweep over shapes the other tests do not name: every call of the library against the oracle on the
+    # same small inputs (evaluation, the three neighbourhoods, move costs, the evolutionary loop)
+    rng = np.random.default_rng(1000 + seed)
+    D_dp = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 13, 16, 17, 24, 33]))
+    D_pp = int(rng.integers(1, 13)) if D_dp <= 16 else int(rng.integers(1, 5))
+    N = D_dp * D_pp
+    P = int(rng.integers(1, 30))
+    w = custom(N, D_dp, D_pp, seed=2000 + seed)
+    o, g = both(w)
+    perms = workloads.random_population(P, N, seed=seed)
+    assert_costs_equal(host(dtfm.eval_population(g, dev(perms))), o.eval_population(perms))
+    if D_dp >= 2 and D_pp >= 2:
+        _ls_parity(w, perms, 4, dtfm.GAIN4)
+        _ls_parity(w, perms, 3, dtfm.KL)
+    if 2 <= N <= 40:
+        _ls_parity(w, perms, 2, dtfm.ALL_PAIRS)
+        M = N * (N - 1) // 2
+        mc = host(dtfm.move_costs(g, dev(perms[:2]))).reshape(-1, M)
+        for p in range(mc.shape[0]):
+            m = 0
+            for a in range(N):
+                for b in range(a + 1, N):
+                    if (a * 7 + b + seed) % 5 == 0:      # a fifth of the moves
+                        q = perms[p].copy()
+                        q[a], q[b] = q[b], q[a]
+                        assert mc[p, m] == o.eval_population(q[None])[0]
+                    m += 1
+    if N >= 2:
+        nb = dtfm.GAIN4 if (D_dp >= 2 and D_pp >= 2) else dtfm.ALL_PAIRS
+        _evolve_parity(w, seed, 2, max(2, P // 3), lam=int(rng.integers(1, 9)), ls_moves=1 if N <= 40 or nb == dtfm.GAIN4 else 0,
+                       neighbourhood=nb)
