@@ -354,7 +354,9 @@ __device__ const unsigned char dtfm_binom10[11][11] = {
     {1, 6, 15, 20, 15, 6, 1, 0, 0, 0, 0}, {1, 7, 21, 35, 35, 21, 7, 1, 0, 0, 0}, {1, 8, 28, 56, 70, 56, 28, 8, 1, 0, 0},
     {1, 9, 36, 84, 126, 126, 84, 36, 9, 1, 0}, {1, 10, 45, 120, 210, 252, 210, 120, 45, 10, 1}};
 
-template <int NL>  // low stages per block; the workgroup has 2^NL threads
+// NL: low stages per block (the workgroup has 2^NL threads); NPAIR: pairs of row slots that can hold a stage
+// (ceil(D_pp / 2): the slots beyond D_pp are +inf in every row and are not read)
+template <int NL, int NPAIR>
 __global__ void __launch_bounds__(1 << NL)
 k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ datap, int n,
                     double *__restrict__ xchg, double *__restrict__ cost, size_t P)
@@ -436,7 +438,7 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
                     const double2 *row = reinterpret_cast<const double2 *>(tab + L * RS);
                     double y = INFINITY;
 #pragma unroll
-                    for (int h = 0; h < 8; h++) {
+                    for (int h = 0; h < NPAIR; h++) {
                         const double2 x = row[h];
                         y = fmin(y, __dadd_rn(x.x, Gc[2 * h]));
                         y = fmin(y, __dadd_rn(x.y, Gc[2 * h + 1]));
@@ -528,10 +530,10 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
         size_t grid = rows < DTFM_HK_GLOBAL_GRID ? rows : DTFM_HK_GLOBAL_GRID;
         constexpr int NL = DTFM_HK_BLOCK_LOW;
         size_t lds = ((size_t)(DTFM_HK_ROW_STRIDE << NL) + 256) * sizeof(double) + ((size_t)sizeof(uint16_t) << NL);
-        DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_held_karp_blocked<NL>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(k_held_karp_blocked<NL>, dim3((unsigned)grid), dim3(1 << NL), lds, st, b.ghat,
-                           b.datap, n, b.hk_tab, cost, rows);
+        auto kern = n <= 12 ? k_held_karp_blocked<NL, 6> : n <= 14 ? k_held_karp_blocked<NL, 7> : k_held_karp_blocked<NL, 8>;
+        DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)lds));
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(1 << NL), lds, st, b.ghat, b.datap, n, b.hk_tab, cost, rows);
     }
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;
