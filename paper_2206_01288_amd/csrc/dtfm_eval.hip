@@ -354,6 +354,42 @@ __device__ const unsigned char dtfm_binom10[11][11] = {
     {1, 6, 15, 20, 15, 6, 1, 0, 0, 0, 0}, {1, 7, 21, 35, 35, 21, 7, 1, 0, 0, 0}, {1, 8, 28, 56, 70, 56, 28, 8, 1, 0, 0},
     {1, 9, 36, 84, 126, 126, 84, 36, 9, 1, 0}, {1, 10, 45, 120, 210, 252, 210, 120, 45, 10, 1}};
 
+// The layers of one block of the blocked Held-Karp kernel (see k_held_karp_blocked); HM, a compile-time
+// constant, says which pairs of high-stage slots hold a stage of the block's set H.
+template <int NL, int NPAIR, uint32_t HM>
+__device__ __forceinline__ void hk_block_layers(double *tab, const uint16_t *lsub, const int *loff, const double (&Gc)[16],
+                                                double *X, uint32_t H, int nh, int n, int v, int grp)
+{
+    static_assert(NL % 2 == 0 && 16 - NL <= 6, "slot pairs (NL + 2 q, NL + 2 q + 1), q < 3");
+    constexpr int GROUPS = (1 << NL) / 16, RS = DTFM_HK_ROW_STRIDE;
+    for (int k = 0; k <= NL; k++) {
+        const int first = loff[k], cnt = loff[k + 1] - first;
+        for (int i = grp; i < cnt; i += GROUPS) {
+            const uint32_t L = lsub[first + i];
+            const uint32_t S = (H << NL) | L;
+            const bool in = (S >> v) & 1u;
+            const double2 *row = reinterpret_cast<const double2 *>(tab + L * RS);
+            double y = INFINITY;
+#pragma unroll
+            for (int h = 0; h < NPAIR; h++) {
+                // HM: bit q set = the pair of slots NL + 2 q, NL + 2 q + 1 holds a stage of H
+                const bool present = 2 * h >= NL ? ((HM >> ((2 * h - NL) / 2)) & 1u) != 0u : true;
+                if (!present) continue;
+                const double2 x = row[h];
+                y = fmin(y, __dadd_rn(x.x, Gc[2 * h]));
+                y = fmin(y, __dadd_rn(x.y, Gc[2 * h + 1]));
+            }
+            if (!in && v < n && S != 0u) {
+                if (v < NL)
+                    tab[(L | (1u << v)) * RS + v] = y;
+                else
+                    X[(((size_t)(H | (1u << (v - NL))) * nh + (v - NL)) << NL) + L] = y;
+            }
+        }
+        DTFM_LDS_BARRIER();
+    }
+}
+
 // NL: low stages per block (the workgroup has 2^NL threads); NPAIR: pairs of row slots that can hold a stage
 // (ceil(D_pp / 2): the slots beyond D_pp are +inf in every row and are not read)
 template <int NL, int NPAIR>
@@ -429,29 +465,17 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
             for (int hi = 0; hi < NHMAX; hi++)
                 if (hi < nh) tab[Lt * RS + NL + hi] = xv[hi];
             DTFM_LDS_BARRIER();
-            for (int k = 0; k <= NL; k++) {
-                const int first = loff[k], cnt = loff[k + 1] - first;
-                for (int i = grp; i < cnt; i += GROUPS) {
-                    const uint32_t L = lsub[first + i];
-                    const uint32_t S = (H << NL) | L;
-                    const bool in = (S >> v) & 1u;
-                    const double2 *row = reinterpret_cast<const double2 *>(tab + L * RS);
-                    double y = INFINITY;
-#pragma unroll
-                    for (int h = 0; h < NPAIR; h++) {
-                        const double2 x = row[h];
-                        y = fmin(y, __dadd_rn(x.x, Gc[2 * h]));
-                        y = fmin(y, __dadd_rn(x.y, Gc[2 * h + 1]));
-                    }
-                    if (!in && v < n && S != 0u) {
-                        if (v < NL)
-                            tab[(L | (1u << v)) * RS + v] = y;
-                        else
-                            X[(((size_t)(H | (1u << (v - NL))) * nh + (v - NL)) << NL) + L] = y;
-                    }
-                }
-                DTFM_LDS_BARRIER();
+            // The slots of high stages outside H are +inf in every row of the block. One copy of the layer
+            // loops per set of empty slot pairs (NL, NL+1), (NL+2, NL+3), (NL+4, NL+5): a copy neither reads nor
+            // relaxes its empty pairs. (A copy per set H, 64 of them, outgrows the instruction cache.)
+#define DTFM_HK_CASE(m) \
+    case m: hk_block_layers<NL, NPAIR, m>(tab, lsub, loff, Gc, X, H, nh, n, v, grp); break;
+            switch (((H & 3u) != 0u ? 1u : 0u) | ((H & 12u) != 0u ? 2u : 0u) | ((H & 48u) != 0u ? 4u : 0u)) {
+                DTFM_HK_CASE(0) DTFM_HK_CASE(1) DTFM_HK_CASE(2) DTFM_HK_CASE(3)
+                DTFM_HK_CASE(4) DTFM_HK_CASE(5) DTFM_HK_CASE(6) DTFM_HK_CASE(7)
+            default: break;
             }
+#undef DTFM_HK_CASE
         }
         if (threadIdx.x == 0) {   // the block of H = all high stages is still in LDS; its last row is the full set
             double m = INFINITY;
