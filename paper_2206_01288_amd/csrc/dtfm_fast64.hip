@@ -342,17 +342,7 @@ __device__ __forceinline__ void propose_gain4(const wave_ctx &cx, const unsigned
     }
 }
 
-// ---- Sec. 3.4 local search with the paper's four-candidate neighbourhood, all rounds in one launch
-// Each wavefront carries its candidates through every round: propose a swap (fastest link inside
-// each of the round's two stages, the four end-point swaps ranked by the paper's Gain), evaluate the
-// swapped allocation with eval_group, keep it iff strictly cheaper. The fastest link is found on the
-// ranks (same order and same ties as the weights); the Gain sums use the fp64 weights in slot order.
-// Sec. 3.4 selection, crossover and mutation for the four offspring cand0 .. cand0 + 3 of a wavefront (16
-// lanes each), the rows left as bytes at `rows` (4 x 64, stage-major). Same draws and steps as
-// k_make_offspring: two uniform parents; the child starts as parent 1; m_x times a random device that parent
-// 2 keeps in another stage is swapped with the device at a random slot of that stage; m_m random
-// transpositions. The draws of MK_STEPS steps are made by the 16 lanes (two steps per Philox block), the
-// dependent swaps by the first lane of each candidate.
+// ---- offspring of the evolutionary search made inside the local-search kernel (4 candidates per wavefront)
 // The lane's share of the two parents' rows (positions sub, sub + 16, sub + 32, sub + 48 of the lane's
 // candidate): loaded ahead of the table set-up, which hides the selection draw and the loads.
 struct parent_rows {
@@ -374,6 +364,12 @@ __device__ __forceinline__ parent_rows load_parents4(const dtfm_offspring_src &s
     return r;
 }
 
+// Sec. 3.4 selection, crossover and mutation for the four offspring cand0 .. cand0 + 3 of a wavefront (16
+// lanes each), the rows left as bytes at `rows` (4 x 64, stage-major). Same draws and steps as
+// k_make_offspring: two uniform parents; the child starts as parent 1; m_x times a random device that parent
+// 2 keeps in another stage is swapped with the device at a random slot of that stage; m_m random
+// transpositions. The draws of MK_STEPS steps are made by the 16 lanes (two steps per Philox block), the
+// dependent swaps by the first lane of each candidate.
 __device__ __forceinline__ void make_offspring4(const wave_ctx &cx, const dtfm_offspring_src &src, const parent_rows &par,
                                                 size_t cand0, size_t L, unsigned char *rows, unsigned char *scratch)
 {
@@ -453,6 +449,12 @@ __device__ __forceinline__ void make_offspring4(const wave_ctx &cx, const dtfm_o
     }
 }
 
+// ---- Sec. 3.4 local search with the paper's four-candidate neighbourhood, all rounds in one launch
+// Each wavefront carries its candidates through every round: propose a swap (fastest link inside
+// each of the round's two stages, the four end-point swaps ranked by the paper's Gain), evaluate the
+// swapped allocation with eval_group, keep it iff strictly cheaper. The fastest link is found on the
+// ranks (same order and same ties as the weights); the Gain sums use the fp64 weights in slot order.
+// With MAKE (4 candidates per wavefront) the rows are not read but made here: the offspring of `src`.
 template <int NC, bool MAKE>
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
 k_ls_gain4_fast64(const double *__restrict__ W_dp, const double *__restrict__ W_pp,
