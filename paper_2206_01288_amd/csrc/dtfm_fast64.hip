@@ -617,13 +617,13 @@ void dtfm_fast64_release(dtfm_problem *pr)
 
 // Candidates per wavefront pass. 32 keep every lane of the matching phase busy (32 * 14 couples = 7
 // full passes) and are used once that still gives every wavefront slot of the chip a pass; 8 fill
-// Held-Karp's lanes; when there are too few candidates to give every SIMD of the chip a wavefront
-// that way, 4 per wavefront shorten the pass.
+// Held-Karp's lanes. Up to two wavefronts per SIMD of 4 candidates each (8192 candidates) the shorter
+// passes of 4 win: their matching and Held-Karp programmes use the idle lanes to split the work.
 static int group_size(const dtfm_problem *pr, size_t rows)
 {
     const size_t simds = 4 * (size_t)pr->f64_grid;
     if (rows >= 32 * 2 * simds) return 32;
-    return rows <= 4 * simds ? 4 : 8;
+    return rows <= 8 * simds ? 4 : 8;
 }
 
 // Wavefronts per workgroup. The LDS tables allow one workgroup per CU, so a launch with fewer

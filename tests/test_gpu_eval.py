@@ -60,7 +60,7 @@ def test_config2_full_population(name, P):
 
 
 def test_config2_population_eight_candidates_per_wavefront():
-    # populations between 4097 and 65535 take the eight-candidates-per-wavefront variant of the fused kernel
+    # populations between 8193 and 65535 take the eight-candidates-per-wavefront variant of the fused kernel
     w = workloads.config("C2")
     o, g = both(w)
     perms = workloads.random_population(20003, 64, seed=11)
@@ -94,10 +94,10 @@ def test_config2_population_thirty_two_candidates_per_wavefront(P):
         assert np.array_equal(ghat[p], o.coarsen(perms[p])) and datap[p] == o.datap(perms[p])
 
 
-@pytest.mark.parametrize("P", [2047, 2049, 4095, 4096, 4097, 8191, 8193, 16383, 16385, 65535, 65536])
+@pytest.mark.parametrize("P", [2047, 2049, 4095, 4096, 4097, 8191, 8192, 8193, 16383, 16385, 65535, 65536])
 def test_population_sizes_where_the_group_size_changes(P):
-    # 4 candidates per wavefront pass up to 4096, 8 up to 65535, 32 from 65536; workgroups of 2, 4 or 8
-    # wavefronts (2 up to 1023 passes, 4 up to 2047): around each switch the costs
+    # 4 candidates per wavefront pass up to 8192, 8 up to 65535, 32 from 65536; workgroups of 2, 4 or 8
+    # wavefronts (as few as give every pass a wavefront of its own): around each switch the costs
     # are those of the oracle (sampled) and, row by row, those of small separately evaluated chunks
     w = workloads.config("C2")
     o, g = both(w)

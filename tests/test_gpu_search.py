@@ -134,9 +134,10 @@ def test_gain4_config2_ragged_small_populations(P):
     _ls_parity(workloads.config("C2"), workloads.random_population(P, 64, seed=20 + P), 31, dtfm.GAIN4)
 
 
-@pytest.mark.parametrize("P", [9001, 16500, 65573, 114693])
+@pytest.mark.parametrize("P", [5001, 8192, 9001, 16500, 65573, 114693])
 def test_gain4_large_population_variants(P):
-    # 9001, 16500: eight candidates per wavefront pass (workgroups of four and of eight wavefronts);
+    # 5001, 8192: four candidates per wavefront pass, two wavefronts per SIMD; 9001, 16500: eight candidates per
+    # wavefront pass (workgroups of four and of eight wavefronts);
     # 65573: thirty-two for the first 65536, a launch of its own for the rest; 114693: thirty-two, with a
     # ragged last group
     w = workloads.config("C2")
@@ -144,7 +145,7 @@ def test_gain4_large_population_variants(P):
     perms = workloads.random_population(P, 64, seed=12)
     d = dev(perms)
     cost, applied = dtfm.local_search(g, d, 3, dtfm.GAIN4, want_applied=True)
-    sel = np.r_[0:40, 8000:8040, P - 40:P]
+    sel = np.r_[0:40, P // 2:P // 2 + 40, P - 40:P]
     rp, rc, ra = o.local_search(perms[sel], 3, oracle.GAIN4)
     assert np.array_equal(host(d)[sel], rp) and np.array_equal(host(applied)[sel], ra)
     assert_costs_equal(host(cost)[sel], rc)
