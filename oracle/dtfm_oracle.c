@@ -25,19 +25,31 @@
  *   orc_local_search ALL_PAIRS  pinned: neighbourhood enumerated independently on tiny N,
  *                               monotonicity, fixed points, homogeneous no-move case
  *   orc_local_search GAIN4      gain formula pinned by hand computation; the choice of stage
- *                               pair per round and acceptance rule are this build's reading:
- *                               parity unpinned beyond invariants
+ *                               pair per round and the acceptance rule are this build's reading
+ *                               of Sec. 3.4 (the paper fixes neither); that the oracle implements
+ *                               that reading is pinned against a definition-level restatement
+ *                               in pure Python with Eqs. 1-4 by enumeration (proposal, schedule,
+ *                               acceptance, applied moves)
  *   orc_get_assignment          the tie-breaking rules are this build's choice (the paper names
  *                               none): pinned as implementing those rules by enumeration of all
  *                               tours and all matchings on tiny cases, by the closed form on a
  *                               homogeneous network, and by re-deriving the cost from the output
  *   orc_local_search KL         gain_KL formula pinned by hand computation and by its textbook
- *                               meaning (change of the cut weight between the two groups); the
- *                               round schedule and acceptance rule are shared with GAIN4 and are
- *                               this build's reading: parity unpinned beyond invariants
+ *                               meaning (change of the cut weight between the two groups); round
+ *                               schedule and acceptance rule as for GAIN4, pinned the same way
  *   orc_philox4x32_10           pinned: published known-answer vectors
- *   orc_evolve                  invariants only (valid permutations, elitism, determinism);
- *                               the GA operators are this build's reading: parity unpinned
+ *   draw / orc_init_candidate / orc_make_offspring / orc_evolve
+ *                               the paper names the steps of its genetic algorithm (two random
+ *                               parents, nodes swapped between them, local search, insert and
+ *                               drop the worst) but no operator in detail; the counter layout,
+ *                               shuffle, crossover, mutation and replacement are this build's
+ *                               reading. That the oracle implements exactly that reading is
+ *                               pinned: whole populations and whole runs against a pure-Python
+ *                               restatement with its own Philox (itself checked against the
+ *                               known-answer vectors), a hand-worked 4-device case with the draws
+ *                               written out, and planted mistakes (swapped counter words, wrong
+ *                               parent-2 stage lookup, shuffle draw index) that the comparison
+ *                               is shown to catch
  */
 #include <math.h>
 #include <stdint.h>
