@@ -7,9 +7,12 @@
  * local_search, evolve) only enqueue kernels on the caller's stream and return without
  * synchronising; results are valid once the stream has been synchronised. All functions return
  * a status code (DTFM_OK = 0); none aborts or throws. A problem handle owns device copies of the
- * weight matrices and a scratch area that grows on demand (hipMalloc inside a hot call happens
- * only when a larger population than ever before is passed); calls on one handle must not
- * overlap in time.
+ * weight matrices and a scratch area that grows on demand: when a hot call is given a larger
+ * population than the handle has seen (or reserved with dtfm_reserve), that call first waits for
+ * the whole device (hipDeviceSynchronize), frees the old area and allocates a larger one
+ * (hipFree, hipMalloc), and only then enqueues. Call dtfm_reserve once, outside the hot loop, to
+ * keep the hot calls free of that. Calls on one handle share its scratch area and must not
+ * overlap in time (they race otherwise), whatever streams they are given.
  *
  * Candidate layout ("perm"): row-major P x N int32. Row p is a permutation of 0..N-1; position q
  * holds the device sigma_{i,j} (Sec. 2, assignment strategy) that runs pipeline stage
@@ -73,6 +76,13 @@ int dtfm_get_weights(const dtfm_problem *prob, double *W_dp_host, double *W_pp_h
  * 0..N-1 are undefined behaviour. P = 0 is a no-op. Errors: NULL, ARG (P < 0), HIP. */
 int dtfm_eval_population(dtfm_problem *prob, const int32_t *perm, int P, double *cost,
                          void *hip_stream);
+
+/* Grows the handle's scratch area, now, to what eval_population, coarsened_graph, get_assignment
+ * and local_search with `neighbourhood` (move_costs counts as DTFM_ALL_PAIRS) on up to
+ * max(P, lambda) rows and evolve with population P and lambda offspring need, so that those calls neither allocate nor synchronise
+ * later. Synchronises the device when it has to grow the area. P or lambda may be 0.
+ * Errors: NULL, ARG (negative sizes, unknown neighbourhood), HIP (out of memory). */
+int dtfm_reserve(dtfm_problem *prob, int P, int lambda, int neighbourhood);
 
 /* The intermediate quantities of the same evaluation, for checking: ghat (device, P*D_pp*D_pp
  * doubles, symmetric, zero diagonal) receives the coarsened graph of Sec. 3.3 (Eq. 3 per stage

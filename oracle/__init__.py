@@ -77,6 +77,7 @@ def lib():
         L.orc_draw_randint.restype = c_uint32
         L.orc_init_candidate.argtypes = [c_uint64, c_int, c_int, ip]
         L.orc_make_offspring.argtypes = [c_uint64, c_int, c_int, ip, c_int, c_int, c_int, c_int, c_int, ip, ip]
+        L.orc_replace.argtypes = [c_int, c_int, c_int, ip, dp, ip, dp]
         L.orc_evolve.argtypes = [dp, dp, c_int, c_int, c_int, c_uint64, c_int, POINTER(GAParams), ip, dp, dp]
         _lib = L
     return _lib
@@ -188,6 +189,41 @@ class Problem:
         lib().orc_evolve(a, b, self.N, self.D_dp, self.D_pp, c_uint64(seed), generations,
                          ctypes.byref(prm), pop.ctypes.data_as(POINTER(c_int)),
                          cost.ctypes.data_as(POINTER(c_double)), trace.ctypes.data_as(POINTER(c_double)))
+        return pop, cost, trace
+
+    def evolve_by_generation(self, seed, generations, P, lam=None, m_x=None, m_m=1, ls_moves=8,
+                             neighbourhood=GAIN4, threads=1, on_generation=None):
+        """The run of `evolve` from a cold start, composed generation by generation from the oracle's own
+        parts (init_candidate, eval_population, make_offspring, local_search, orc_replace) so that the
+        evaluations, which are independent per candidate, can run on `threads` host threads and each
+        generation can be reported: on_generation(g, population, cost) is called with g = -1 for the
+        evaluated initial population and then after every replacement. Same results as evolve()."""
+        from concurrent.futures import ThreadPoolExecutor
+        lam = P if lam is None else lam
+        m_x = self.N // 4 if m_x is None else m_x
+
+        def split(rows):
+            return [c for c in np.array_split(rows, max(1, min(len(rows), threads * 4))) if len(c)]
+
+        with ThreadPoolExecutor(max(1, threads)) as ex:
+            pop = np.stack([init_candidate(seed, k, self.N) for k in range(P)])
+            cost = np.concatenate(list(ex.map(self.eval_population, split(pop))))
+            if on_generation:
+                on_generation(-1, pop, cost)
+            trace = np.empty(generations)
+            for g in range(generations):
+                off = np.stack([make_offspring(seed, g, k, pop, self.D_dp, m_x, m_m)[0] for k in range(lam)])
+                res = list(ex.map(lambda rows: self.local_search(rows, ls_moves, neighbourhood), split(off)))
+                off = np.ascontiguousarray(np.concatenate([r[0] for r in res]), dtype=np.int32)
+                off_cost = np.ascontiguousarray(np.concatenate([r[1] for r in res]))
+                pop = np.ascontiguousarray(pop, dtype=np.int32)
+                cost = np.ascontiguousarray(cost)
+                lib().orc_replace(self.N, P, lam, pop.ctypes.data_as(POINTER(c_int)),
+                                  cost.ctypes.data_as(POINTER(c_double)), off.ctypes.data_as(POINTER(c_int)),
+                                  off_cost.ctypes.data_as(POINTER(c_double)))
+                trace[g] = cost[0]
+                if on_generation:
+                    on_generation(g, pop, cost)
         return pop, cost, trace
 
 

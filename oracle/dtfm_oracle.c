@@ -686,10 +686,31 @@ static int cmp_keyed(const void *a, const void *b)
     return (x->origin > y->origin) - (x->origin < y->origin);
 }
 
+/* Replacement (Sec. 3.4: "add o*, remove the worst if o* is better", taken for a whole generation):
+ * the P best of parents and offspring ordered by (cost, origin index), parents numbered before
+ * offspring, so that an offspring enters only by beating an incumbent. pop/cost: P parents, in/out
+ * (out ascending); off/off_cost: L offspring. */
+void orc_replace(int N, int P, int L, int *pop, double *cost, const int *off, const double *off_cost)
+{
+    int *next = (int *)malloc(sizeof(int) * (size_t)P * N);
+    double *next_cost = (double *)malloc(sizeof(double) * P);
+    keyed *keys = (keyed *)malloc(sizeof(keyed) * (size_t)(P + L));
+    for (int i = 0; i < P; i++) { keys[i].cost = cost[i]; keys[i].origin = i; }
+    for (int k = 0; k < L; k++) { keys[P + k].cost = off_cost[k]; keys[P + k].origin = P + k; }
+    qsort(keys, (size_t)(P + L), sizeof(keyed), cmp_keyed);
+    for (int i = 0; i < P; i++) {
+        int o = keys[i].origin;
+        const int *src = (o < P) ? pop + (size_t)o * N : off + (size_t)(o - P) * N;
+        memcpy(next + (size_t)i * N, src, sizeof(int) * N);
+        next_cost[i] = keys[i].cost;
+    }
+    memcpy(pop, next, sizeof(int) * (size_t)P * N);
+    memcpy(cost, next_cost, sizeof(double) * P);
+    free(next); free(next_cost); free(keys);
+}
+
 /* Generational restatement of the paper's loop: every generation makes lambda offspring from the
- * generation-start population, improves each by local search, then keeps the P best of parents
- * and offspring ordered by (cost, origin index), parents numbered before offspring, so that an
- * offspring enters only by beating an incumbent ("add o*, remove the worst if o* is better").
+ * generation-start population, improves each by local search, then replaces (orc_replace).
  * population: P x N (in when warm_start, out), cost: P out (ascending after >= 1 generation),
  * best_trace: one value per generation = lowest cost in the population after replacement. */
 void orc_evolve(const double *W_dp, const double *W_pp, int N, int D_dp, int D_pp, uint64_t seed,
@@ -698,10 +719,7 @@ void orc_evolve(const double *W_dp, const double *W_pp, int N, int D_dp, int D_p
 {
     int P = prm->P, L = prm->lambda;
     int *off = (int *)malloc(sizeof(int) * (size_t)L * N);
-    int *next = (int *)malloc(sizeof(int) * (size_t)P * N);
     double *off_cost = (double *)malloc(sizeof(double) * L);
-    double *next_cost = (double *)malloc(sizeof(double) * P);
-    keyed *keys = (keyed *)malloc(sizeof(keyed) * (size_t)(P + L));
     if (!prm->warm_start)
         for (int k = 0; k < P; k++) orc_init_candidate(seed, k, N, population + (size_t)k * N);
     orc_eval_population(W_dp, W_pp, N, D_dp, D_pp, population, P, cost);
@@ -709,18 +727,8 @@ void orc_evolve(const double *W_dp, const double *W_pp, int N, int D_dp, int D_p
         for (int k = 0; k < L; k++)
             orc_make_offspring(seed, g, k, population, P, N, D_dp, prm->m_x, prm->m_m, off + (size_t)k * N, NULL);
         orc_local_search(W_dp, W_pp, N, D_dp, D_pp, off, L, prm->ls_moves, prm->neighbourhood, off_cost, NULL);
-        for (int i = 0; i < P; i++) { keys[i].cost = cost[i]; keys[i].origin = i; }
-        for (int k = 0; k < L; k++) { keys[P + k].cost = off_cost[k]; keys[P + k].origin = P + k; }
-        qsort(keys, (size_t)(P + L), sizeof(keyed), cmp_keyed);
-        for (int i = 0; i < P; i++) {
-            int o = keys[i].origin;
-            const int *src = (o < P) ? population + (size_t)o * N : off + (size_t)(o - P) * N;
-            memcpy(next + (size_t)i * N, src, sizeof(int) * N);
-            next_cost[i] = keys[i].cost;
-        }
-        memcpy(population, next, sizeof(int) * (size_t)P * N);
-        memcpy(cost, next_cost, sizeof(double) * P);
+        orc_replace(N, P, L, population, cost, off, off_cost);
         best_trace[g] = cost[0];
     }
-    free(off); free(next); free(off_cost); free(next_cost); free(keys);
+    free(off); free(off_cost);
 }

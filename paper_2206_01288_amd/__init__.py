@@ -5,10 +5,10 @@ PyTorch is used only to own device memory and to name the HIP stream. There is n
 loading fails loudly when the library has not been built.
 """
 from .binding import (ALL_PAIRS, GAIN4, KL, DtfmError, GAParams, Problem, create_problem, destroy_problem,
-                      eval_population, coarsened_graph, get_assignment, validate_population, local_search, move_costs, evolve,
+                      eval_population, reserve, coarsened_graph, get_assignment, validate_population, local_search, move_costs, evolve,
                       philox_blocks, get_weights, library_path, load_library, DECLARED_SYMBOLS)
 
 __all__ = ["ALL_PAIRS", "GAIN4", "KL", "DtfmError", "GAParams", "Problem", "create_problem", "destroy_problem",
-           "eval_population", "coarsened_graph", "get_assignment", "validate_population", "local_search", "move_costs",
+           "eval_population", "reserve", "coarsened_graph", "get_assignment", "validate_population", "local_search", "move_costs",
            "evolve",
            "philox_blocks", "get_weights", "library_path", "load_library", "DECLARED_SYMBOLS"]

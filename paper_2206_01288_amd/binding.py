@@ -18,7 +18,7 @@ KL = 2
 DECLARED_SYMBOLS = [
     "dtfm_create_problem", "dtfm_destroy_problem", "dtfm_get_weights", "dtfm_eval_population",
     "dtfm_coarsened_graph", "dtfm_get_assignment", "dtfm_validate_population", "dtfm_local_search",
-    "dtfm_move_costs", "dtfm_evolve",
+    "dtfm_move_costs", "dtfm_evolve", "dtfm_reserve",
     "dtfm_philox_blocks", "dtfm_status_string", "dtfm_last_hip_error",
 ]
 
@@ -57,6 +57,7 @@ def load_library():
     L.dtfm_destroy_problem.restype = None
     L.dtfm_get_weights.argtypes = [c_void_p, dp, dp]
     L.dtfm_eval_population.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p]
+    L.dtfm_reserve.argtypes = [c_void_p, c_int, c_int, c_int]
     L.dtfm_coarsened_graph.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p]
     L.dtfm_get_assignment.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p]
     L.dtfm_validate_population.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p]
@@ -156,6 +157,11 @@ def eval_population(prob: Problem, perm, cost=None, stream=None):
     _check(L.dtfm_eval_population(prob.handle, _dev_ptr(perm, torch.int32, P * prob.N, "perm"), P,
                                   _dev_ptr(cost, torch.float64, P, "cost"), _stream(stream)))
     return cost
+
+
+def reserve(prob: Problem, P: int, lam: int = 0, neighbourhood: int = GAIN4):
+    """dtfm_reserve: grows the handle's scratch area once, ahead of the hot calls."""
+    _check(load_library().dtfm_reserve(prob.handle, int(P), int(lam), int(neighbourhood)))
 
 
 def coarsened_graph(prob: Problem, perm, stream=None):

@@ -300,6 +300,33 @@ extern "C" int dtfm_evolve(dtfm_problem *pr, uint64_t seed, int generations, con
     return dtfm_ga_enqueue(pr, b, seed, generations, *prm, population, cost, best_trace, (hipStream_t)hip_stream);
 }
 
+extern "C" int dtfm_reserve(dtfm_problem *pr, int P, int lambda, int neighbourhood)
+{
+    if (pr == nullptr) return DTFM_ERR_NULL;
+    if (P < 0 || lambda < 0) return DTFM_ERR_ARG;
+    if (neighbourhood != DTFM_ALL_PAIRS && neighbourhood != DTFM_GAIN4 && neighbourhood != DTFM_KL) return DTFM_ERR_ARG;
+    const size_t rows = (size_t)(P > lambda ? P : lambda);
+    if (rows == 0) return DTFM_OK;
+    size_t need = 0;
+    auto grow = [&](const dtfm_arena &m) { need = m.off > need ? m.off : need; };
+    dtfm_arena m = {nullptr, 0};
+    dtfm_eval_carve(pr, m, rows);
+    grow(m);
+    m = {nullptr, 0};
+    dtfm_ls_carve(pr, m, rows, neighbourhood);
+    grow(m);
+    m = {nullptr, 0};
+    dtfm_assign_carve(pr, m, rows);
+    grow(m);
+    if (P > 0 && lambda > 0) {
+        dtfm_ga_params prm = {P, lambda, 0, 0, 0, neighbourhood, 0};
+        m = {nullptr, 0};
+        dtfm_ga_carve(pr, m, prm);
+        grow(m);
+    }
+    return ensure_scratch(pr, need);
+}
+
 extern "C" int dtfm_philox_blocks(uint64_t seed, uint32_t stream, uint32_t g, uint32_t k, uint32_t first_block,
                                   int n_blocks, uint32_t *out, void *hip_stream)
 {

@@ -485,17 +485,25 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
     }
 }
 
-dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows)
+size_t dtfm_hk_exchange_bytes(const dtfm_problem *pr)
+{
+    if (pr->D_pp <= DTFM_HK_LDS_MAX_DPP) return 0;
+    size_t nh = (size_t)pr->D_pp - DTFM_HK_BLOCK_LOW;
+    return ((nh << nh) << DTFM_HK_BLOCK_LOW) * sizeof(double);
+}
+
+dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows, size_t hk_grid_cap)
 {
     dtfm_eval_bufs b;
     size_t n = pr->D_pp;
     b.datap = ar.take<double>(rows);
     b.ghat = ar.take<double>(rows * n * n);
     b.hk_tab = nullptr;
+    b.hk_grid = 0;
     if (pr->D_pp > DTFM_HK_LDS_MAX_DPP) {
-        size_t grid = rows < DTFM_HK_GLOBAL_GRID ? rows : DTFM_HK_GLOBAL_GRID;
-        size_t nh = n - DTFM_HK_BLOCK_LOW;
-        b.hk_tab = ar.take<double>(grid * ((nh << nh) << DTFM_HK_BLOCK_LOW));
+        size_t cap = hk_grid_cap != 0 && hk_grid_cap < DTFM_HK_GLOBAL_GRID ? hk_grid_cap : DTFM_HK_GLOBAL_GRID;
+        b.hk_grid = rows < cap ? rows : cap;
+        b.hk_tab = ar.take<double>(b.hk_grid * (dtfm_hk_exchange_bytes(pr) / sizeof(double)));
     }
     return b;
 }
@@ -551,7 +559,7 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
         hipLaunchKernelGGL(k_held_karp<true>, dim3((unsigned)rows), dim3(bt), lds, st, b.ghat, b.datap, n,
                            pr->hk_subsets, pr->hk_off, (double *)nullptr, cost, rows);
     } else {
-        size_t grid = rows < DTFM_HK_GLOBAL_GRID ? rows : DTFM_HK_GLOBAL_GRID;
+        size_t grid = b.hk_grid;
         constexpr int NL = DTFM_HK_BLOCK_LOW;
         size_t lds = ((size_t)(DTFM_HK_ROW_STRIDE << NL) + 256) * sizeof(double) + ((size_t)sizeof(uint16_t) << NL);
         auto kern = n <= 12 ? k_held_karp_blocked<NL, 6> : n <= 14 ? k_held_karp_blocked<NL, 7> : k_held_karp_blocked<NL, 8>;

@@ -76,9 +76,13 @@ int dtfm_hip_fail(hipError_t e, const char *what);
 struct dtfm_eval_bufs {
     double *datap;   // rows
     double *ghat;    // rows * D_pp * D_pp
-    double *hk_tab;  // DTFM_HK_GLOBAL_GRID exchange areas, or null when the table fits LDS
+    double *hk_tab;  // hk_grid exchange areas, or null when the table fits LDS
+    size_t hk_grid;  // workgroups of the blocked Held-Karp kernel (each owns one exchange area)
 };
-dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows);
+// hk_grid_cap: upper limit on the number of exchange areas (0: DTFM_HK_GLOBAL_GRID)
+dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows, size_t hk_grid_cap = 0);
+// bytes of one exchange area of the blocked Held-Karp kernel (0 when the table fits LDS)
+size_t dtfm_hk_exchange_bytes(const dtfm_problem *pr);
 // enqueues a2..a6 for `rows` candidates; cost may be null (then only datap/ghat are produced)
 int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int32_t *perm,
                       size_t rows, double *cost, hipStream_t st);

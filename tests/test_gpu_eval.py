@@ -218,3 +218,17 @@ def test_error_paths_on_device():
     o1, g1 = both(w1)
     p1 = dev(workloads.random_population(4, 5, seed=0))
     assert L.dtfm_local_search(g1.handle, p1.data_ptr(), 4, 1, dtfm.GAIN4, cost.data_ptr(), None, None) == 6
+
+
+def test_reserve_keeps_hot_calls_from_growing_the_arena():
+    w = workloads.config("C4")
+    _, g = both(w)
+    dtfm.reserve(g, 64, 64, dtfm.GAIN4)
+    perms = dev(workloads.random_population(64, w.N, seed=3))
+    a = host(dtfm.eval_population(g, perms))
+    pop, cost, trace = dtfm.evolve(g, 1, 1, 64, ls_moves=1)
+    b = host(dtfm.eval_population(g, perms))
+    assert np.array_equal(a, b)
+    with pytest.raises(dtfm.DtfmError):
+        dtfm.reserve(g, -1)
+    dtfm.destroy_problem(g)

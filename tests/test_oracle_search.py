@@ -342,3 +342,16 @@ def test_evolve_steady_state_is_insert_and_drop_worst():
         assert np.array_equal(pop, want_pop) and np.array_equal(cost, want_cost)
         assert trace[-1] == cost[0]
     assert 0 < inserted < G      # both branches of the rule were exercised
+
+
+def test_evolve_by_generation_equals_evolve():
+    # the generation-wise, threaded composition used to write the stored configuration-5 trajectory gives
+    # the bits of the oracle's sequential loop
+    for name, P, lam, kw in (("C1", 10, None, {}), ("C2", 12, 5, dict(m_x=40, m_m=2, ls_moves=3)),
+                             ("C1", 6, 1, dict(ls_moves=2)), ("C1", 4, 9, dict(neighbourhood=oracle.KL))):
+        w, pr = _problem(name)
+        want = pr.evolve(5, 4, P, lam=lam, **kw)
+        seen = []
+        got = pr.evolve_by_generation(5, 4, P, lam=lam, threads=3, on_generation=lambda g, p, c: seen.append((g, c.min())), **kw)
+        assert all(np.array_equal(a, b) for a, b in zip(want, got))
+        assert [g for g, _ in seen] == [-1, 0, 1, 2, 3] and [c for _, c in seen[1:]] == want[2].tolist()
