@@ -38,7 +38,8 @@ enum {
     DTFM_ERR_VALUE = 3,         /* negative / non-finite latency or size, non-positive bandwidth */
     DTFM_ERR_ARG = 4,           /* bad P, rounds, neighbourhood, generations or GA parameter */
     DTFM_ERR_HIP = 5,           /* a HIP runtime call failed (no device, out of memory, ...) */
-    DTFM_ERR_UNSUPPORTED = 6    /* e.g. GAIN4 with D_dp < 2 or D_pp < 2 */
+    DTFM_ERR_UNSUPPORTED = 6,   /* e.g. GAIN4 with D_dp < 2 or D_pp < 2 */
+    DTFM_ERR_TOO_LARGE = 7      /* dtfm_eval_population_noalloc: P does not fit the fixed scratch area */
 };
 
 /* Supported limits: D_pp <= 16 (Held-Karp table 2^D_pp x D_pp), D_dp <= 64 (one wavefront lane
@@ -76,6 +77,24 @@ int dtfm_get_weights(const dtfm_problem *prob, double *W_dp_host, double *W_pp_h
  * 0..N-1 are undefined behaviour. P = 0 is a no-op. Errors: NULL, ARG (P < 0), HIP. */
 int dtfm_eval_population(dtfm_problem *prob, const int32_t *perm, int P, double *cost,
                          void *hip_stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): dtfm_eval_population with the same arguments, results
+ * and kernels, whose intermediate buffers (DataP per candidate, the coarsened graphs, and for
+ * D_pp > 10 the Held-Karp exchange areas) lie in a fixed area of DTFM_FIXED_SCRATCH_BYTES that is
+ * part of the library's device image (every GPU the library is used on holds one copy until the
+ * process ends). The call allocates and frees nothing and does not synchronise. It needs
+ * 8 (1 + D_pp^2) bytes per candidate (rounded up to 256-byte pieces), and for D_pp > 10 at least
+ * one exchange area of 8 (D_pp - 10) 2^D_pp bytes behind that (3 MiB at D_pp = 16; as many areas
+ * as fit are used, one per workgroup, so the Held-Karp step runs on fewer workgroups than in
+ * dtfm_eval_population); a larger P returns DTFM_ERR_TOO_LARGE and enqueues nothing. The 64-device
+ * shape (N = 64, D_dp = 8, D_pp = 8) needs no scratch and takes any P. All calls on one GPU share
+ * the one area, which keeps the previous call's contents: calls that overlap in time on one GPU
+ * race, also across problem handles and streams. The current device must be the one the
+ * handle was created on (DTFM_ERR_ARG otherwise). Other errors as dtfm_eval_population. */
+#define DTFM_FIXED_SCRATCH_BYTES (32u << 20)
+int dtfm_eval_population_noalloc(dtfm_problem *prob, const int32_t *perm, int P, double *cost,
+                                 void *hip_stream);
 
 /* Grows the handle's scratch area, now, to what eval_population, coarsened_graph, get_assignment
  * and local_search with `neighbourhood` (move_costs counts as DTFM_ALL_PAIRS) on up to

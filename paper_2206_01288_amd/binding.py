@@ -13,12 +13,13 @@ _LIB_PATH = os.path.join(_PKG, "libdtfm.so")
 ALL_PAIRS = 0
 GAIN4 = 1
 KL = 2
+FIXED_SCRATCH_BYTES = 32 << 20     # DTFM_FIXED_SCRATCH_BYTES of include/dtfm.h
 
 # every entry point include/dtfm.h declares
 DECLARED_SYMBOLS = [
     "dtfm_create_problem", "dtfm_destroy_problem", "dtfm_get_weights", "dtfm_eval_population",
     "dtfm_coarsened_graph", "dtfm_get_assignment", "dtfm_validate_population", "dtfm_local_search",
-    "dtfm_move_costs", "dtfm_evolve", "dtfm_reserve",
+    "dtfm_move_costs", "dtfm_evolve", "dtfm_eval_population_noalloc", "dtfm_reserve",
     "dtfm_philox_blocks", "dtfm_status_string", "dtfm_last_hip_error",
 ]
 
@@ -57,6 +58,7 @@ def load_library():
     L.dtfm_destroy_problem.restype = None
     L.dtfm_get_weights.argtypes = [c_void_p, dp, dp]
     L.dtfm_eval_population.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p]
+    L.dtfm_eval_population_noalloc.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p]
     L.dtfm_reserve.argtypes = [c_void_p, c_int, c_int, c_int]
     L.dtfm_coarsened_graph.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p]
     L.dtfm_get_assignment.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p]
@@ -156,6 +158,16 @@ def eval_population(prob: Problem, perm, cost=None, stream=None):
         cost = torch.empty(P, dtype=torch.float64, device=perm.device)
     _check(L.dtfm_eval_population(prob.handle, _dev_ptr(perm, torch.int32, P * prob.N, "perm"), P,
                                   _dev_ptr(cost, torch.float64, P, "cost"), _stream(stream)))
+    return cost
+
+
+def eval_population_noalloc(prob: Problem, perm, cost, stream=None):
+    """dtfm_eval_population_noalloc: as eval_population, with the caller's `cost` tensor (nothing is allocated)."""
+    import torch
+    L = load_library()
+    P = perm.shape[0] if perm.dim() == 2 else 0
+    _check(L.dtfm_eval_population_noalloc(prob.handle, _dev_ptr(perm, torch.int32, P * prob.N, "perm"), P,
+                                          _dev_ptr(cost, torch.float64, P, "cost"), _stream(stream)))
     return cost
 
 

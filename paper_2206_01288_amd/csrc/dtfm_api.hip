@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -30,8 +31,32 @@ extern "C" const char *dtfm_status_string(int status)
     case DTFM_ERR_ARG: return "bad argument";
     case DTFM_ERR_HIP: return "HIP runtime error";
     case DTFM_ERR_UNSUPPORTED: return "unsupported for this problem shape";
+    case DTFM_ERR_TOO_LARGE: return "population too large for the fixed scratch area of the allocation-free entry point";
     default: return "unknown status";
     }
+}
+
+// Scratch area of the allocation-free entry point: part of the library's device image, so every GPU the
+// library runs on holds its own copy from the first use of the library until the process ends. In host
+// code the array's name is only a handle for hipGetSymbolAddress; kernels and copies get the address that
+// call returns for the current device, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[DTFM_FIXED_SCRATCH_BYTES];
+#define DTFM_MAX_DEVICES 64
+static char *g_fixed_scratch[DTFM_MAX_DEVICES];
+static std::mutex g_fixed_scratch_mutex;
+
+// address of `scratch` on `device`, which must be the current device
+static int fixed_scratch_of(int device, char **out)
+{
+    if (device < 0 || device >= DTFM_MAX_DEVICES) return DTFM_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_fixed_scratch_mutex);
+    if (g_fixed_scratch[device] == nullptr) {
+        void *ptr = nullptr;
+        DTFM_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        g_fixed_scratch[device] = static_cast<char *>(ptr);
+    }
+    *out = g_fixed_scratch[device];
+    return DTFM_OK;
 }
 
 static int ensure_scratch(dtfm_problem *pr, size_t bytes)
@@ -108,6 +133,8 @@ extern "C" int dtfm_create_problem(const double *latency, const double *bandwidt
         if (e__ != hipSuccess) return fail(dtfm_hip_fail(e__, #call));      \
     } while (0)
     CREATE_HIP(hipGetDevice(&pr->device));
+    rc = fixed_scratch_of(pr->device, &pr->fixed_scratch);
+    if (rc != DTFM_OK) return fail(rc);
     CREATE_HIP(hipMalloc((void **)&pr->W_dp, mat));
     CREATE_HIP(hipMalloc((void **)&pr->W_pp, mat));
     CREATE_HIP(hipMalloc((void **)&pr->hk_subsets, subs.size() * sizeof(uint32_t)));
@@ -189,6 +216,47 @@ extern "C" int dtfm_eval_population(dtfm_problem *pr, const int32_t *perm, int P
     dtfm_arena ar = {pr->scratch, 0};
     dtfm_eval_bufs b = dtfm_eval_carve(pr, ar, (size_t)P);
     return dtfm_eval_enqueue(pr, b, perm, (size_t)P, cost, st);
+}
+
+// Carves the evaluation buffers for P rows out of the fixed scratch area; with the blocked Held-Karp kernel
+// as many exchange areas as still fit behind them (fewer workgroups than a call that may allocate).
+static int carve_fixed(const dtfm_problem *pr, size_t P, dtfm_eval_bufs *b)
+{
+    dtfm_arena measure = {nullptr, 0};
+    dtfm_eval_carve(pr, measure, P, 1);
+    if (measure.off > DTFM_FIXED_SCRATCH_BYTES) return DTFM_ERR_TOO_LARGE;
+    size_t cap = 0;
+    const size_t area = (dtfm_hk_exchange_bytes(pr) + 255) & ~(size_t)255;
+    if (area != 0) {
+        cap = 1 + (DTFM_FIXED_SCRATCH_BYTES - measure.off) / area;
+        if (cap > P) cap = P;
+        // rounding of the carved pieces to 256 bytes: make sure the chosen number fits
+        for (;; cap--) {
+            dtfm_arena m2 = {nullptr, 0};
+            dtfm_eval_carve(pr, m2, P, cap);
+            if (m2.off <= DTFM_FIXED_SCRATCH_BYTES) break;
+            if (cap == 1) return DTFM_ERR_TOO_LARGE;
+        }
+    }
+    dtfm_arena ar = {pr->fixed_scratch, 0};
+    *b = dtfm_eval_carve(pr, ar, P, cap);
+    return DTFM_OK;
+}
+
+extern "C" int dtfm_eval_population_noalloc(dtfm_problem *pr, const int32_t *perm, int P, double *cost,
+                                            void *hip_stream)
+{
+    if (pr == nullptr) return DTFM_ERR_NULL;
+    if (P < 0) return DTFM_ERR_ARG;
+    if (P == 0) return DTFM_OK;
+    if (perm == nullptr || cost == nullptr) return DTFM_ERR_NULL;
+    int device = -1;
+    DTFM_HIP(hipGetDevice(&device));
+    if (device != pr->device) return DTFM_ERR_ARG;   // the handle's matrices and scratch copy live on its device
+    dtfm_eval_bufs b;
+    int rc = carve_fixed(pr, (size_t)P, &b);
+    if (rc != DTFM_OK) return rc;
+    return dtfm_eval_enqueue(pr, b, perm, (size_t)P, cost, (hipStream_t)hip_stream);
 }
 
 extern "C" int dtfm_coarsened_graph(dtfm_problem *pr, const int32_t *perm, int P, double *ghat,

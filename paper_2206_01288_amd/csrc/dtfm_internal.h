@@ -44,6 +44,7 @@ struct dtfm_problem {
     dtfm_layer_off hk_off;
     char *scratch;          // device arena, grown on demand
     size_t scratch_bytes;
+    char *fixed_scratch;    // this device's copy of the library's fixed scratch area (allocation-free entry point)
     // fused kernel for the 64-device shape (N = 64, D_dp = 8, D_pp = 8)
     bool fast64;
     uint16_t *f64_rank;     // device, N*N: rank of W_pp[d][d'] among all off-diagonal weights

@@ -23,11 +23,11 @@ def test_library_exports_every_declared_symbol():
 def test_status_strings():
     L = dtfm.load_library()
     seen = set()
-    for s in range(0, 8):
+    for s in range(0, 9):
         text = L.dtfm_status_string(s)
         assert text is not None and len(text) > 0
         seen.add(text)
-    assert len(seen) == 8 and L.dtfm_status_string(0) == b"ok"
+    assert len(seen) == 9 and L.dtfm_status_string(0) == b"ok"
 
 
 @pytest.mark.parametrize("kw,status", [
