@@ -176,15 +176,19 @@ def reserve(prob: Problem, P: int, lam: int = 0, neighbourhood: int = GAIN4):
     _check(load_library().dtfm_reserve(prob.handle, int(P), int(lam), int(neighbourhood)))
 
 
-def coarsened_graph(prob: Problem, perm, stream=None):
-    """Returns (ghat [P, D_pp, D_pp], datap [P]) device tensors."""
+def coarsened_graph(prob: Problem, perm, stream=None, out=None):
+    """Returns (ghat [P, D_pp, D_pp], datap [P]) device tensors (`out`: the pair to fill instead of new ones)."""
     import torch
     L = load_library()
     P = perm.shape[0]
-    ghat = torch.empty((P, prob.D_pp, prob.D_pp), dtype=torch.float64, device=perm.device)
-    datap = torch.empty(P, dtype=torch.float64, device=perm.device)
+    if out is not None:
+        ghat, datap = out
+    else:
+        ghat = torch.empty((P, prob.D_pp, prob.D_pp), dtype=torch.float64, device=perm.device)
+        datap = torch.empty(P, dtype=torch.float64, device=perm.device)
     _check(L.dtfm_coarsened_graph(prob.handle, _dev_ptr(perm, torch.int32, P * prob.N, "perm"), P,
-                                  _dev_ptr(ghat, torch.float64), _dev_ptr(datap, torch.float64), _stream(stream)))
+                                  _dev_ptr(ghat, torch.float64, P * prob.D_pp * prob.D_pp, "ghat"),
+                                  _dev_ptr(datap, torch.float64, P, "datap"), _stream(stream)))
     return ghat, datap
 
 
