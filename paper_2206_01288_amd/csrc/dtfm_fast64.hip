@@ -264,6 +264,108 @@ k_eval_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank
     }
 }
 
+// Population evaluation for populations so small that every SIMD has one group of four candidates and the launch
+// is as long as one wavefront's instruction stream: the group gets a PAIR of wavefronts (w and w + cw of the
+// workgroup, which share a SIMD). Both match: each takes two of the four candidates, two lanes per couple of stage
+// pairs (28 couples, 56 lanes, the programme of match_couple_halves, 1,070 instructions instead of 1,790), and the
+// two streams fill each other's wait states. Then the first runs Held-Karp for all four candidates (64 lanes,
+// hk_registers<true>) while the second computes their DataP straight from the global W_dp (no LDS copy of it).
+// Workgroup barriers: after the table set-up, after the matching, before the final sum.
+__global__ void __launch_bounds__(WAVES_PER_BLOCK * 64)
+k_eval_fast64_paired(const double *__restrict__ W_dp, const uint16_t *__restrict__ rank_tab,
+                     const double *__restrict__ rank_val, const int32_t *__restrict__ perm, size_t P,
+                     double *__restrict__ cost, double *__restrict__ ghat_out, double *__restrict__ datap_out)
+{
+    constexpr int NC = 4;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cw = blockDim.x >> 7;            // groups of the workgroup; wavefronts g and g + cw work on group g
+    const bool second = wave >= cw;
+    const int slice = second ? wave - cw : wave;
+    wave_ctx cx;
+    cx.lane = lane;
+    cx.hv = lane & 7;
+    cx.R = reinterpret_cast<const uint16_t *>(smem);
+    cx.rank_val = reinterpret_cast<const double *>(smem + LDS_RANK_BYTES);
+    cx.Wdp = nullptr;
+    cx.Wpp = nullptr;
+    cx.wl = smem + LDS_TABLES + slice * wave_lds_bytes(NC, false);
+    unsigned char *wl = cx.wl;
+    const size_t grp = (size_t)blockIdx.x * cw + slice;
+    // ---- set-up: rank table and rank values by all; a1: the group's rows by its first wavefront ----
+#pragma unroll 2
+    for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x) {
+        const int row = i / (NDEV / 2), col2 = i - row * (NDEV / 2);
+        reinterpret_cast<uint32_t *>(smem)[row * (RSTRIDE / 2) + col2] = reinterpret_cast<const uint32_t *>(rank_tab)[i];
+    }
+#pragma unroll 4
+    for (int i = threadIdx.x; i < NDEV * NDEV / 2; i += blockDim.x)
+        reinterpret_cast<double2 *>(smem + LDS_RANK_BYTES)[i] = reinterpret_cast<const double2 *>(rank_val)[i];
+    if (!second) {
+#pragma unroll
+        for (int c = 0; c < NC; c++) {
+            size_t cand = grp * NC + c;
+            if (cand >= P) cand = P - 1;   // ragged tail: recompute the last row, never stored
+            wl[OFF_PB + c * 64 + lane] = (unsigned char)perm[cand * NDEV + lane];
+        }
+    }
+    __syncthreads();
+    uint16_t *ghr16 = reinterpret_cast<uint16_t *>(wl + off_ghr(NC));
+    double *res = reinterpret_cast<double *>(wl + off_res(NC));
+    {   // ---- a4: candidates 0, 1 by the first wavefront, 2, 3 by the second; lanes 2 t, 2 t + 1 share couple t ----
+        int t = lane >> 1;
+        const bool valid = t < 28 && !(lane & 1);
+        if (t >= 28) t = 27;   // idle lanes repeat the last item and write nothing
+        const int mc = (second ? 2 : 0) + t / 14, q = t % 14;
+        int j1[2], j2[2];
+        pair8_decode(2 * q, j1[0], j2[0]);
+        pair8_decode(2 * q + 1, j1[1], j2[1]);
+        const uint32_t gfull = match_couple_halves(cx, wl + OFF_PB + mc * 64, j1, j2);
+        if (valid) {
+            ghr16[mc * 28 + pair_index(j1[0], j2[0])] = (uint16_t)gfull;
+            ghr16[mc * 28 + pair_index(j1[1], j2[1])] = (uint16_t)(gfull >> 16);
+        }
+    }
+    __syncthreads();
+    const int hc = (lane >> 3) & 3;
+    if (second) {
+        // ---- a2/a3: DataP of the four candidates, lane = (candidate, stage) ----
+        double dp = stage_datap(W_dp, *reinterpret_cast<const uint2 *>(wl + OFF_PB + hc * 64 + 8 * cx.hv));
+        dp = fmax(dp, dpp_move<DPP_XOR1>(dp));
+        dp = fmax(dp, dpp_move<DPP_XOR2>(dp));
+        dp = fmax(dp, dpp_move<DPP_HALF_MIRROR>(dp));
+        if (cx.hv == 0 && lane < NC * 8) res[NC + hc] = dp;
+        if (ghat_out != nullptr) {
+            const int u = lane >> 3, v = lane & 7;
+            const int pi = pair_index(u < v ? u : v, u < v ? v : u);
+#pragma nounroll
+            for (int c = 0; c < NC; c++)
+                if (grp * NC + c < P) ghat_out[(grp * NC + c) * 64 + lane] = u == v ? 0.0 : cx.rank_val[ghr16[c * 28 + pi]];
+        }
+        __syncthreads();
+        return;
+    }
+    // ---- a5: Held-Karp in registers, the two halves of the wavefront sharing each candidate (see hk_registers) ----
+    const bool relabel = lane >= 32;
+    const int v = relabel ? hk_swap01(cx.hv) : cx.hv;
+    double G[8];
+    G[0] = 0.0;
+#pragma unroll
+    for (int d = 1; d < 8; d++) {
+        const int u = v ^ (relabel ? hk_swap01(d) : d);
+        G[d] = cx.rank_val[ghr16[hc * 28 + pair_index(u < v ? u : v, u < v ? v : u)]];
+    }
+    const double pp = hk_registers<true>(G, lane);
+    __syncthreads();
+    // ---- a6 ----
+    const size_t cand = grp * NC + hc;
+    if (cx.hv == 0 && lane < NC * 8 && cand < P) {
+        const double dp = res[NC + hc];
+        if (cost != nullptr) cost[cand] = __dadd_rn(dp, pp);
+        if (datap_out != nullptr) datap_out[cand] = dp;
+    }
+}
+
 // W_pp[a][b], a != b, for the proposals: from the LDS copy where there is one; with 32 candidates per
 // wavefront (no room for it) through the rank tables, rank_val[rank[a][b]] being the same bits.
 template <int NC>
@@ -592,6 +694,8 @@ int dtfm_fast64_prepare(dtfm_problem *pr)
                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(8, false)));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64<4>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(4, false)));
+    DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_eval_fast64_paired),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(4, false)));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<32, false>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_total(32, true)));
     DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_ls_gain4_fast64<8, false>),
@@ -669,6 +773,16 @@ int dtfm_fast64_enqueue(const dtfm_problem *pr, const int32_t *perm, size_t rows
         if (rc != DTFM_OK) return rc;
         return dtfm_fast64_enqueue(pr, perm + head * NDEV, rows - head, cost ? cost + head : nullptr,
                                    ghat ? ghat + head * 64 : nullptr, datap ? datap + head : nullptr, st);
+    }
+    const size_t passes4 = (rows + 3) / 4;
+    if (group_size(pr, rows) == 4 && passes4 <= 4 * (size_t)pr->f64_grid) {
+        // one group of four per SIMD at most: a pair of wavefronts per group
+        const int cw = passes4 > 2 * (size_t)pr->f64_grid ? 4 : 2;
+        hipLaunchKernelGGL(k_eval_fast64_paired, dim3((unsigned)((passes4 + cw - 1) / cw)), dim3(2 * cw * 64),
+                           lds_total(4, false, cw), st, pr->W_dp, pr->f64_rank, pr->f64_rank_val, perm, rows, cost, ghat,
+                           datap);
+        DTFM_HIP(hipGetLastError());
+        return DTFM_OK;
     }
     switch (group_size(pr, rows)) {
     case 32: launch_eval<32>(pr, perm, rows, cost, ghat, datap, st); break;

@@ -28,6 +28,14 @@ def host(t):
     return t.cpu().numpy()
 
 
+def oracle_eval_threaded(o, perms, threads=16):
+    """The oracle's eval_population over host threads (candidates are independent; ctypes releases the GIL)."""
+    from concurrent.futures import ThreadPoolExecutor
+    chunks = [c for c in np.array_split(perms, threads * 2) if len(c)]
+    with ThreadPoolExecutor(threads) as ex:
+        return np.concatenate(list(ex.map(o.eval_population, chunks)))
+
+
 def assert_costs_equal(gpu, ref):
     """spec bar: 1e-9 relative; the build's own bar: identical bits."""
     gpu, ref = np.asarray(gpu), np.asarray(ref)

@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2206_01288_amd as dtfm
 import workloads
-from tests.gpu_util import assert_costs_equal, both, custom, dev, host
+from tests.gpu_util import assert_costs_equal, both, custom, dev, host, oracle_eval_threaded
 
 pytestmark = pytest.mark.gpu
 
@@ -123,30 +123,49 @@ def test_config2_roofline_launch_size_sampled():
     assert_costs_equal(c[7, idx], o.eval_population(base[idx]))
 
 
-def test_config4_full_population_sampled():
+def test_config4_full_population_every_row():
+    # the configured launch (1024 candidates, D_pp = 16: blocked Held-Karp, 16 x 16 matchings): every row against the oracle
     w = workloads.config("C4")
     o, g = both(w)
     perms = workloads.random_population(1024, 256, seed=1)
     c = host(dtfm.eval_population(g, dev(perms)))
-    idx = np.random.default_rng(0).choice(1024, size=48, replace=False)
-    assert_costs_equal(c[idx], o.eval_population(perms[idx]))
-    # properties that hold for every row: reversal of the pipeline keeps the bits
+    ref = oracle_eval_threaded(o, perms)
+    assert_costs_equal(c, ref)
+    assert int(np.argmin(c)) == int(np.argmin(ref))
+    # reversal of the pipeline keeps the bits
     rev = perms.reshape(1024, 16, 16)[:, ::-1, :].reshape(1024, 256).copy()
     assert np.array_equal(host(dtfm.eval_population(g, dev(rev))), c)
 
 
-def test_config5_population_sampled():
+def test_config5_population_every_row_of_256():
+    # 256 candidates of configuration 5 (64 x 64 matchings, sliced DataP, blocked Held-Karp): every row against the oracle
     w = workloads.config("C5")
     o, g = both(w)
     perms = workloads.random_population(256, 1024, seed=1)
     dperm = dev(perms)
     c = host(dtfm.eval_population(g, dperm))
-    idx = [0, 1, 100, 255]
-    assert_costs_equal(c[idx], o.eval_population(perms[idx]))
+    ref = oracle_eval_threaded(o, perms)
+    assert_costs_equal(c, ref)
+    assert int(np.argmin(c)) == int(np.argmin(ref))
     ghat, datap = dtfm.coarsened_graph(g, dperm[:2].contiguous())
     assert np.array_equal(host(ghat)[1], o.coarsen(perms[1]))
     rev = perms.reshape(256, 16, 64)[:, ::-1, :].reshape(256, 1024).copy()
     assert np.array_equal(host(dtfm.eval_population(g, dev(rev))), c)
+
+
+def test_config5_full_population_launch_sampled():
+    # the configured launch of configuration 5 (4096 candidates): the rows of the 256-candidate launch above, placed
+    # across the large one, give the same bits; 32 more rows against the oracle
+    w = workloads.config("C5")
+    o, g = both(w)
+    small = workloads.random_population(256, 1024, seed=1)
+    perms = workloads.random_population(4096, 1024, seed=2)
+    where = np.arange(256) * 16 + 7
+    perms[where] = small
+    c = host(dtfm.eval_population(g, dev(perms)))
+    assert np.array_equal(c[where], host(dtfm.eval_population(g, dev(small))))
+    idx = np.random.default_rng(5).choice(4096, size=32, replace=False)
+    assert_costs_equal(c[idx], oracle_eval_threaded(o, perms[idx]))
 
 
 @pytest.mark.parametrize("D_dp,D_pp", [(1, 1), (1, 5), (5, 1), (2, 2), (3, 4), (7, 3), (4, 9), (3, 10),

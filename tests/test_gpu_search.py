@@ -326,6 +326,53 @@ def test_config5_full_size_generations():
     assert cost[0] < rand.min()
 
 
+def _read_c5_golden():
+    """tests/golden/c5_evolve_seed7_P4096.txt, written by tests/golden/make_c5_trace.py from the CPU oracle."""
+    import os
+    import struct
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "c5_evolve_seed7_P4096.txt")
+    unhex = lambda t: struct.unpack("<d", struct.pack("<Q", int(t, 16)))[0]
+    meta, gens, costs, in_costs = {}, {}, [], False
+    with open(path) as f:
+        for ln in f:
+            t = ln.split()
+            if not t or t[0].startswith("#"):
+                continue
+            if in_costs:
+                costs += [unhex(x) for x in t]
+            elif t[0] == "generation":
+                gens[int(t[1])] = {"best": unhex(t[3]), "pop": t[5], "cost": t[7]}
+            elif t[0] == "best_trace":
+                meta["trace"] = np.array([unhex(x) for x in t[1:]])
+            elif t[0] == "final_costs":
+                in_costs = True
+            else:
+                meta[t[0]] = t[1]
+    return meta, gens, np.array(costs)
+
+
+def test_config5_trajectory_against_stored_oracle_run():
+    # configuration 5 at its population (4096, Philox seed 7, 8 rounds of the four-candidate local search): the first
+    # generations against the run of the CPU oracle stored under tests/golden (initial population, every generation's
+    # population and costs by their SHA-256, the best-cost trace and the final costs bit for bit)
+    import hashlib
+    meta, gens, final_costs = _read_c5_golden()
+    G, P = int(meta["generations"]), int(meta["population"])
+    assert (int(meta["seed"]), P, int(meta["ls_moves"]), meta["neighbourhood"]) == (7, 4096, 8, "GAIN4") and G >= 2
+    w = workloads.config("C5")
+    _, g = both(w)
+    sha = lambda a: hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()
+    for gen in range(0, G + 1):
+        pop, cost, trace = dtfm.evolve(g, 7, gen, P, ls_moves=8, neighbourhood=dtfm.GAIN4)
+        pop, cost, trace = host(pop), host(cost), host(trace)
+        want = gens[gen - 1]
+        assert pop.dtype == np.int32 and cost.dtype == np.float64
+        assert sha(pop) == want["pop"], "population after generation %d" % (gen - 1)
+        assert sha(cost) == want["cost"], "costs after generation %d" % (gen - 1)
+        assert cost.min() == want["best"]
+    assert np.array_equal(trace, meta["trace"]) and np.array_equal(cost, final_costs)
+
+
 def test_search_calls_are_ordered_on_a_side_stream():
     # local_search, evolve and move_costs enqueue on the caller's current stream: work queued behind them
     # on that stream sees their results, and the results equal those of the default stream
