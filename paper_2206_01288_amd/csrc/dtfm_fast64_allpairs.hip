@@ -30,7 +30,8 @@ constexpr int AP_EDGE_SCR_ODD = 128 + 1024;            //   [mv]        the same
 constexpr int AP_OFF_F = AP_OFF_EDGE + (128 + 1024) * 2;   // u16 [j][k][i][c]
 constexpr int AP_OFF_DPM = AP_OFF_F + 8 * 8 * 8 * 8 * 2;   // double [64]: DataP after swap mv
 constexpr int AP_OFF_DPB = AP_OFF_DPM + 64 * 8;            // double [8]: DataP of every stage of the current row
-constexpr int AP_WAVE_BYTES = AP_OFF_DPB + 64;
+constexpr int AP_OFF_LIST = AP_OFF_DPB + 64;               // u8 [64]: the swaps of the batch that can still win
+constexpr int AP_WAVE_BYTES = AP_OFF_LIST + 64;
 constexpr int AP_LDS_TOTAL = LDS_TABLES + WAVES_PER_BLOCK * AP_WAVE_BYTES;
 static_assert(AP_OFF_F % 16 == 0 && AP_OFF_DPM % 8 == 0 && AP_WAVE_BYTES % 16 == 0, "alignment");
 static_assert(AP_LDS_TOTAL <= 160 * 1024, "LDS budget of a CU");
@@ -93,6 +94,7 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
     uint16_t *F = reinterpret_cast<uint16_t *>(wl + AP_OFF_F);
     double *dpm = reinterpret_cast<double *>(wl + AP_OFF_DPM);
     double *dpb = reinterpret_cast<double *>(wl + AP_OFF_DPB);
+    unsigned char *list = wl + AP_OFF_LIST;
     const int hm = lane >> 3, hv = lane & 7;   // Held-Karp role: swap slot within the pass, stage
 
     const int wpb = blockDim.x >> 6;   // wavefronts per workgroup: WAVES_PER_BLOCK, fewer when there are few rows
@@ -142,79 +144,121 @@ k_ls_allpairs_fast64(const double *__restrict__ W_dp, const uint16_t *__restrict
 #pragma unroll
             for (int k = 1; k < 8; k++) dp_base = fmax(dp_base, dpb[k]);
 
-            double bestc = INFINITY, pp_base = 0.0;
+            double bestc = INFINITY;
             uint32_t bestk = 0xFFFFFFFFu;   // key = 64 a + b of positions a < b: the order of the move indices
-            const int n_it = 1 + 28 * 8;
-            int j = 99, jp = 99;   // no stage: the first pass prices the row itself
-#pragma nounroll
-            for (int it = 0; it < n_it; it++) {
-                // it = 0: Held-Karp of the row itself; then 28 batches (j < j') of 8 passes of 8 swaps
-                const int bpass = (it - 1) & 7, batch = (it - 1) >> 3;
-                if (it > 0 && bpass == 0) {
-                    pair8_decode(batch, j, jp);
-                    const uint2 cj = *reinterpret_cast<const uint2 *>(cur + 8 * j), cjp = *reinterpret_cast<const uint2 *>(cur + 8 * jp);
-                    const int i = lane >> 3, ip = lane & 7;            // this lane's swap mv = lane
-                    const uint32_t x = byte_at(cj, i), y = byte_at(cjp, ip);
-                    // edges (j,k) and (j',k) with one row replaced
-#pragma nounroll
-                    for (int k = 0; k < 8; k++) {
-                        if (k == j || k == jp) continue;
-                        const uint2 ck = *reinterpret_cast<const uint2 *>(cur + 8 * k);
-                        edge[AP_EDGE_REP + lane * 8 + k] = (uint16_t)replaced_row(R, F + ((j * 8 + k) * 8 + i) * 8, y, ck);
-                        edge[AP_EDGE_REP + (64 + lane) * 8 + k] = (uint16_t)replaced_row(R, F + ((jp * 8 + k) * 8 + ip) * 8, x, ck);
-                    }
-                    // edge (j,j'), for this batch and the next one at once (every other batch): lanes 0..31 take
-                    // this batch's swaps 2 l and 2 l + 1 (same i, i' and i' + 1), lanes 32..63 the next batch's
-                    if ((batch & 1) == 0) {
-                        const int l = lane & 31, si = l >> 2, sp = 2 * (l & 3);
-                        int sj = j, sjp = jp;
-                        if (lane >= 32) pair8_decode(batch + 1 < 28 ? batch + 1 : batch, sj, sjp);
-                        const uint2 scj = *reinterpret_cast<const uint2 *>(cur + 8 * sj), scjp = *reinterpret_cast<const uint2 *>(cur + 8 * sjp);
-                        const uint32_t sx = byte_at(scj, si);
-                        const uint2 rowdev[2] = {put_byte(scj, si, byte_at(scjp, sp)), put_byte(scj, si, byte_at(scjp, sp + 1))};
-                        const uint2 coldev[2] = {put_byte(scjp, sp, sx), put_byte(scjp, sp + 1, sx)};
-                        uint32_t G[256];
-                        match_rows<8, false>(R, rowdev, coldev, G);
-                        reinterpret_cast<uint32_t *>(edge + (lane < 32 ? AP_EDGE_SCR : AP_EDGE_SCR_ODD))[l] = G[255];
-                    }
-                    // DataP after the swap
-                    {
-                        double d = fmax(stage_datap(Wdp, put_byte(cj, i, y)), stage_datap(Wdp, put_byte(cjp, ip, x)));
-#pragma unroll
-                        for (int k = 0; k < 8; k++)
-                            if (k != j && k != jp) d = fmax(d, dpb[k]);
-                        dpm[lane] = d;
-                    }
-                    WAVE_LDS_SYNC();
-                }
-                const int mv = bpass * 8 + hm;
+            // Held-Karp of the row itself (every group of 8 lanes computes the same)
+            double pp_base;
+            {
                 double G[8];
                 G[0] = 0.0;
 #pragma unroll
-                for (int d = 1; d < 8; d++) {
-                    const int u = hv ^ d;
-                    // which edge rank this is: the (j,j') edge after the swap, an edge of j or j' with a row
-                    // replaced, or an edge of the row's own coarsened graph (always, when it = 0: j = j' = 99)
-                    const bool vj = hv == j, uj = u == j, vjp = hv == jp, ujp = u == jp;
-                    int e = AP_EDGE_GBM + hv * 8 + u;
-                    e = (vjp || ujp) ? AP_EDGE_REP + (64 + mv) * 8 + (vjp ? u : hv) : e;
-                    e = (vj || uj) ? AP_EDGE_REP + mv * 8 + (vj ? u : hv) : e;
-                    e = ((vj && ujp) || (vjp && uj)) ? ((batch & 1) ? AP_EDGE_SCR_ODD : AP_EDGE_SCR) + mv : e;
-                    G[d] = rank_val[edge[e]];
-                }
-                const double pp = hk_registers<false>(G, lane);
-                if (it == 0) {
-                    pp_base = pp;
-                } else {
-                    const double total = __dadd_rn(dpm[mv], pp);
-                    const uint32_t a = 8 * j + (mv >> 3), b = 8 * jp + (mv & 7);
-                    keep_best(bestc, bestk, total, 64 * a + b);
-                    if (move_cost != nullptr && hv == 0)
-                        move_cost[cand * (size_t)N_MOVES + (a * NDEV - a * (a + 1) / 2 + (b - a - 1))] = total;
-                    if (bpass == 7) WAVE_LDS_SYNC();   // the next batch overwrites the slice
-                }
+                for (int d = 1; d < 8; d++) G[d] = rank_val[edge[AP_EDGE_GBM + hv * 8 + (hv ^ d)]];
+                pp_base = hk_registers<false>(G, lane);
             }
             cur_cost = __dadd_rn(dp_base, pp_base);
+            const bool prune = move_cost == nullptr;   // pricing every swap: nothing may be left out
+            // 28 batches (j < j') of 64 swaps; Held-Karp takes eight swaps per pass
+#pragma nounroll
+            for (int batch = 0; batch < 28; batch++) {
+                int j, jp;
+                pair8_decode(batch, j, jp);
+                const uint2 cj = *reinterpret_cast<const uint2 *>(cur + 8 * j), cjp = *reinterpret_cast<const uint2 *>(cur + 8 * jp);
+                const int i = lane >> 3, ip = lane & 7;            // this lane's swap mv = lane
+                const uint32_t x = byte_at(cj, i), y = byte_at(cjp, ip);
+                // edges (j,k) and (j',k) with one row replaced
+#pragma nounroll
+                for (int k = 0; k < 8; k++) {
+                    if (k == j || k == jp) continue;
+                    const uint2 ck = *reinterpret_cast<const uint2 *>(cur + 8 * k);
+                    edge[AP_EDGE_REP + lane * 8 + k] = (uint16_t)replaced_row(R, F + ((j * 8 + k) * 8 + i) * 8, y, ck);
+                    edge[AP_EDGE_REP + (64 + lane) * 8 + k] = (uint16_t)replaced_row(R, F + ((jp * 8 + k) * 8 + ip) * 8, x, ck);
+                }
+                // edge (j,j'), for this batch and the next one at once (every other batch): lanes 0..31 take
+                // this batch's swaps 2 l and 2 l + 1 (same i, i' and i' + 1), lanes 32..63 the next batch's
+                if ((batch & 1) == 0) {
+                    const int l = lane & 31, si = l >> 2, sp = 2 * (l & 3);
+                    int sj = j, sjp = jp;
+                    if (lane >= 32) pair8_decode(batch + 1 < 28 ? batch + 1 : batch, sj, sjp);
+                    const uint2 scj = *reinterpret_cast<const uint2 *>(cur + 8 * sj), scjp = *reinterpret_cast<const uint2 *>(cur + 8 * sjp);
+                    const uint32_t sx = byte_at(scj, si);
+                    const uint2 rowdev[2] = {put_byte(scj, si, byte_at(scjp, sp)), put_byte(scj, si, byte_at(scjp, sp + 1))};
+                    const uint2 coldev[2] = {put_byte(scjp, sp, sx), put_byte(scjp, sp + 1, sx)};
+                    uint32_t G[256];
+                    match_rows<8, false>(R, rowdev, coldev, G);
+                    reinterpret_cast<uint32_t *>(edge + (lane < 32 ? AP_EDGE_SCR : AP_EDGE_SCR_ODD))[l] = G[255];
+                }
+                // DataP after the swap
+                double dp_swap = fmax(stage_datap(Wdp, put_byte(cj, i, y)), stage_datap(Wdp, put_byte(cjp, ip, x)));
+#pragma unroll
+                for (int k = 0; k < 8; k++)
+                    if (k != j && k != jp) dp_swap = fmax(dp_swap, dpb[k]);
+                dpm[lane] = dp_swap;
+                WAVE_LDS_SYNC();
+                const int scr = (batch & 1) ? AP_EDGE_SCR_ODD : AP_EDGE_SCR;
+                // rank of edge (v, u) of the coarsened graph after swap mv: the (j,j') edge, an edge of j or j' with a
+                // row replaced, or an edge of the row's own graph
+                auto edge_index = [&](int mv, int v, int u) -> int {
+                    const bool vj = v == j, uj = u == j, vjp = v == jp, ujp = u == jp;
+                    int e = AP_EDGE_GBM + v * 8 + u;
+                    e = (vjp || ujp) ? AP_EDGE_REP + (64 + mv) * 8 + (vjp ? u : v) : e;
+                    e = (vj || uj) ? AP_EDGE_REP + mv * 8 + (vj ? u : v) : e;
+                    e = ((vj && ujp) || (vjp && uj)) ? scr + mv : e;
+                    return e;
+                };
+                // ---- which swaps can still win: a lower bound on the cost after the swap against the cheapest so far ----
+                // A path over the 8 stages gives each stage but its first an edge of its own (the one it is entered by),
+                // each at least the stage's cheapest edge m_v, so Eq. 4 is at least sum_v m_v - max_v m_v; every rounded
+                // path sum is within 7 roundings below its exact value and the bound is a sum of 7 non-negative terms,
+                // within 7 roundings above its own, which the factor below more than covers. fl is monotone, so fl(DataP + bound) <= the swap's cost: a swap
+                // whose bound is strictly above the cheapest cost so far (or the row's own) can neither be applied nor
+                // tie with the winner, and is left out.
+                int cnt = 64;
+                if (prune) {
+                    double thr = bestc;
+#pragma unroll
+                    for (int o = 32; o >= 1; o >>= 1) thr = fmin(thr, __shfl_xor(thr, o));
+                    thr = fmin(thr, cur_cost);
+                    double sum = 0.0, mx = 0.0;   // sum of the m_v but the largest, which stays in mx: no cancellation
+#pragma unroll
+                    for (int v = 0; v < 8; v++) {
+                        uint32_t m = 0xFFFFu;
+#pragma unroll
+                        for (int u = 0; u < 8; u++)
+                            if (u != v) m = min(m, (uint32_t)edge[edge_index(lane, v, u)]);
+                        const double mw = rank_val[m];
+                        if (v == 0) {
+                            mx = mw;
+                        } else {
+                            sum = __dadd_rn(sum, fmin(mx, mw));
+                            mx = fmax(mx, mw);
+                        }
+                    }
+                    const double bound = __dadd_rn(dp_swap, __dmul_rn(sum, 1.0 - 1e-12));
+                    const bool keep = !(bound > thr);
+                    const uint64_t mask = __ballot(keep);
+                    cnt = __popcll(mask);
+                    const int rank = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                    if (keep) list[rank] = (unsigned char)lane;
+                    WAVE_LDS_SYNC();
+                }
+#pragma nounroll
+                for (int pass = 0; pass * 8 < cnt; pass++) {
+                    const int slot = pass * 8 + hm;
+                    const bool valid = slot < cnt;
+                    const int mv = prune ? list[valid ? slot : cnt - 1] : slot;
+                    double G[8];
+                    G[0] = 0.0;
+#pragma unroll
+                    for (int d = 1; d < 8; d++) G[d] = rank_val[edge[edge_index(mv, hv, hv ^ d)]];
+                    const double pp = hk_registers<false>(G, lane);
+                    const double total = __dadd_rn(dpm[mv], pp);
+                    const uint32_t a = 8 * j + (mv >> 3), b = 8 * jp + (mv & 7);
+                    if (valid) keep_best(bestc, bestk, total, 64 * a + b);
+                    if (move_cost != nullptr && hv == 0)
+                        move_cost[cand * (size_t)N_MOVES + (a * NDEV - a * (a + 1) / 2 + (b - a - 1))] = total;
+                }
+                WAVE_LDS_SYNC();   // the next batch overwrites the slice
+            }
             // ---- swaps inside a stage: only the order of that stage's sums changes ----
 #pragma nounroll
             for (int pass = 0; pass < 4; pass++) {
