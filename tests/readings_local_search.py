@@ -38,13 +38,14 @@ def _swap(perm, a, b):
 
 
 class Run:
-    def __init__(self, name, budget):
+    def __init__(self, name, budget, generations=0):
         w = workloads.config(name)
         self.w = w
         self.pr = oracle.Problem(w.latency, w.bandwidth, w.c_dp, w.c_pp, w.D_dp, w.D_pp)
         self.pairs = list(itertools.combinations(range(w.D_pp), 2))
         self.evals = 0
         self.budget = budget
+        self.generations = generations   # > 0: stop after that many generations instead of at the budget
 
     def cost(self, perm):
         self.evals += 1
@@ -130,14 +131,14 @@ class Run:
         pop = np.stack([oracle.init_candidate(seed, k, w.N) for k in range(P)])
         cost = np.array([self.cost(p) for p in pop])
         g = 0
-        while self.evals < self.budget:
+        while (g < self.generations) if self.generations > 0 else (self.evals < self.budget):
             off, oc = [], []
             for k in range(P):
                 child = oracle.make_offspring(seed, g, k, pop, w.D_dp, w.N // 4, 1)[0]
                 child, c = ls(child, self.cost(child))
                 off.append(child)
                 oc.append(c)
-                if self.evals >= self.budget:
+                if self.generations <= 0 and self.evals >= self.budget:
                     break
             allp = np.concatenate([pop, np.stack(off)])
             allc = np.concatenate([cost, np.array(oc)])
@@ -148,10 +149,10 @@ class Run:
 
 
 def one(args):
-    name, variant, seed, budget, P = args
-    run = Run(name, budget)
+    name, variant, seed, budget, P, gens = args
+    run = Run(name, budget, gens)
     best, gens = run.evolve(seed, P, getattr(run, "ls_" + variant.replace("-", "_")))
-    return name, variant, seed, best, gens
+    return name, variant, seed, best, gens, run.evals
 
 
 def main():
@@ -160,20 +161,26 @@ def main():
     ap.add_argument("--population", type=int, default=64)
     ap.add_argument("--procs", type=int, default=6)
     ap.add_argument("--networks", default="C2b,C2")
+    ap.add_argument("--generations", type=int, default=0, help="> 0: the same number of generations (offspring) for every "
+                    "reading instead of the same number of evaluations")
     args = ap.parse_args()
     variants = ["none", "gain4", "gain4-sweep", "best4", "global", "kl"]
-    jobs = [(n, v, s, args.budget, args.population) for n in args.networks.split(",") for v in variants for s in (0, 1, 2)]
+    jobs = [(n, v, s, args.budget, args.population, args.generations) for n in args.networks.split(",") for v in variants for s in (0, 1, 2)]
     with ProcessPoolExecutor(args.procs) as ex:
         res = list(ex.map(one, jobs))
-    print("budget %d evaluations, population %d" % (args.budget, args.population))
+    if args.generations > 0:
+        print("%d generations each, population %d" % (args.generations, args.population))
+    else:
+        print("budget %d evaluations, population %d" % (args.budget, args.population))
     for n in args.networks.split(","):
         rand = Run(n, 0)
         rc = [rand.pr.comm_cost(p) for p in workloads.random_population(1024, rand.w.N, seed=9)]
         print("%s: random allocations mean %.3f, best of 1024 %.3f" % (n, np.mean(rc), np.min(rc)))
         for v in variants:
             rows = [r for r in res if r[0] == n and r[1] == v]
-            print("  %-12s best cost mean %.3f  (seeds: %s; generations %s)" % (
-                v, np.mean([r[3] for r in rows]), " ".join("%.3f" % r[3] for r in rows), " ".join(str(r[4]) for r in rows)))
+            print("  %-12s best cost mean %.3f  (seeds: %s; generations %s; evaluations %s)" % (
+                v, np.mean([r[3] for r in rows]), " ".join("%.3f" % r[3] for r in rows), " ".join(str(r[4]) for r in rows),
+                " ".join(str(r[5]) for r in rows)))
 
 
 if __name__ == "__main__":
