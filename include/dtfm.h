@@ -84,7 +84,7 @@ int dtfm_eval_population(dtfm_problem *prob, const int32_t *perm, int P, double 
  * D_pp > 10 the Held-Karp exchange areas) lie in a fixed area of DTFM_FIXED_SCRATCH_BYTES that is
  * part of the library's device image (every GPU the library is used on holds one copy until the
  * process ends). The call allocates and frees nothing and does not synchronise. It needs
- * 8 (1 + D_pp^2) bytes per candidate (rounded up to 256-byte pieces), and for D_pp > 10 at least
+ * 8 (1 + D_pp^2) + 12 bytes per candidate (in pieces rounded up to 256 bytes), and for D_pp > 10 at least
  * one exchange area of 8 (D_pp - 10) 2^D_pp bytes behind that (3 MiB at D_pp = 16; as many areas
  * as fit are used, one per workgroup, so the Held-Karp step runs on fewer workgroups than in
  * dtfm_eval_population); a larger P returns DTFM_ERR_TOO_LARGE and enqueues nothing. The 64-device

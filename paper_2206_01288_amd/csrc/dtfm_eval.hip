@@ -296,13 +296,18 @@ k_match(const uint32_t *__restrict__ Wr, const double *__restrict__ rank_val,
 template <bool LDS_TABLE>
 __global__ void k_held_karp(const double *__restrict__ ghat, const double *__restrict__ datap, int n,
                             const uint32_t *__restrict__ subsets, dtfm_layer_off lo,
-                            double *__restrict__ tab_global, double *__restrict__ cost, size_t P)
+                            double *__restrict__ tab_global, double *__restrict__ cost, size_t P,
+                            const int32_t *__restrict__ list, const int32_t *__restrict__ count,
+                            double *__restrict__ pp_out)
 {
     extern __shared__ double smem[];
     double *G = smem;
     double *tab = LDS_TABLE ? smem + n * n : tab_global + (size_t)blockIdx.x * ((size_t)n << n);
     const uint32_t full = (1u << n) - 1u;
-    for (size_t p = blockIdx.x; p < P; p += gridDim.x) {
+    // with a list: only the rows list[0 .. *count)
+    const size_t todo = list != nullptr ? (size_t)*count : P;
+    for (size_t idx = blockIdx.x; idx < todo; idx += gridDim.x) {
+        const size_t p = list != nullptr ? (size_t)list[idx] : idx;
         for (int e = threadIdx.x; e < n * n; e += blockDim.x) G[e] = ghat[p * n * n + e];
         for (int v = threadIdx.x; v < n; v += blockDim.x) tab[((size_t)1 << v) * n + v] = 0.0;
         __syncthreads();
@@ -329,6 +334,7 @@ __global__ void k_held_karp(const double *__restrict__ ghat, const double *__res
             double m = INFINITY;
             for (int v = 0; v < n; v++) m = fmin(m, tab[(size_t)full * n + v]);
             cost[p] = __dadd_rn(datap[p], m);
+            if (pp_out != nullptr) pp_out[p] = m;
         }
         __syncthreads();
     }
@@ -395,7 +401,8 @@ __device__ __forceinline__ void hk_block_layers(double *tab, const uint16_t *lsu
 template <int NL, int NPAIR>
 __global__ void __launch_bounds__(1 << NL)
 k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ datap, int n,
-                    double *__restrict__ xchg, double *__restrict__ cost, size_t P)
+                    double *__restrict__ xchg, double *__restrict__ cost, size_t P,
+                    const int32_t *__restrict__ list, const int32_t *__restrict__ count, double *__restrict__ pp_out)
 {
     // rows are RS = 18 doubles apart (144 B = 36 banks): the same slot of 16 consecutive rows falls
     // into 16 different bank pairs, and the 128-bit row reads stay aligned
@@ -426,7 +433,9 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
                 if (j <= NL) acc += dtfm_binom10[NL][j];
             }
     }
-    for (size_t p = blockIdx.x; p < P; p += gridDim.x) {
+    const size_t todo = list != nullptr ? (size_t)*count : P;   // with a list: only the rows list[0 .. *count)
+    for (size_t idx = blockIdx.x; idx < todo; idx += gridDim.x) {
+        const size_t p = list != nullptr ? (size_t)list[idx] : idx;
         __syncthreads();
         for (int e = threadIdx.x; e < 256; e += THREADS) {
             const int a = e >> 4, b = e & 15;
@@ -481,9 +490,46 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
             double m = INFINITY;
             for (int u = 0; u < n; u++) m = fmin(m, tab[(ROWS - 1) * RS + u]);
             cost[p] = __dadd_rn(datap[p], m);
+            if (pp_out != nullptr) pp_out[p] = m;
         }
     }
 }
+
+// Trial evaluations of the local search (Sec. 3.4): settles, without Held-Karp, the trials whose coarsened graph
+// says enough. Eq. 4 depends on the graph only, so a trial whose graph equals its current row's has the same
+// PipelineP-Cost: cost = fl(DataP' + pp_cur), the bits Held-Karp would give. Every path sum is monotone in every
+// edge (fl(x + w) is), hence so is Eq. 4: a trial whose graph is nowhere below the current one has
+// PipelineP >= pp_cur, and if fl(DataP' + pp_cur) already reaches the current cost the trial cannot be strictly
+// cheaper: it is rejected, which is all the search needs of it (its cost is set to +inf). The other trials go on the
+// list for Held-Karp. One wavefront per trial; *count must be zero on entry.
+__global__ void k_trial_shortcut(const double *__restrict__ ghat, const double *__restrict__ datap, int nn,
+                                 const double *__restrict__ ghat_cur, const double *__restrict__ pp_cur,
+                                 const double *__restrict__ cur, double *__restrict__ cost, double *__restrict__ pp_out,
+                                 int32_t *__restrict__ list, int32_t *__restrict__ count, size_t rows)
+{
+    const size_t p = (size_t)blockIdx.x * (blockDim.x / DTFM_WAVE) + threadIdx.x / DTFM_WAVE;
+    if (p >= rows) return;   // whole wavefront
+    const int lane = threadIdx.x & (DTFM_WAVE - 1);
+    bool differs = false, below = false;
+    for (int e = lane; e < nn; e += DTFM_WAVE) {
+        const double a = ghat[p * nn + e], b = ghat_cur[p * nn + e];
+        differs |= a != b;
+        below |= a < b;
+    }
+    const bool any_differs = __ballot(differs) != 0ull, any_below = __ballot(below) != 0ull;
+    if (lane != 0) return;
+    const double with_cur = __dadd_rn(datap[p], pp_cur[p]);
+    if (!any_differs) {
+        cost[p] = with_cur;
+        pp_out[p] = pp_cur[p];
+    } else if (!any_below && with_cur >= cur[p]) {
+        cost[p] = INFINITY;
+    } else {
+        list[atomicAdd(count, 1)] = (int32_t)p;
+    }
+}
+
+__global__ void k_zero_count(int32_t *count) { *count = 0; }
 
 size_t dtfm_hk_exchange_bytes(const dtfm_problem *pr)
 {
@@ -505,6 +551,9 @@ dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t ro
         b.hk_grid = rows < cap ? rows : cap;
         b.hk_tab = ar.take<double>(b.hk_grid * (dtfm_hk_exchange_bytes(pr) / sizeof(double)));
     }
+    b.pp = ar.take<double>(rows);
+    b.list = ar.take<int32_t>(rows);
+    b.count = ar.take<int32_t>(1);
     return b;
 }
 
@@ -517,7 +566,7 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
 // As dtfm_eval_enqueue; with inc_j >= 0 (inc_j < inc_jp) b.ghat already holds the coarsened graphs of rows
 // that differ from `perm` only in stages inc_j and inc_jp: only the edges of those two stages are matched again.
 int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int32_t *perm, size_t rows,
-                          double *cost, int inc_j, int inc_jp, hipStream_t st)
+                          double *cost, int inc_j, int inc_jp, hipStream_t st, const dtfm_trial_ref *ref)
 {
     if (rows == 0) return DTFM_OK;
     if (pr->fast64)
@@ -550,6 +599,16 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
         DTFM_HIP(hipGetLastError());
     }
     if (cost == nullptr) return DTFM_OK;
+    const int32_t *list = nullptr, *count = nullptr;
+    if (ref != nullptr) {   // trials of the local search: Held-Karp only where the coarsened graph does not settle the trial
+        hipLaunchKernelGGL(k_zero_count, dim3(1), dim3(1), 0, st, b.count);
+        DTFM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(k_trial_shortcut, dim3((unsigned)((rows + 3) / 4)), dim3(4 * DTFM_WAVE), 0, st, b.ghat, b.datap,
+                           n * n, ref->ghat_cur, ref->pp_cur, ref->cur, cost, b.pp, b.list, b.count, rows);
+        DTFM_HIP(hipGetLastError());
+        list = b.list;
+        count = b.count;
+    }
     if (n <= DTFM_HK_LDS_MAX_DPP) {
         size_t lds = ((size_t)n * n + ((size_t)n << n)) * sizeof(double);
         int bt = n <= 6 ? 64 : 256;
@@ -557,7 +616,7 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
             DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_held_karp<true>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(k_held_karp<true>, dim3((unsigned)rows), dim3(bt), lds, st, b.ghat, b.datap, n,
-                           pr->hk_subsets, pr->hk_off, (double *)nullptr, cost, rows);
+                           pr->hk_subsets, pr->hk_off, (double *)nullptr, cost, rows, list, count, b.pp);
     } else {
         size_t grid = b.hk_grid;
         constexpr int NL = DTFM_HK_BLOCK_LOW;
@@ -565,7 +624,8 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
         auto kern = n <= 12 ? k_held_karp_blocked<NL, 6> : n <= 14 ? k_held_karp_blocked<NL, 7> : k_held_karp_blocked<NL, 8>;
         DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds));
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(1 << NL), lds, st, b.ghat, b.datap, n, b.hk_tab, cost, rows);
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(1 << NL), lds, st, b.ghat, b.datap, n, b.hk_tab, cost, rows, list,
+                           count, b.pp);
     }
     DTFM_HIP(hipGetLastError());
     return DTFM_OK;

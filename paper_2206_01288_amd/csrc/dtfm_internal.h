@@ -79,6 +79,18 @@ struct dtfm_eval_bufs {
     double *ghat;    // rows * D_pp * D_pp
     double *hk_tab;  // hk_grid exchange areas, or null when the table fits LDS
     size_t hk_grid;  // workgroups of the blocked Held-Karp kernel (each owns one exchange area)
+    double *pp;      // rows: PipelineP-Cost (the Held-Karp value) of every row whose Held-Karp was run
+    int32_t *list;   // rows: the rows whose Held-Karp is still to run (trial evaluations, see dtfm_trial_ref)
+    int32_t *count;  // 1: length of list
+};
+// What a trial evaluation of the local search knows about the rows its trials were made from: with it, a trial
+// whose coarsened graph equals its current row's, or is nowhere below it while DataP + the current PipelineP
+// already reaches the current cost, is settled without Held-Karp (Eq. 4 depends on the graph only, and is
+// monotone in every edge).
+struct dtfm_trial_ref {
+    const double *ghat_cur;   // rows * D_pp * D_pp: coarsened graphs of the current rows
+    const double *pp_cur;     // rows: their PipelineP-Cost
+    const double *cur;        // rows: their cost (Eq. 1)
 };
 // hk_grid_cap: upper limit on the number of exchange areas (0: DTFM_HK_GLOBAL_GRID)
 dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows, size_t hk_grid_cap = 0);
@@ -90,7 +102,7 @@ int dtfm_eval_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int
 // the same when b.ghat already holds the coarsened graphs of rows that differ from `perm` only in stages
 // inc_j < inc_jp (inc_j < 0: plain evaluation): only the edges of those two stages are matched again
 int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const int32_t *perm, size_t rows,
-                          double *cost, int inc_j, int inc_jp, hipStream_t st);
+                          double *cost, int inc_j, int inc_jp, hipStream_t st, const dtfm_trial_ref *ref = nullptr);
 int dtfm_weights_enqueue(const double *lat_dev, const double *bw_dev, int N, double shard,
                          double c_pp, double *W_dp, double *W_pp, hipStream_t st);
 
@@ -149,6 +161,7 @@ struct dtfm_ls_bufs {
     size_t chunk;       // candidates per ALL_PAIRS chunk
     size_t rows;        // rows evaluated per eval call
     double *ghat_cur;   // P * D_pp * D_pp: coarsened graphs of the current rows (GAIN4 / KL rounds)
+    double *pp_cur;     // P: PipelineP-Cost of the current rows (GAIN4 / KL rounds)
     dtfm_eval_bufs ev;
 };
 dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int neighbourhood);

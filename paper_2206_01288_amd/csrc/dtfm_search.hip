@@ -256,11 +256,13 @@ __global__ void k_kl_propose(const double *__restrict__ W_pp, const int32_t *__r
 // GAIN4 / KL rounds: the coarsened graph of an accepted trial row becomes the candidate's current one
 // (runs before k_accept, on the same condition)
 __global__ void k_keep_ghat(const double *__restrict__ tmp_cost, const double *__restrict__ cur, int nn,
-                            const double *__restrict__ ghat_trial, double *__restrict__ ghat_cur)
+                            const double *__restrict__ ghat_trial, double *__restrict__ ghat_cur,
+                            const double *__restrict__ pp_trial, double *__restrict__ pp_cur)
 {
     const size_t p = blockIdx.x;
     if (!(tmp_cost[p] < cur[p])) return;
     for (int e = threadIdx.x; e < nn; e += blockDim.x) ghat_cur[p * nn + e] = ghat_trial[p * nn + e];
+    if (threadIdx.x == 0) pp_cur[p] = pp_trial[p];
 }
 
 __global__ void k_accept(int32_t *__restrict__ perm, int N, const double *__restrict__ tmp_cost,
@@ -319,6 +321,7 @@ dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int
     b.tmp_perm = ar.take<int32_t>(b.rows * N);
     b.tmp_cost = ar.take<double>(b.rows);
     b.ghat_cur = ar.take<double>(P * (size_t)pr->D_pp * pr->D_pp);
+    b.pp_cur = ar.take<double>(P);
     b.ev = dtfm_eval_carve(pr, ar, b.rows);
     return b;
 }
@@ -391,9 +394,11 @@ int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm
                     j++;
                 }
                 jp = j + 1 + t;
-                if (r == 0) {   // the evaluation above left the current rows' graphs in b.ev.ghat
+                if (r == 0) {   // the evaluation above left the current rows' graphs and PipelineP-Costs in b.ev
                     hipLaunchKernelGGL(k_copy_f64, dim3((unsigned)((P * nn + 255) / 256)), dim3(256), 0, st, b.ev.ghat,
                                        b.ghat_cur, P * nn);
+                    DTFM_HIP(hipGetLastError());
+                    hipLaunchKernelGGL(k_copy_f64, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, b.ev.pp, b.pp_cur, P);
                     DTFM_HIP(hipGetLastError());
                 } else {
                     hipLaunchKernelGGL(k_copy_f64, dim3((unsigned)((P * nn + 255) / 256)), dim3(256), 0, st, b.ghat_cur,
@@ -404,11 +409,12 @@ int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm
             hipLaunchKernelGGL(neighbourhood == DTFM_KL ? k_kl_propose : k_gain4_propose, dim3((unsigned)P),
                                dim3(DTFM_WAVE), 0, st, pr->W_pp, perm, N, pr->D_dp, pr->D_pp, r, b.tmp_perm, b.move_ab);
             DTFM_HIP(hipGetLastError());
-            rc = dtfm_eval_inc_enqueue(pr, b.ev, b.tmp_perm, P, b.tmp_cost, j, jp, st);
+            const dtfm_trial_ref ref = {b.ghat_cur, b.pp_cur, b.cur};
+            rc = dtfm_eval_inc_enqueue(pr, b.ev, b.tmp_perm, P, b.tmp_cost, j, jp, st, inc ? &ref : nullptr);
             if (rc != DTFM_OK) return rc;
             if (inc) {
                 hipLaunchKernelGGL(k_keep_ghat, dim3((unsigned)P), dim3(DTFM_WAVE), 0, st, b.tmp_cost, b.cur, nn, b.ev.ghat,
-                                   b.ghat_cur);
+                                   b.ghat_cur, b.ev.pp, b.pp_cur);
                 DTFM_HIP(hipGetLastError());
             }
             hipLaunchKernelGGL(k_accept, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, perm, N, b.tmp_cost,
