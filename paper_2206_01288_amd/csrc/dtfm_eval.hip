@@ -360,18 +360,38 @@ __device__ const unsigned char dtfm_binom10[11][11] = {
     {1, 6, 15, 20, 15, 6, 1, 0, 0, 0, 0}, {1, 7, 21, 35, 35, 21, 7, 1, 0, 0, 0}, {1, 8, 28, 56, 70, 56, 28, 8, 1, 0, 0},
     {1, 9, 36, 84, 126, 126, 84, 36, 9, 1, 0}, {1, 10, 45, 120, 210, 252, 210, 120, 45, 10, 1}};
 
+constexpr int dtfm_binom(int n, int k)
+{
+    int r = 1;
+    for (int i = 1; i <= k; i++) r = r * (n - k + i) / i;
+    return r;
+}
+// first position of the sets with k elements in the (popcount, value) order of the subsets of NL stages
+constexpr int dtfm_layer_first(int NL, int k)
+{
+    int f = 0;
+    for (int j = 0; j < k; j++) f += dtfm_binom(NL, j);
+    return f;
+}
+
 // The layers of one block of the blocked Held-Karp kernel (see k_held_karp_blocked); HM, a compile-time
-// constant, says which pairs of high-stage slots hold a stage of the block's set H.
+// constant, says which pairs of high-stage slots hold a stage of the block's set H. The loop over the layers is
+// unrolled: their sizes are compile-time constants, and the low part L of a group's next row (a table look-up
+// in LDS) is fetched one row ahead, across the barrier too. The barrier after the last layer also completes
+// the block's stores to the exchange area.
 template <int NL, int NPAIR, uint32_t HM>
-__device__ __forceinline__ void hk_block_layers(double *tab, const uint16_t *lsub, const int *loff, const double (&Gc)[16],
+__device__ __forceinline__ void hk_block_layers(double *tab, const uint16_t *lsub, const double (&Gc)[16],
                                                 double *X, uint32_t H, int nh, int n, int v, int grp)
 {
     static_assert(NL % 2 == 0 && 16 - NL <= 6, "slot pairs (NL + 2 q, NL + 2 q + 1), q < 3");
     constexpr int GROUPS = (1 << NL) / 16, RS = DTFM_HK_ROW_STRIDE;
+    uint32_t Lnext = 0;   // layer 0 is the empty low part alone (group 0)
+#pragma unroll
     for (int k = 0; k <= NL; k++) {
-        const int first = loff[k], cnt = loff[k + 1] - first;
+        const int first = dtfm_layer_first(NL, k), cnt = dtfm_binom(NL, k);
         for (int i = grp; i < cnt; i += GROUPS) {
-            const uint32_t L = lsub[first + i];
+            const uint32_t L = Lnext;
+            if (i + GROUPS < cnt) Lnext = lsub[first + i + GROUPS];
             const uint32_t S = (H << NL) | L;
             const bool in = (S >> v) & 1u;
             const double2 *row = reinterpret_cast<const double2 *>(tab + L * RS);
@@ -392,7 +412,12 @@ __device__ __forceinline__ void hk_block_layers(double *tab, const uint16_t *lsu
                     X[(((size_t)(H | (1u << (v - NL))) * nh + (v - NL)) << NL) + L] = y;
             }
         }
-        DTFM_LDS_BARRIER();
+        if (k < NL) {
+            if (grp < dtfm_binom(NL, k + 1)) Lnext = lsub[dtfm_layer_first(NL, k + 1) + grp];
+            DTFM_LDS_BARRIER();
+        } else {
+            __syncthreads();
+        }
     }
 }
 
@@ -406,52 +431,49 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
 {
     // rows are RS = 18 doubles apart (144 B = 36 banks): the same slot of 16 consecutive rows falls
     // into 16 different bank pairs, and the 128-bit row reads stay aligned
-    constexpr int ROWS = 1 << NL, THREADS = 1 << NL, GROUPS = THREADS / 16, RS = DTFM_HK_ROW_STRIDE;
+    constexpr int ROWS = 1 << NL, THREADS = 1 << NL, RS = DTFM_HK_ROW_STRIDE;
     extern __shared__ double smem[];
     double *tab = smem;                                           // [ROWS][RS], 16 slots used
     double *G = smem + ROWS * RS;                                 // [16][16], +inf outside n x n
     uint16_t *lsub = reinterpret_cast<uint16_t *>(G + 256);       // low parts ordered by popcount
-    __shared__ int loff[NL + 2];                                  // first index of each popcount in lsub
+    __shared__ unsigned char horder[1 << (16 - NL)];              // the sets H ordered by popcount
     constexpr int NHMAX = 16 - NL;
     const int nh = n - NL;
     double *X = xchg + (size_t)blockIdx.x * (((size_t)nh << nh) << NL);   // [H][high stage][L]
     const int v = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int Lt = threadIdx.x;   // the row this thread prepares at the start of a block
 
     {   // position of L = threadIdx.x in the (popcount, value) order: combinatorial number system
         const int L = threadIdx.x, k = __popc(L);
-        int first = 0;
-        for (int j = 0; j < k; j++) first += dtfm_binom10[NL][j];
         int rank = 0, i = 0;
         for (int m = L; m; m &= m - 1) {
             i++;
             rank += dtfm_binom10[__ffs(m) - 1][i];
         }
+        int first = 0;
+        for (int j = 0; j < k; j++) first += dtfm_binom10[NL][j];
         lsub[first + rank] = (uint16_t)L;
-        if (L == 0)
-            for (int j = 0, acc = 0; j <= NL + 1; j++) {
-                loff[j] = acc;
-                if (j <= NL) acc += dtfm_binom10[NL][j];
-            }
+        if (L < (1 << nh)) {   // the same order for the sets H of the nh high stages
+            int hfirst = 0;
+            for (int j = 0; j < k; j++) hfirst += dtfm_binom10[nh][j];
+            horder[hfirst + rank] = (unsigned char)L;
+        }
     }
+    const int nblocks = 1 << nh;
     const size_t todo = list != nullptr ? (size_t)*count : P;   // with a list: only the rows list[0 .. *count)
     for (size_t idx = blockIdx.x; idx < todo; idx += gridDim.x) {
         const size_t p = list != nullptr ? (size_t)list[idx] : idx;
-        __syncthreads();
+        __syncthreads();   // the tables above; the previous candidate's result has been read
         for (int e = threadIdx.x; e < 256; e += THREADS) {
             const int a = e >> 4, b = e & 15;
             G[e] = (a < n && b < n) ? ghat[p * n * n + a * n + b] : INFINITY;
         }
-#pragma unroll
-        for (int e = 0; e < RS; e++) tab[e * THREADS + threadIdx.x] = INFINITY;   // empty slots read as +inf
-        __syncthreads();
-        if ((int)threadIdx.x < NL) tab[((size_t)1 << threadIdx.x) * RS + threadIdx.x] = 0.0;   // block H = 0
         __syncthreads();
         double Gc[16];   // column v of Ghat
 #pragma unroll
         for (int u = 0; u < 16; u++) Gc[u] = G[u * 16 + v];
         // entries of block Hq that end in a high stage: pushed by the blocks Hq - h (a single high
         // stage alone is a path of one node); +inf for the high stages outside Hq
-        const int Lt = threadIdx.x;
         auto fetch = [&](uint32_t Hq, double (&xv)[NHMAX]) {
 #pragma unroll
             for (int hi = 0; hi < NHMAX; hi++) {
@@ -461,24 +483,43 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
                 xv[hi] = val;
             }
         };
-        for (uint32_t H = 0; H < (1u << nh); H++) {
-            if (H != 0u) {   // the previous block is done (barrier after its last layer)
+        // The blocks go by popcount of H (every subset of H before H). Two consecutive blocks of the same
+        // popcount do not depend on each other, so the exchanged entries of the next block are loaded while this
+        // one is computed; the first block of a popcount loads its own after the barrier that ends the one before.
+        double xv[NHMAX];
 #pragma unroll
-                for (int e = 0; e < RS; e++) tab[e * THREADS + threadIdx.x] = INFINITY;
+        for (int hi = 0; hi < NHMAX; hi++) xv[hi] = INFINITY;   // block H = 0
+        bool have = true;
+        for (int bi = 0; bi < nblocks; bi++) {
+            const uint32_t H = horder[bi];
+            // this thread's row of the new block: the previous block is done (barrier after its last layer). Low slots
+            // +inf (block 0: a single low stage alone is a path of one node), high slots as exchanged.
+            if (!have) fetch(H, xv);
+            {
+                double2 *mine = reinterpret_cast<double2 *>(tab + Lt * RS);
+                const bool single = H == 0u && __popc(Lt) == 1;
+                const int one = __ffs(Lt) - 1;
+#pragma unroll
+                for (int h = 0; h < NL / 2; h++)
+                    mine[h] = make_double2(single && one == 2 * h ? 0.0 : INFINITY, single && one == 2 * h + 1 ? 0.0 : INFINITY);
+#pragma unroll
+                for (int h = NL / 2; h < 8; h++)
+                    mine[h] = make_double2(xv[2 * h - NL], 2 * h - NL + 1 < NHMAX ? xv[2 * h - NL + 1] : INFINITY);
             }
-            // orders the fill before the stores below and completes every exchange store issued so far
-            __syncthreads();
-            double xv[NHMAX];
-            fetch(H, xv);
-#pragma unroll
-            for (int hi = 0; hi < NHMAX; hi++)
-                if (hi < nh) tab[Lt * RS + NL + hi] = xv[hi];
+            have = false;
+            if (bi + 1 < nblocks) {
+                const uint32_t Hn = horder[bi + 1];
+                if (__popc(Hn) == __popc(H)) {
+                    fetch(Hn, xv);
+                    have = true;
+                }
+            }
             DTFM_LDS_BARRIER();
             // The slots of high stages outside H are +inf in every row of the block. One copy of the layer
             // loops per set of empty slot pairs (NL, NL+1), (NL+2, NL+3), (NL+4, NL+5): a copy neither reads nor
             // relaxes its empty pairs. (A copy per set H, 64 of them, outgrows the instruction cache.)
 #define DTFM_HK_CASE(m) \
-    case m: hk_block_layers<NL, NPAIR, m>(tab, lsub, loff, Gc, X, H, nh, n, v, grp); break;
+    case m: hk_block_layers<NL, NPAIR, m>(tab, lsub, Gc, X, H, nh, n, v, grp); break;
             switch (((H & 3u) != 0u ? 1u : 0u) | ((H & 12u) != 0u ? 2u : 0u) | ((H & 48u) != 0u ? 4u : 0u)) {
                 DTFM_HK_CASE(0) DTFM_HK_CASE(1) DTFM_HK_CASE(2) DTFM_HK_CASE(3)
                 DTFM_HK_CASE(4) DTFM_HK_CASE(5) DTFM_HK_CASE(6) DTFM_HK_CASE(7)
@@ -486,7 +527,7 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
             }
 #undef DTFM_HK_CASE
         }
-        if (threadIdx.x == 0) {   // the block of H = all high stages is still in LDS; its last row is the full set
+        if (threadIdx.x == 0) {   // the block of H = all high stages came last and is still in LDS; its last row is the full set
             double m = INFINITY;
             for (int u = 0; u < n; u++) m = fmin(m, tab[(ROWS - 1) * RS + u]);
             cost[p] = __dadd_rn(datap[p], m);
