@@ -137,7 +137,11 @@ int dtfm_validate_population(dtfm_problem *prob, const int32_t *perm, int P, int
  * neighbourhood on the true cost (Eq. 1) and applies at most one swap of two positions, only if
  * the cost strictly decreases.
  *  DTFM_ALL_PAIRS: all N(N-1)/2 position pairs a < b in lexicographic order; the cheapest
- *    resulting allocation wins, the lowest move index on ties.
+ *    resulting allocation wins, the lowest move index on ties. A swap of two slots of the same
+ *    stage leaves the partition C_1..C_Dpp (and so Eq. 1 as a function of the sets) unchanged and
+ *    only reorders that stage's Eq. 2 sums; it is priced like any other move, so once no real move
+ *    improves, such a swap can still be applied on a gain of one unit in the last place of the
+ *    rounded sum (the oracle does the same; `applied` then names it and the cost drops by that).
  *  DTFM_GAIN4: the paper's neighbourhood ("Improving Local Search Strategy"): round r takes
  *    stage pair number r mod D_pp(D_pp-1)/2 in lexicographic order, the fastest link (smallest
  *    W_pp) inside each of the two stages, and among the four swaps of their end points the one

@@ -237,12 +237,16 @@ k_match(const uint32_t *__restrict__ Wr, const double *__restrict__ rank_val,
         for (int pass = 0; pass < 2 * 16 * NB + 2; pass++) {
             uint64_t reach = __ballot(dist <= theta) & ~visited & allcols;
             if (reach == 0ull) {
+                // smallest dist of an unvisited column: prefix minima inside each row of 16 lanes by data-parallel
+                // shifts (a lane without a source keeps its own value), then the four row results
                 uint32_t k = (((visited >> lane) & 1ull) != 0ull || !active) ? 0xffffffffu : dist;
-                for (int o = 32; o >= 1; o >>= 1) {
-                    uint32_t q = (uint32_t)__shfl_xor((int)k, o);
-                    k = q < k ? q : k;
-                }
-                theta = (uint32_t)__builtin_amdgcn_readfirstlane((int)k);
+                k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x111, 0xF, 0xF, false));   // row_shr:1
+                k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x112, 0xF, 0xF, false));   // row_shr:2
+                k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x114, 0xF, 0xF, false));   // row_shr:4
+                k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x118, 0xF, 0xF, false));   // row_shr:8
+                const uint32_t m0 = (uint32_t)__builtin_amdgcn_readlane((int)k, 15), m1 = (uint32_t)__builtin_amdgcn_readlane((int)k, 31);
+                const uint32_t m2 = (uint32_t)__builtin_amdgcn_readlane((int)k, 47), m3 = (uint32_t)__builtin_amdgcn_readlane((int)k, 63);
+                theta = min(min(m0, m1), min(m2, m3));
                 continue;
             }
             uint64_t hit = reach & freecols;
