@@ -48,7 +48,7 @@ enum {
 #define DTFM_MAX_DDP 64
 #define DTFM_MAX_N 1024
 
-enum { DTFM_ALL_PAIRS = 0, DTFM_GAIN4 = 1, DTFM_KL = 2 };
+enum { DTFM_ALL_PAIRS = 0, DTFM_GAIN4 = 1, DTFM_KL = 2, DTFM_BEST4 = 3 };
 
 /* Sec. 2 (formalisation of the scheduling problem) and Eqs. 2-3: builds the problem instance.
  * latency, bandwidth: host, N*N row-major, entry [d*N + d'] = alpha_{d,d'} (seconds) and
@@ -146,6 +146,10 @@ int dtfm_validate_population(dtfm_problem *prob, const int32_t *perm, int P, int
  *    stage pair number r mod D_pp(D_pp-1)/2 in lexicographic order, the fastest link (smallest
  *    W_pp) inside each of the two stages, and among the four swaps of their end points the one
  *    of largest Gain (the paper's gain function with w = W_pp); that swap is the round's move.
+ *  DTFM_BEST4: a second reading of the same passage (the paper does not say whether a swap is
+ *    taken on its Gain or on the cost): the same stage pair per round and the same four candidate
+ *    swaps as DTFM_GAIN4 (in the order (d1,d1'), (d1,d2'), (d2,d1'), (d2,d2')), all four priced by
+ *    Eq. 1; the cheapest of them, the first on ties, is the round's move.
  *  DTFM_KL: the strategy the paper compares with ("Existing Local Search Strategy"), for
  *    ablations: same stage pair per round as DTFM_GAIN4; among all D_dp^2 swaps of a device of
  *    one stage with a device of the other, the one of largest Kernighan-Lin gain (the paper's
@@ -153,7 +157,7 @@ int dtfm_validate_population(dtfm_problem *prob, const int32_t *perm, int P, int
  * perm: device, P*N, in/out. cost: device, P doubles, out: cost of the final rows.
  * applied: device, P*moves int64, may be null: the index (in the ALL_PAIRS numbering) of the
  * swap applied by candidate p in round r at [p*moves + r], or -1.
- * Errors: NULL, ARG (P < 0, moves < 0, unknown neighbourhood), UNSUPPORTED (GAIN4 with
+ * Errors: NULL, ARG (P < 0, moves < 0, unknown neighbourhood), UNSUPPORTED (GAIN4 or BEST4 with
  * D_dp < 2 or D_pp < 2, KL with D_pp < 2), HIP. */
 int dtfm_local_search(dtfm_problem *prob, int32_t *perm, int P, int moves, int neighbourhood,
                       double *cost, int64_t *applied, void *hip_stream);
@@ -172,7 +176,7 @@ typedef struct {
     int32_t m_x;            /* crossover: device draws per offspring, >= 0 */
     int32_t m_m;            /* mutation: random position transpositions per offspring, >= 0 */
     int32_t ls_moves;       /* local-search rounds per offspring, >= 0 */
-    int32_t neighbourhood;  /* DTFM_ALL_PAIRS, DTFM_GAIN4 or DTFM_KL */
+    int32_t neighbourhood;  /* DTFM_ALL_PAIRS, DTFM_GAIN4, DTFM_KL or DTFM_BEST4 */
     int32_t warm_start;     /* 1: `population` holds the initial population on entry */
 } dtfm_ga_params;
 

@@ -21,6 +21,7 @@ _LIB = os.path.join(_HERE, "libdtfm_oracle.so")
 ALL_PAIRS = 0
 GAIN4 = 1
 KL = 2
+BEST4 = 3
 
 
 def build(force: bool = False) -> str:
@@ -69,6 +70,7 @@ def lib():
         L.orc_lexmin_matching.argtypes = [dp, c_int, c_double, ip]
         L.orc_lexmin_matching.restype = c_int
         L.orc_get_assignment.argtypes = [dp, c_int, c_int, c_int, ip, ip, ip]
+        L.orc_four_candidates.argtypes = [dp, c_int, c_int, c_int, ip, c_int, ip, ip]
         L.orc_gain4_propose.argtypes = [dp, c_int, c_int, c_int, ip, c_int, ip, ip, dp]
         L.orc_kl_propose.argtypes = [dp, c_int, c_int, c_int, ip, c_int, ip, ip, dp]
         L.orc_local_search.argtypes = [dp, dp, c_int, c_int, c_int, ip, c_int, c_int, c_int, dp, lp]
@@ -154,6 +156,15 @@ class Problem:
         lib().orc_gain4_propose(self._w()[1], self.N, self.D_dp, self.D_pp, pp, r,
                                 ctypes.byref(a), ctypes.byref(b), gains.ctypes.data_as(POINTER(c_double)))
         return a.value, b.value, gains
+
+    def four_candidates(self, perm, r):
+        """The four swaps [(a, b)] that round r's stage pair offers, in the paper's order."""
+        perm, pp = _i(perm)
+        a = np.empty(4, dtype=np.int32)
+        b = np.empty(4, dtype=np.int32)
+        lib().orc_four_candidates(self._w()[1], self.N, self.D_dp, self.D_pp, pp, r,
+                                  a.ctypes.data_as(POINTER(c_int)), b.ctypes.data_as(POINTER(c_int)))
+        return list(zip(a.tolist(), b.tolist()))
 
     def kl_propose(self, perm, r):
         """(position a, position b, gain_KL of all D_dp x D_dp swaps) for round r."""

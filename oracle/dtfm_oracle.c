@@ -34,6 +34,9 @@
  *                               none): pinned as implementing those rules by enumeration of all
  *                               tours and all matchings on tiny cases, by the closed form on a
  *                               homogeneous network, and by re-deriving the cost from the output
+ *   orc_local_search BEST4      a second reading of the same passage (the four candidates judged by the cost
+ *                               instead of by the Gain): pinned like GAIN4 against the definition-level
+ *                               restatement (candidates, schedule, choice, ties, acceptance)
  *   orc_local_search KL         gain_KL formula pinned by hand computation and by its textbook
  *                               meaning (change of the cut weight between the two groups); round
  *                               schedule and acceptance rule as for GAIN4, pinned the same way
@@ -59,6 +62,7 @@
 #define ORC_ALL_PAIRS 0
 #define ORC_GAIN4 1
 #define ORC_KL 2
+#define ORC_BEST4 3
 
 /* ------------------------------------------------------------------------------------------ */
 /* Sec. 2: communication graph G. Each edge carries the average of the two directions.         */
@@ -417,6 +421,10 @@ void orc_get_assignment(const double *W_pp, int N, int D_dp, int D_pp, const int
  * ALL_PAIRS: every position pair a < b, in lexicographic order, is a move; the move with the
  * lowest resulting cost is chosen, the first such on ties.
  *
+ * BEST4 (a second reading of the paper's neighbourhood): the same stage pair per round and the same four
+ * candidate swaps as GAIN4, but the round's move is the one of lowest true cost among the four (all four
+ * are evaluated; the first on ties). The candidates are fixed by the fastest links; the Gain function is not used.
+ *
  * KL (the strategy the paper compares against, Sec. 3.4 "Existing Local Search Strategy"): same
  * stage pair per round as GAIN4; the swap of largest gain_KL among all D_dp^2 swaps between the
  * two stages is the round's single move (see orc_kl_propose).
@@ -457,6 +465,27 @@ static void fastest_link(const double *W_pp, int N, int D_dp, const int *C, int 
                 *s2 = k;
             }
         }
+}
+
+/* The four swaps that stage pair number r mod (D_pp (D_pp-1)/2) offers in round r (Sec. 3.4, "Improving Local
+ * Search Strategy": the end points of the fastest link inside each of the two stages), as positions
+ * pos_a[k] < pos_b[k], k in the order (d1,d1'), (d1,d2'), (d2,d1'), (d2,d2'). */
+void orc_four_candidates(const double *W_pp, int N, int D_dp, int D_pp, const int *perm, int r, int *pos_a, int *pos_b)
+{
+    int npairs = D_pp * (D_pp - 1) / 2;
+    int t = r % npairs, j = 0, jp = 1, cnt = 0;
+    for (int a = 0; a < D_pp; a++)
+        for (int b = a + 1; b < D_pp; b++) {
+            if (cnt == t) { j = a; jp = b; }
+            cnt++;
+        }
+    int s[2], sp[2];
+    fastest_link(W_pp, N, D_dp, perm + j * D_dp, &s[0], &s[1]);
+    fastest_link(W_pp, N, D_dp, perm + jp * D_dp, &sp[0], &sp[1]);
+    for (int k = 0; k < 4; k++) {
+        pos_a[k] = j * D_dp + s[k / 2];
+        pos_b[k] = jp * D_dp + sp[k % 2];
+    }
 }
 
 /* Positions (a < b) of GAIN4's proposed swap for round r. Also returns the four gains. */
@@ -559,6 +588,17 @@ void orc_local_search(const double *W_dp, const double *W_pp, int N, int D_dp, i
                         t = x[a]; x[a] = x[b]; x[b] = t;
                         if (c < bc) { bc = c; ba = a; bb = b; }
                     }
+            } else if (neighbourhood == ORC_BEST4) {
+                /* the Gain's four candidates, judged by the cost itself: all four are evaluated, the cheapest
+                 * (the first of them on ties) is the round's move */
+                int pa[4], pb[4];
+                orc_four_candidates(W_pp, N, D_dp, D_pp, x, r, pa, pb);
+                for (int k = 0; k < 4; k++) {
+                    int t = x[pa[k]]; x[pa[k]] = x[pb[k]]; x[pb[k]] = t;
+                    double c = orc_comm_cost(W_dp, W_pp, N, D_dp, D_pp, x, 0);
+                    t = x[pa[k]]; x[pa[k]] = x[pb[k]]; x[pb[k]] = t;
+                    if (c < bc) { bc = c; ba = pa[k]; bb = pb[k]; }
+                }
             } else {
                 if (neighbourhood == ORC_KL) orc_kl_propose(W_pp, N, D_dp, D_pp, x, r, &ba, &bb, NULL);
                 else orc_gain4_propose(W_pp, N, D_dp, D_pp, x, r, &ba, &bb, NULL);
@@ -628,7 +668,7 @@ typedef struct {
     int m_x;            /* crossover: device draws per offspring */
     int m_m;            /* mutation: random transpositions per offspring */
     int ls_moves;       /* local-search rounds per offspring */
-    int neighbourhood;  /* ORC_ALL_PAIRS or ORC_GAIN4 */
+    int neighbourhood;  /* ORC_ALL_PAIRS, ORC_GAIN4, ORC_KL or ORC_BEST4 */
     int warm_start;     /* 1: population[] holds the initial population */
 } orc_ga_params;
 

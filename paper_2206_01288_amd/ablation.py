@@ -2,8 +2,9 @@
 
     python -m paper_2206_01288_amd.ablation [--network C2b] [--budget 600000] [--seeds 0 1 2]
 
-Runs the evolutionary search on one GPU with the paper's four-candidate local search (GAIN4), with
-the Kernighan-Lin gain (KL), with no local search, and in steady-state mode (one offspring per
+Runs the evolutionary search on one GPU with the paper's four-candidate local search in its two
+readings (GAIN4: the top-Gain swap of the four is tried; BEST4: all four are priced and the cheapest
+is tried), with the Kernighan-Lin gain (KL), with no local search, and in steady-state mode (one offspring per
 generation, the paper's loop), every variant with the same budget of cost evaluations (or, with
 --offspring, the same number of offspring), and prints
 the best estimated cost (seconds) each reaches per seed, next to the mean cost of random
@@ -46,14 +47,15 @@ def main():
            "random_allocation_mean_cost": float(rand.mean().item()), "random_allocation_best_of_4096": float(rand.min().item()),
            "best_cost": {}}
     variants = {
-        # name: (lambda, ls_moves, neighbourhood)
+        # name: (lambda, ls_moves, neighbourhood, cost evaluations per local-search round)
         "gain4 (paper's local search)": (P, m, dtfm.GAIN4),
+        "best4 (the four candidates by cost)": (P, max(1, m // 4), dtfm.BEST4),
         "kl gain": (P, m, dtfm.KL),
         "no local search": (P, 0, dtfm.GAIN4),
         "gain4, steady state (lambda=1)": (1, m, dtfm.GAIN4),
     }
     for name, (lam, moves, nb) in variants.items():
-        per_gen = lam * (1 + moves)
+        per_gen = lam * (1 + moves * (4 if nb == dtfm.BEST4 else 1))
         gens = max(1, (args.budget - P) // per_gen) if args.offspring <= 0 else max(1, args.offspring // lam)
         res, secs = [], []
         for seed in args.seeds:
@@ -65,7 +67,7 @@ def main():
             res.append(float(trace[-1].item()))
         out["best_cost"][name] = {"generations": gens, "per_seed": res, "mean": float(np.mean(res)),
                                   "seconds_per_run": float(np.mean(secs))}
-        print("%-32s generations %7d  %.2f s/run  best cost per seed %s"
+        print("%-36s generations %7d  %.2f s/run  best cost per seed %s"
               % (name, gens, np.mean(secs), " ".join("%.4f" % r for r in res)), flush=True)
     print(json.dumps(out))
 

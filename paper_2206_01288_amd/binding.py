@@ -13,6 +13,7 @@ _LIB_PATH = os.path.join(_PKG, "libdtfm.so")
 ALL_PAIRS = 0
 GAIN4 = 1
 KL = 2
+BEST4 = 3
 FIXED_SCRATCH_BYTES = 32 << 20     # DTFM_FIXED_SCRATCH_BYTES of include/dtfm.h
 
 # every entry point include/dtfm.h declares

@@ -309,9 +309,10 @@ extern "C" int dtfm_validate_population(dtfm_problem *pr, const int32_t *perm, i
 
 static int check_neighbourhood(const dtfm_problem *pr, int neighbourhood)
 {
-    if (neighbourhood != DTFM_ALL_PAIRS && neighbourhood != DTFM_GAIN4 && neighbourhood != DTFM_KL) return DTFM_ERR_ARG;
+    if (neighbourhood != DTFM_ALL_PAIRS && neighbourhood != DTFM_GAIN4 && neighbourhood != DTFM_KL && neighbourhood != DTFM_BEST4)
+        return DTFM_ERR_ARG;
     // the paper's neighbourhood needs a link inside a stage and a second stage to swap with
-    if (neighbourhood == DTFM_GAIN4 && (pr->D_dp < 2 || pr->D_pp < 2)) return DTFM_ERR_UNSUPPORTED;
+    if ((neighbourhood == DTFM_GAIN4 || neighbourhood == DTFM_BEST4) && (pr->D_dp < 2 || pr->D_pp < 2)) return DTFM_ERR_UNSUPPORTED;
     if (neighbourhood == DTFM_KL && pr->D_pp < 2) return DTFM_ERR_UNSUPPORTED;   // no second stage to swap with
     return DTFM_OK;
 }
@@ -372,7 +373,8 @@ extern "C" int dtfm_reserve(dtfm_problem *pr, int P, int lambda, int neighbourho
 {
     if (pr == nullptr) return DTFM_ERR_NULL;
     if (P < 0 || lambda < 0) return DTFM_ERR_ARG;
-    if (neighbourhood != DTFM_ALL_PAIRS && neighbourhood != DTFM_GAIN4 && neighbourhood != DTFM_KL) return DTFM_ERR_ARG;
+    if (neighbourhood != DTFM_ALL_PAIRS && neighbourhood != DTFM_GAIN4 && neighbourhood != DTFM_KL && neighbourhood != DTFM_BEST4)
+        return DTFM_ERR_ARG;
     const size_t rows = (size_t)(P > lambda ? P : lambda);
     if (rows == 0) return DTFM_OK;
     size_t need = 0;

@@ -550,24 +550,25 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
 __global__ void k_trial_shortcut(const double *__restrict__ ghat, const double *__restrict__ datap, int nn,
                                  const double *__restrict__ ghat_cur, const double *__restrict__ pp_cur,
                                  const double *__restrict__ cur, double *__restrict__ cost, double *__restrict__ pp_out,
-                                 int32_t *__restrict__ list, int32_t *__restrict__ count, size_t rows)
+                                 int32_t *__restrict__ list, int32_t *__restrict__ count, size_t rows, int trials_per_row)
 {
     const size_t p = (size_t)blockIdx.x * (blockDim.x / DTFM_WAVE) + threadIdx.x / DTFM_WAVE;
     if (p >= rows) return;   // whole wavefront
+    const size_t c = p / (size_t)trials_per_row;   // the current row this trial was made from
     const int lane = threadIdx.x & (DTFM_WAVE - 1);
     bool differs = false, below = false;
     for (int e = lane; e < nn; e += DTFM_WAVE) {
-        const double a = ghat[p * nn + e], b = ghat_cur[p * nn + e];
+        const double a = ghat[p * nn + e], b = ghat_cur[c * nn + e];
         differs |= a != b;
         below |= a < b;
     }
     const bool any_differs = __ballot(differs) != 0ull, any_below = __ballot(below) != 0ull;
     if (lane != 0) return;
-    const double with_cur = __dadd_rn(datap[p], pp_cur[p]);
+    const double with_cur = __dadd_rn(datap[p], pp_cur[c]);
     if (!any_differs) {
         cost[p] = with_cur;
-        pp_out[p] = pp_cur[p];
-    } else if (!any_below && with_cur >= cur[p]) {
+        pp_out[p] = pp_cur[c];
+    } else if (!any_below && with_cur >= cur[c]) {
         cost[p] = INFINITY;
     } else {
         list[atomicAdd(count, 1)] = (int32_t)p;
@@ -649,7 +650,7 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
         hipLaunchKernelGGL(k_zero_count, dim3(1), dim3(1), 0, st, b.count);
         DTFM_HIP(hipGetLastError());
         hipLaunchKernelGGL(k_trial_shortcut, dim3((unsigned)((rows + 3) / 4)), dim3(4 * DTFM_WAVE), 0, st, b.ghat, b.datap,
-                           n * n, ref->ghat_cur, ref->pp_cur, ref->cur, cost, b.pp, b.list, b.count, rows);
+                           n * n, ref->ghat_cur, ref->pp_cur, ref->cur, cost, b.pp, b.list, b.count, rows, ref->trials_per_row);
         DTFM_HIP(hipGetLastError());
         list = b.list;
         count = b.count;

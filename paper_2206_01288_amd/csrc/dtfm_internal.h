@@ -91,6 +91,7 @@ struct dtfm_trial_ref {
     const double *ghat_cur;   // rows * D_pp * D_pp: coarsened graphs of the current rows
     const double *pp_cur;     // rows: their PipelineP-Cost
     const double *cur;        // rows: their cost (Eq. 1)
+    int trials_per_row;       // consecutive trial rows made from one current row (1, or 4 for BEST4)
 };
 // hk_grid_cap: upper limit on the number of exchange areas (0: DTFM_HK_GLOBAL_GRID)
 dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows, size_t hk_grid_cap = 0);

@@ -185,6 +185,104 @@ __global__ void k_gain4_propose(const double *__restrict__ W_pp, const int32_t *
     }
 }
 
+// BEST4 (the four candidates of the paper's neighbourhood judged by the cost): one wavefront per candidate writes
+// the four swapped allocations of round r, rows 4 p .. 4 p + 3 of tmp_perm in the order (d1,d1'), (d1,d2'), (d2,d1'),
+// (d2,d2'), and their positions. The fastest link of a stage as in k_gain4_propose.
+__global__ void k_best4_propose(const double *__restrict__ W_pp, const int32_t *__restrict__ perm,
+                                int N, int D_dp, int D_pp, int r, int32_t *__restrict__ tmp_perm,
+                                int32_t *__restrict__ move_ab)
+{
+    const int lane = threadIdx.x;
+    size_t p = blockIdx.x;
+    int npairs = D_pp * (D_pp - 1) / 2;
+    int j, jp;
+    pair_decode(D_pp, r % npairs, j, jp);
+    const int32_t *row = perm + p * N;
+    const int32_t *Cs[2] = {row + j * D_dp, row + jp * D_dp};
+    int slot[2][2];
+    long long E = (long long)D_dp * (D_dp - 1) / 2;
+    for (int s = 0; s < 2; s++) {
+        const int32_t *C = Cs[s];
+        double best = INFINITY;
+        long long be = E;
+        for (long long e = lane; e < E; e += DTFM_WAVE) {
+            int i, k;
+            pair_decode(D_dp, e, i, k);
+            double w = W_pp[(size_t)C[i] * N + C[k]];
+            if (w < best) {
+                best = w;
+                be = e;
+            }
+        }
+        for (int o = 32; o >= 1; o >>= 1) {
+            double ow = __shfl_xor(best, o);
+            long long oe = __shfl_xor(be, o);
+            if (ow < best || (ow == best && oe < be)) {
+                best = ow;
+                be = oe;
+            }
+        }
+        if (be >= E) be = 0;  // only on malformed (non-finite) weights
+        pair_decode(D_dp, be, slot[s][0], slot[s][1]);
+    }
+    for (int k = 0; k < 4; k++) {
+        const int a = j * D_dp + slot[0][k >> 1], b = jp * D_dp + slot[1][k & 1];
+        int32_t *dst = tmp_perm + (4 * p + k) * N;
+        for (int q = lane; q < N; q += DTFM_WAVE) {
+            int s = q == a ? b : (q == b ? a : q);
+            dst[q] = row[s];
+        }
+        if (lane == 0) {
+            move_ab[2 * (4 * p + k)] = a;
+            move_ab[2 * (4 * p + k) + 1] = b;
+        }
+    }
+}
+
+// BEST4: the cheapest of the candidate's four trials (the first on ties) is applied iff strictly cheaper than the
+// current row; its coarsened graph and PipelineP-Cost then become the current ones (ghat_cur may be null).
+__global__ void k_best4_pick(int32_t *__restrict__ perm, int N, const double *__restrict__ tmp_cost,
+                             double *__restrict__ cur, const int32_t *__restrict__ move_ab, int64_t *__restrict__ applied,
+                             int moves, int r, int nn, const double *__restrict__ ghat_trial, double *__restrict__ ghat_cur,
+                             const double *__restrict__ pp_trial, double *__restrict__ pp_cur)
+{
+    const size_t p = blockIdx.x;
+    int bk = 0;
+    double bc = tmp_cost[4 * p];
+    for (int k = 1; k < 4; k++) {
+        const double c = tmp_cost[4 * p + k];
+        if (c < bc) {
+            bc = c;
+            bk = k;
+        }
+    }
+    const bool take = bc < cur[p];   // uniform over the workgroup
+    if (take && ghat_cur != nullptr)
+        for (int e = threadIdx.x; e < nn; e += blockDim.x) ghat_cur[p * nn + e] = ghat_trial[(4 * p + bk) * nn + e];
+    if (threadIdx.x != 0) return;
+    long long mv = -1;
+    if (take) {
+        const int a = move_ab[2 * (4 * p + bk)], b = move_ab[2 * (4 * p + bk) + 1];
+        int32_t *row = perm + p * N;
+        const int32_t t = row[a];
+        row[a] = row[b];
+        row[b] = t;
+        cur[p] = bc;
+        if (pp_cur != nullptr) pp_cur[p] = pp_trial[4 * p + bk];
+        mv = pair_encode(N, a, b);
+    }
+    if (applied != nullptr) applied[p * (size_t)moves + r] = mv;
+}
+
+// dst[(reps c + k) * nn + e] = src[c * nn + e]: the current rows' coarsened graphs under each of their trial rows
+__global__ void k_replicate_f64(const double *__restrict__ src, double *__restrict__ dst, int nn, int reps, size_t total)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const size_t row = i / nn, e = i - row * nn;
+    dst[i] = src[(row / reps) * nn + e];
+}
+
 // KL neighbourhood (Sec. 3.4 "Existing Local Search Strategy", the strategy the paper compares with):
 // one wavefront per candidate; round r looks at the same stage pair as the four-candidate
 // neighbourhood and proposes, among all D_dp^2 swaps between the two stages, the one of largest
@@ -307,7 +405,6 @@ dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int
     dtfm_ls_bufs b;
     size_t N = pr->N, M = N * (N - 1) / 2;
     b.cur = ar.take<double>(P);
-    b.move_ab = ar.take<int32_t>(2 * P);
     if (neighbourhood == DTFM_ALL_PAIRS && M > 0) {
         size_t chunk = DTFM_LS_ROWS_MAX / M;
         if (chunk < 1) chunk = 1;
@@ -316,8 +413,9 @@ dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int
         b.rows = chunk * M > P ? chunk * M : P;
     } else {
         b.chunk = P;
-        b.rows = P;
+        b.rows = neighbourhood == DTFM_BEST4 ? 4 * P : P;   // BEST4 prices four trials per candidate
     }
+    b.move_ab = ar.take<int32_t>(2 * b.rows);
     b.tmp_perm = ar.take<int32_t>(b.rows * N);
     b.tmp_cost = ar.take<double>(b.rows);
     b.ghat_cur = ar.take<double>(P * (size_t)pr->D_pp * pr->D_pp);
@@ -385,6 +483,8 @@ int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm
             // again only the 2 D_pp - 3 edges of those two stages.
             const int n = pr->D_pp, nn = n * n;
             const bool inc = n >= 3 && !pr->fast64;   // the 64-device shape prices rows with its own fused kernel
+            const int tpr = neighbourhood == DTFM_BEST4 ? 4 : 1;   // trial rows per candidate
+            const size_t T = P * (size_t)tpr;
             int j = -1, jp = -1;
             if (inc) {
                 int t = r % pr->npairs;   // the round's stage pair, lexicographic order
@@ -400,18 +500,27 @@ int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm
                     DTFM_HIP(hipGetLastError());
                     hipLaunchKernelGGL(k_copy_f64, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, b.ev.pp, b.pp_cur, P);
                     DTFM_HIP(hipGetLastError());
-                } else {
-                    hipLaunchKernelGGL(k_copy_f64, dim3((unsigned)((P * nn + 255) / 256)), dim3(256), 0, st, b.ghat_cur,
-                                       b.ev.ghat, P * nn);
+                }
+                if (r > 0 || tpr > 1) {   // every trial row starts from its current row's graph
+                    hipLaunchKernelGGL(k_replicate_f64, dim3((unsigned)((T * nn + 255) / 256)), dim3(256), 0, st, b.ghat_cur,
+                                       b.ev.ghat, nn, tpr, T * nn);
                     DTFM_HIP(hipGetLastError());
                 }
             }
-            hipLaunchKernelGGL(neighbourhood == DTFM_KL ? k_kl_propose : k_gain4_propose, dim3((unsigned)P),
-                               dim3(DTFM_WAVE), 0, st, pr->W_pp, perm, N, pr->D_dp, pr->D_pp, r, b.tmp_perm, b.move_ab);
+            hipLaunchKernelGGL(neighbourhood == DTFM_KL ? k_kl_propose : neighbourhood == DTFM_BEST4 ? k_best4_propose : k_gain4_propose,
+                               dim3((unsigned)P), dim3(DTFM_WAVE), 0, st, pr->W_pp, perm, N, pr->D_dp, pr->D_pp, r, b.tmp_perm,
+                               b.move_ab);
             DTFM_HIP(hipGetLastError());
-            const dtfm_trial_ref ref = {b.ghat_cur, b.pp_cur, b.cur};
-            rc = dtfm_eval_inc_enqueue(pr, b.ev, b.tmp_perm, P, b.tmp_cost, j, jp, st, inc ? &ref : nullptr);
+            const dtfm_trial_ref ref = {b.ghat_cur, b.pp_cur, b.cur, tpr};
+            rc = dtfm_eval_inc_enqueue(pr, b.ev, b.tmp_perm, T, b.tmp_cost, j, jp, st, inc ? &ref : nullptr);
             if (rc != DTFM_OK) return rc;
+            if (neighbourhood == DTFM_BEST4) {
+                hipLaunchKernelGGL(k_best4_pick, dim3((unsigned)P), dim3(DTFM_WAVE), 0, st, perm, N, b.tmp_cost, b.cur, b.move_ab,
+                                   applied, moves, r, nn, b.ev.ghat, inc ? b.ghat_cur : (double *)nullptr, b.ev.pp,
+                                   inc ? b.pp_cur : (double *)nullptr);
+                DTFM_HIP(hipGetLastError());
+                continue;
+            }
             if (inc) {
                 hipLaunchKernelGGL(k_keep_ghat, dim3((unsigned)P), dim3(DTFM_WAVE), 0, st, b.tmp_cost, b.cur, nn, b.ev.ghat,
                                    b.ghat_cur, b.ev.pp, b.pp_cur);

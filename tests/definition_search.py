@@ -152,6 +152,45 @@ def gain4_proposal(W_pp, perm, D_dp, D_pp, r):
     return best[1], best[2]
 
 
+def four_candidates(W_pp, perm, D_dp, D_pp, r):
+    """The four swaps round r's stage pair offers (Sec. 3.4, "Improving Local Search Strategy": the end points
+    d1, d2 of the fastest link inside C_j and d1', d2' of the fastest inside C_j'), as position pairs in the
+    order (d1,d1'), (d1,d2'), (d2,d1'), (d2,d2'). Fastest = first smallest W_pp over slot pairs i < i'."""
+    j, jp = stage_pair_of_round(r, D_pp)
+    ends = []
+    for st in (j, jp):
+        C = perm[st * D_dp:(st + 1) * D_dp]
+        best = None
+        for i, i2 in itertools.combinations(range(D_dp), 2):
+            if best is None or W_pp[C[i]][C[i2]] < best[0]:
+                best = (W_pp[C[i]][C[i2]], st * D_dp + i, st * D_dp + i2)
+        ends.append(best[1:])
+    return [(a, b) for a in ends[0] for b in ends[1]]
+
+
+def local_search_best4(cost_fn, W_pp, perm, D_dp, D_pp, rounds):
+    """The second reading of the paper's neighbourhood: per round the four candidates are all priced by the true
+    cost, the cheapest (the first on ties) is applied iff it is strictly cheaper than the current allocation.
+    Returns (perm, cost, applied)."""
+    perm = list(perm)
+    cur = cost_fn(perm)
+    applied = []
+    for r in range(rounds):
+        best = None
+        for a, b in four_candidates(W_pp, perm, D_dp, D_pp, r):
+            trial = list(perm)
+            trial[a], trial[b] = trial[b], trial[a]
+            c = cost_fn(trial)
+            if best is None or c < best[0]:
+                best = (c, trial, (a, b))
+        if best[0] < cur:
+            cur, perm = best[0], best[1]
+            applied.append(best[2])
+        else:
+            applied.append(None)
+    return perm, cur, applied
+
+
 def kl_proposal(W_pp, perm, D_dp, D_pp, r):
     """The Kernighan-Lin neighbourhood the paper compares with (Sec. 3.4, "Existing Local Search
     Strategy") for round r: among all swaps of a device x of C_j with a device y of C_j', the first

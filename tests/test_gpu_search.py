@@ -326,6 +326,30 @@ def test_config5_full_size_generations():
     assert cost[0] < rand.min()
 
 
+@pytest.mark.parametrize("name,P,rounds", [("C1", 40, 14), ("C2", 64, 30), ("C2b", 24, 30), ("C3h", 8, 5), ("C4", 6, 4),
+                                           ("C5", 2, 3)])
+def test_best4_local_search(name, P, rounds):
+    # the four candidates of the paper's neighbourhood judged by the cost: rows, costs and applied moves against the oracle
+    w = workloads.config(name)
+    applied = _ls_parity(w, workloads.random_population(P, w.N, seed=8), rounds, dtfm.BEST4)
+    if name in ("C1", "C2", "C2b", "C4"):
+        assert (applied >= 0).any()
+    if name == "C3h":
+        assert (applied == -1).all()
+
+
+@pytest.mark.parametrize("D_dp,D_pp", [(2, 2), (3, 5), (2, 7), (9, 2), (4, 11), (17, 3)])
+def test_best4_odd_shapes(D_dp, D_pp):
+    N = D_dp * D_pp
+    _ls_parity(custom(N, D_dp, D_pp, seed=N), workloads.random_population(7, N, seed=4), 9, dtfm.BEST4)
+
+
+def test_evolve_with_best4():
+    _evolve_parity(workloads.config("C2"), 2, 3, 24, ls_moves=3, neighbourhood=dtfm.BEST4)
+    _evolve_parity(workloads.config("C1"), 5, 4, 9, lam=4, ls_moves=4, neighbourhood=dtfm.BEST4)
+    _evolve_parity(custom(48, 4, 12, seed=3), 1, 2, 6, ls_moves=2, neighbourhood=dtfm.BEST4)
+
+
 def _read_c5_golden():
     """tests/golden/c5_evolve_seed7_P4096.txt, written by tests/golden/make_c5_trace.py from the CPU oracle."""
     import os
@@ -412,6 +436,7 @@ def test_random_shapes_every_call(seed):
     if D_dp >= 2 and D_pp >= 2:
         _ls_parity(w, perms, 4, dtfm.GAIN4)
         _ls_parity(w, perms, 3, dtfm.KL)
+        _ls_parity(w, perms, 3, dtfm.BEST4)
     if 2 <= N <= 40:
         _ls_parity(w, perms, 2, dtfm.ALL_PAIRS)
         M = N * (N - 1) // 2

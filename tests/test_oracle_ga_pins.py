@@ -184,6 +184,46 @@ def test_local_search_rounds_match_definition(nb, proposal):
         assert n_applied > 0
 
 
+def test_best4_rounds_match_definition():
+    # the four candidates of a round, their order, the choice by true cost with ties to the first, acceptance
+    total = 0
+    for N, D_dp in [(8, 2), (12, 3), (12, 2), (24, 4)]:
+        D_pp = N // D_dp
+        lat, bw = _network(N, 7 * N)
+        pr = oracle.Problem(lat, bw, 2.5e8, 4e6, D_dp, D_pp)
+        cost_fn = _cost_fn(pr, D_dp, N <= 12)
+        W = pr.W_pp.tolist()
+        pairs = [(a, b) for a in range(N) for b in range(a + 1, N)]
+        rounds = D_pp * (D_pp - 1) // 2 + 2
+        perms = np.array([ds.init_candidate(2, k, N) for k in range(4)], dtype=np.int32)
+        for p in range(4):
+            for r in range(rounds):
+                assert pr.four_candidates(perms[p], r) == ds.four_candidates(W, perms[p].tolist(), D_dp, D_pp, r)
+        out, cost, applied = pr.local_search(perms, rounds, oracle.BEST4)
+        for p in range(4):
+            wperm, wcost, wapplied = ds.local_search_best4(cost_fn, W, perms[p].tolist(), D_dp, D_pp, rounds)
+            assert out[p].tolist() == wperm and cost[p] == wcost
+            assert [None if m < 0 else pairs[m] for m in applied[p]] == wapplied
+            total += sum(m is not None for m in wapplied)
+    assert total > 0
+    # the paper's own Case-5 tables: whole regions share their weights, so trials tie with each other
+    import workloads
+    w = workloads.config("C2b")
+    pr = oracle.Problem(w.latency, w.bandwidth, w.c_dp, w.c_pp, w.D_dp, w.D_pp)
+    cost_fn = _cost_fn(pr, w.D_dp, False)
+    perms = workloads.random_population(6, 64, seed=4)
+    out, cost, applied = pr.local_search(perms, 30, oracle.BEST4)
+    for p in range(6):
+        wperm, wcost, _ = ds.local_search_best4(cost_fn, pr.W_pp.tolist(), perms[p].tolist(), 8, 8, 30)
+        assert out[p].tolist() == wperm and cost[p] == wcost
+    # ties go to the first of the four: on a homogeneous network every trial ties with the current row: nothing moves
+    lat, bw = np.full((8, 8), 1e-3), np.full((8, 8), 1e9)
+    pr = oracle.Problem(lat, bw, 1e8, 4e6, 2, 4)
+    perms = np.array([ds.init_candidate(3, k, 8) for k in range(3)], dtype=np.int32)
+    out, cost, applied = pr.local_search(perms, 6, oracle.BEST4)
+    assert np.array_equal(out, perms) and np.all(applied == -1)
+
+
 def _cost_fn(pr, D_dp, brute):
     if brute:   # Eqs. 1-4 by enumeration of all stage orders and all matchings
         Wd, Wp = pr.W_dp.tolist(), pr.W_pp.tolist()
