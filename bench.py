@@ -270,7 +270,7 @@ def main():
                                           "frac": indep_ops * P_big / t_big / 1e12 / indep_peak,
                                           "is": "DataP adds and maxima + one look at each of the D_dp^2 entries of every "
                                                 "stage-pair block + Held-Karp add/min, against the 64-bit vector-op peak"},
-                "at_configured_population": {"kernel": "k_eval_fast64<4>", "launch_candidates": P, "launch_seconds": t_small,
+                "at_configured_population": {"kernel": "k_eval_fast64_paired", "launch_candidates": P, "launch_seconds": t_small,
                                              "achieved": total_ops * P / t_small / 1e12, "frac": total_ops * P / t_small / 1e12 / peak,
                                              "algorithm_independent_frac": indep_ops * P / t_small / 1e12 / indep_peak},
                 "rocprof_counters": prof,
