@@ -158,7 +158,7 @@ extern "C" int dtfm_create_problem(const double *latency, const double *bandwidt
         pr->fast64 = true;
     } else {
         // dense ranks of the pipeline weights for the matching kernel: the device-computed W_pp
-        // is read back, sorted and deduplicated once (cold path)
+        // is read back, sorted and deduplicated once (cold path); at most N^2 <= 2^20 distinct values
         std::vector<double> w((size_t)N * N), vals;
         CREATE_HIP(hipMemcpy(w.data(), pr->W_pp, mat, hipMemcpyDeviceToHost));
         vals = w;
@@ -167,6 +167,9 @@ extern "C" int dtfm_create_problem(const double *latency, const double *bandwidt
         std::vector<uint32_t> rk(w.size());
         for (size_t i = 0; i < w.size(); i++)
             rk[i] = (uint32_t)(std::lower_bound(vals.begin(), vals.end(), w[i]) - vals.begin());
+        // the matching kernel's first solve works on 16-bit codes 2 + (rank >> shift) <= 0xfffe
+        pr->rank_shift = 0;
+        while (((vals.size() - 1) >> pr->rank_shift) + 2 > 0xfffe) pr->rank_shift++;
         CREATE_HIP(hipMalloc((void **)&pr->W_rank, rk.size() * sizeof(uint32_t)));
         CREATE_HIP(hipMalloc((void **)&pr->rank_val, vals.size() * sizeof(double)));
         CREATE_HIP(hipMemcpy(pr->W_rank, rk.data(), rk.size() * sizeof(uint32_t), hipMemcpyHostToDevice));

@@ -138,32 +138,66 @@ __global__ void k_zero_f64(double *__restrict__ dst, size_t n)
 }
 
 // ------------------------------------------------------------------------------------------------
-// a4: bottleneck assignment for one (candidate, stage pair) per wavefront, lane c = column c (device
-// at slot c of the second stage). The optimum of Eq. 3 is one of the block's entries and depends
-// only on their order, so the search runs on `Wr`, the dense ranks of W_pp (equal weights share a
-// rank), and the result is mapped back through `rank_val`: no rounding is involved.
-// Lane c keeps its column of the block, E[r] = Wr[C_j1[r]][C_j2[c]], in registers; every row index
-// used below is wavefront-uniform, so E is read by register-relative moves and the search touches
-// no memory. Rows are inserted one at a time. For row r0 the alternating-path search grows a set of
-// reached rows; dist[c] is the smallest edge from a reached row to column c, and every unvisited
-// column with dist <= theta is reachable within the threshold theta. theta starts at the optimum T
-// of the rows inserted so far and is raised, only when the search is stuck, to the smallest dist of
-// an unvisited column: a perfect matching of rows 0..r0 within theta exists iff an alternating path
-// from r0 to a free column exists within theta (Berge), so the final theta is the new optimum.
-typedef uint32_t dtfm_u32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t dtfm_u32x32 __attribute__((ext_vector_type(32)));
+// a4: bottleneck assignment for one (candidate, stage pair) per wavefront (one wavefront per workgroup),
+// lane c = column c (device at slot c of the second stage). The optimum of Eq. 3 is one of the block's
+// entries and depends only on their order, so the search runs on `Wrank`, the dense ranks of W_pp (equal
+// weights share a rank), and the result is mapped back through `rank_val`: no rounding is involved.
+//
+// Invariant: a matching of some of the rows within the threshold theta, and theta <= the optimum T*.
+//  1. theta starts at the largest column minimum (every column is matched through one of its entries).
+//  2. Greedy pass, rows in order: a row takes the first free column it reaches within theta. A row with
+//     no entry within theta at all raises theta to its own minimum first (it too is matched through one
+//     of its entries). Rows that find no free column are left pending.
+//  3. Every pending row r0 is inserted by an alternating-path search: dist[c] is the smallest entry from a
+//     reached row to column c, every unvisited column with dist <= theta is reachable within theta, and
+//     the rows matched to the newly reached columns join the search. When the search is stuck, the reached
+//     rows X own one column fewer than they need among the visited ones, so some row of X is matched
+//     outside them in every perfect matching: T* >= the smallest dist of an unvisited column, and theta is
+//     raised to exactly that. An alternating path to a free column exists within theta iff a larger
+//     matching does (Berge), so after the last insertion theta = T*.
+// The order in which rows are inserted and ties between paths do not change the value.
+//
+// Lane c keeps its column of the block (ranks) in registers for the steps whose row index is known at
+// compile time (1 and 2). For the search, where the row comes from a lane, the wavefront keeps the block in
+// LDS as 16-bit codes, s_E[r * 64 + c] (all lanes read one row: no bank conflicts); 8 KiB per wavefront, and
+// the number of resident wavefronts is what this latency-bound search lives on. A code is an order-preserving
+// image of the rank, code = rank < base ? 1 : 2 + ((rank - base) >> shift), capped at 0xffff:
+//  - first solve: base 0 and the `shift` that fits the largest rank (0 up to 65,532 distinct weights): the
+//    result is the exact optimum when shift = 0, else the bucket of 2^shift ranks that holds it (a matching
+//    within a bucket exists iff one exists within the bucket's largest rank);
+//  - if the block holds more than one distinct rank of that bucket, a second solve with base = the bucket's
+//    first rank and shift 0 separates them (ranks below the bucket all count as "within", ranks above it are
+//    never needed).
+// dist carries, in its low 7 bits, 1 + the column whose matched row gave it (0: the inserted row), so relaxing
+// is one shift-OR and one unsigned minimum; a visited column parks that field in `parked` and holds
+// dist = 0 from then on, which no minimum changes. Lanes c >= D_dp hold the pad rank and never take part.
+__device__ __forceinline__ uint32_t dtfm_wave_min_u32(uint32_t k)
+{
+    // prefix minima inside each row of 16 lanes by data-parallel shifts (a lane without a source keeps its own
+    // value), then the four row results
+    k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x111, 0xF, 0xF, false));   // row_shr:1
+    k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x112, 0xF, 0xF, false));   // row_shr:2
+    k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x114, 0xF, 0xF, false));   // row_shr:4
+    k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x118, 0xF, 0xF, false));   // row_shr:8
+    const uint32_t m0 = (uint32_t)__builtin_amdgcn_readlane((int)k, 15), m1 = (uint32_t)__builtin_amdgcn_readlane((int)k, 31);
+    const uint32_t m2 = (uint32_t)__builtin_amdgcn_readlane((int)k, 47), m3 = (uint32_t)__builtin_amdgcn_readlane((int)k, 63);
+    return min(min(m0, m1), min(m2, m3));
+}
 
-template <int NB>  // number of 16-row register blocks: D_dp <= 16 * NB
-__global__ void __launch_bounds__(256)
-k_match(const uint32_t *__restrict__ Wr, const double *__restrict__ rank_val,
-        const int32_t *__restrict__ perm, int N, int D_dp, int D_pp, int npairs, size_t total,
+#define DTFM_MATCH_PAD 0x3fffffffu   // rank of the entries outside the block: above every rank, far from overflow
+
+template <int NB>  // number of 16-row blocks: D_dp <= 16 * NB
+__global__ void __launch_bounds__(DTFM_WAVE) __attribute__((amdgpu_waves_per_eu(5)))
+k_match(const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val, int shift0,
+        const int32_t *__restrict__ perm, int N, int D_dp, int D_pp,
         double *__restrict__ ghat, int inc_j, int inc_jp)
 {
-    const int lane = threadIdx.x & (DTFM_WAVE - 1);
-    size_t item = (size_t)blockIdx.x * (blockDim.x / DTFM_WAVE) + threadIdx.x / DTFM_WAVE;
-    if (item >= total) return;  // whole wavefront leaves together
-    size_t p = item / npairs;
-    int t = (int)(item - p * npairs);
+    constexpr int R = 16 * NB, RS = R - 16;   // rows below RS exist for every D_dp this instance is launched for
+    extern __shared__ uint16_t s_E[];   // R x 64 codes
+    const int lane = threadIdx.x;
+    const bool active = lane < D_dp;
+    const size_t p = blockIdx.x;   // candidate
+    const int t = (int)blockIdx.y; // stage pair
     int j1, j2;
     if (inc_j < 0) {
         // t-th stage pair (j1 < j2) in lexicographic order
@@ -175,7 +209,7 @@ k_match(const uint32_t *__restrict__ Wr, const double *__restrict__ rank_val,
         }
         j2 = j1 + 1 + rem;
     } else {
-        // only the npairs = 2 D_pp - 3 pairs that contain stage inc_j or inc_jp (inc_j < inc_jp): (inc_j, k) for
+        // only the 2 D_pp - 3 pairs that contain stage inc_j or inc_jp (inc_j < inc_jp): (inc_j, k) for
         // the D_pp - 1 stages k != inc_j, then (inc_jp, k) for the D_pp - 2 others
         int a, k;
         if (t < D_pp - 1) {
@@ -191,100 +225,148 @@ k_match(const uint32_t *__restrict__ Wr, const double *__restrict__ rank_val,
         j2 = a < k ? k : a;
     }
     const int32_t *row = perm + p * N;
-    const int32_t *Ca = row + j1 * D_dp;
-    const bool active = lane < D_dp;
-    const uint32_t *col = Wr + (active ? row[j2 * D_dp + lane] : 0);
+    const int32_t *Ca = row + j1 * D_dp;   // wavefront-uniform: read through the scalar cache
+    const uint32_t *col = Wrank + (active ? row[j2 * D_dp + lane] : 0);
 
-    // The block's column for this lane in registers: 16 entries (NB = 1), 32 (NB = 2) or two vectors of 32.
-    dtfm_u32x16 E0;
-    dtfm_u32x32 F0, F1;
+    uint32_t E[R];
+    uint32_t colmin = DTFM_MATCH_PAD;
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-        if (NB == 1) E0[r] = r < D_dp ? col[(size_t)Ca[r] * N] : 0xffffffffu;
+    for (int r = 0; r < R; r++) {
+        const bool real = r < RS || r < D_dp;
+        const uint32_t v = col[(size_t)Ca[real ? r : 0] * N];
+        E[r] = (active && real) ? v : DTFM_MATCH_PAD;
+        colmin = min(colmin, E[r]);
     }
-#pragma unroll
-    for (int r = 0; r < 32; r++) {
-        if (NB > 1) F0[r] = r < D_dp ? col[(size_t)Ca[r] * N] : 0xffffffffu;
-        if (NB > 2) F1[r] = r + 32 < D_dp ? col[(size_t)Ca[r + 32] * N] : 0xffffffffu;
-    }
-    // E[r] for a wavefront-uniform r. The empty asm statements keep the two register-relative
-    // reads apart (merged into one 64-entry access they would go through scratch memory).
-    auto entry = [&](int r) -> uint32_t {
-        if (NB == 1) return E0[r & 15];
-        const int lo = r & 31, hi = r >> 5;
-        uint32_t w = F0[lo];
-        if (NB > 2) {
-            asm volatile("" : "+v"(w));
-            uint32_t x = F1[lo];
-            asm volatile("" : "+v"(x));
-            w = hi == 1 ? x : w;
-        }
-        return w;
-    };
+    // the largest column minimum = ~ the smallest of the complements (idle lanes: complement of 0)
+    const uint32_t maxcolmin = ~dtfm_wave_min_u32(active ? ~colmin : 0xffffffffu);
 
     const uint64_t allcols = D_dp >= 64 ? ~0ull : ((1ull << D_dp) - 1ull);
-    uint64_t freecols = allcols;  // columns not matched yet
-    int match_row = 0;            // row matched to this lane's column (meaningful when not free)
-    uint32_t T = 0;
-    for (int r0 = 0; r0 < D_dp; r0++) {
-        uint32_t dist = entry(r0);
-        int prev = -1;  // column whose matched row gave `dist`; -1: the inserted row itself
-        uint64_t visited = 0;
-        uint32_t theta = T;
-        int cfin = -1;
-        // every pass visits at least one new column, ends the search, or follows a raise of theta
-        // that makes the next pass do so: at most 2 (r0 + 1) passes
-        for (int pass = 0; pass < 2 * 16 * NB + 2; pass++) {
-            uint64_t reach = __ballot(dist <= theta) & ~visited & allcols;
-            if (reach == 0ull) {
-                // smallest dist of an unvisited column: prefix minima inside each row of 16 lanes by data-parallel
-                // shifts (a lane without a source keeps its own value), then the four row results
-                uint32_t k = (((visited >> lane) & 1ull) != 0ull || !active) ? 0xffffffffu : dist;
-                k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x111, 0xF, 0xF, false));   // row_shr:1
-                k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x112, 0xF, 0xF, false));   // row_shr:2
-                k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x114, 0xF, 0xF, false));   // row_shr:4
-                k = min(k, (uint32_t)__builtin_amdgcn_update_dpp((int)k, (int)k, 0x118, 0xF, 0xF, false));   // row_shr:8
-                const uint32_t m0 = (uint32_t)__builtin_amdgcn_readlane((int)k, 15), m1 = (uint32_t)__builtin_amdgcn_readlane((int)k, 31);
-                const uint32_t m2 = (uint32_t)__builtin_amdgcn_readlane((int)k, 47), m3 = (uint32_t)__builtin_amdgcn_readlane((int)k, 63);
-                theta = min(min(m0, m1), min(m2, m3));
-                continue;
-            }
-            uint64_t hit = reach & freecols;
-            if (hit != 0ull) {
-                cfin = __builtin_ctzll(hit);
-                break;
-            }
-            visited |= reach;
-            const bool open = ((visited >> lane) & 1ull) == 0ull;  // a visited column keeps its path
-            while (reach != 0ull) {  // the rows matched to the newly reached columns join the search
-                const int c = __builtin_ctzll(reach);
-                reach &= reach - 1ull;
-                const int mr = __builtin_amdgcn_readlane(match_row, c);
-                const uint32_t w = entry(mr);
-                if (open && w < dist) {
-                    dist = w;
-                    prev = c;
+    uint32_t base = 0u;
+    int shift = shift0;
+    uint32_t result = 0xffffffffu;   // rank of the optimum; stays so if a search fails (cannot happen for a finite block)
+    for (int solve = 0; solve < 2; solve++) {
+        // codes of this solve into LDS
+        __syncthreads();   // one wavefront: orders its own LDS accesses
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+            const uint32_t d = E[r] - base;
+            uint32_t code = min((d >> shift) + 2u, 0xffffu);
+            if (solve > 0 && E[r] < base) code = 1u;
+            s_E[r * DTFM_WAVE + lane] = (uint16_t)code;
+        }
+        __syncthreads();
+        // theta as a code; a key (code << 7 | field) is within theta iff key <= thr, a rank iff rank <= thr_rank
+        uint32_t theta = maxcolmin < base ? 1u : ((maxcolmin - base) >> shift) + 2u;
+        uint32_t thr = (theta << 7) | 127u;
+        uint32_t thr_rank = base + ((theta - 1u) << shift) - 1u;
+
+        // step 2
+        uint64_t freecols = allcols, pending = 0ull;
+        int match_off = 0;   // s_E offset of the row matched to this lane's column (meaningful when not free)
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+            if (r < RS || r < D_dp) {
+                uint64_t m = __ballot(E[r] <= thr_rank);
+                if (m == 0ull) {
+                    const uint32_t rowmin = dtfm_wave_min_u32(E[r]);   // > thr_rank >= base - 1
+                    theta = ((rowmin - base) >> shift) + 2u;
+                    thr = (theta << 7) | 127u;
+                    thr_rank = base + ((theta - 1u) << shift) - 1u;
+                    m = __ballot(E[r] <= thr_rank);
+                }
+                m &= freecols;
+                if (m != 0ull) {
+                    const int c = __builtin_ctzll(m);
+                    freecols &= ~(1ull << c);
+                    if (lane == c) match_off = r * DTFM_WAVE;
+                } else {
+                    pending |= 1ull << r;
                 }
             }
         }
-        if (cfin < 0) {  // cannot happen for a finite block; leaves +inf rather than a wrong value
-            T = 0xffffffffu;
+
+        // step 3
+        bool failed = false;
+        while (pending != 0ull && !failed) {
+            const int r0 = __builtin_ctzll(pending);
+            pending &= pending - 1ull;
+            uint32_t dist = (uint32_t)s_E[r0 * DTFM_WAVE + lane] << 7;
+            uint32_t parked = 0u;
+            int cfin = -1;
+            // every pass visits at least one new column, ends the search, or follows a raise of theta
+            // that makes the next pass do so: at most 2 D_dp + 1 passes
+            for (int pass = 0; pass < 2 * R + 2; pass++) {
+                const bool newly = dist <= thr && dist != 0u;
+                uint64_t reach = __ballot(newly);
+                if (reach == 0ull) {
+                    // smallest dist of an unvisited column; dist - 1 sends the visited ones (0) to the top
+                    const uint32_t k = dtfm_wave_min_u32(dist - 1u);
+                    if (k >= (0xffffu << 7) - 1u) break;   // no unvisited column with an entry of the block
+                    thr = (k + 1u) | 127u;
+                    continue;
+                }
+                const uint64_t hit = reach & freecols;
+                if (hit != 0ull) {
+                    cfin = __builtin_ctzll(hit);
+                    break;
+                }
+                if (newly) {
+                    parked = dist & 127u;
+                    dist = 0u;
+                }
+                do {   // the rows matched to the newly reached columns join the search, two per turn
+                    const int c0 = __builtin_ctzll(reach);
+                    reach &= reach - 1ull;
+                    const int c1 = reach != 0ull ? __builtin_ctzll(reach) : c0;
+                    reach &= reach - 1ull;
+                    const int o0 = __builtin_amdgcn_readlane(match_off, c0), o1 = __builtin_amdgcn_readlane(match_off, c1);
+                    const uint32_t w0 = ((uint32_t)s_E[o0 + lane] << 7) | (uint32_t)(c0 + 1);
+                    const uint32_t w1 = ((uint32_t)s_E[o1 + lane] << 7) | (uint32_t)(c1 + 1);
+                    dist = min(dist, min(w0, w1));
+                } while (reach != 0ull);
+            }
+            if (cfin < 0) {
+                failed = true;
+                break;
+            }
+            // flip the path: column c takes the row of its predecessor column; the first column takes r0
+            const int via = (int)(dist == 0u ? parked : (dist & 127u));
+            int c = cfin;
+            for (int step = 0; step <= D_dp; step++) {  // a path has at most D_dp columns
+                const int pc = __builtin_amdgcn_readlane(via, c);
+                const int poff = __builtin_amdgcn_readlane(match_off, pc == 0 ? 0 : pc - 1);
+                if (lane == c) match_off = pc == 0 ? r0 * DTFM_WAVE : poff;
+                if (pc == 0) break;
+                c = pc - 1;
+            }
+            freecols &= ~(1ull << cfin);
+        }
+        theta = thr >> 7;   // >= 2: the first solve has no code 1, the second no matching below its bucket
+        if (failed || theta < 2u) break;
+        const uint32_t first = base + ((theta - 2u) << shift);   // first rank of the optimum's bucket
+        if (shift == 0) {
+            result = first;
             break;
         }
-        T = theta;
-        // flip the path: column c takes the row of its predecessor column; the first column takes r0
-        int c = cfin;
-        for (int step = 0; step <= r0; step++) {  // a path has at most r0 + 1 columns
-            const int pc = __builtin_amdgcn_readlane(prev, c);
-            const int prow = __builtin_amdgcn_readlane(match_row, pc < 0 ? 0 : pc);
-            if (lane == c) match_row = pc < 0 ? r0 : prow;
-            if (pc < 0) break;
-            c = pc;
+        // ranks of the block inside the bucket: the smallest and the largest
+        const uint32_t last = first + (1u << shift) - 1u;
+        uint32_t lo = 0xffffffffu, hi = 0xffffffffu;
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+            lo = min(lo, E[r] - first);   // below the bucket: wraps to the top
+            hi = min(hi, last - E[r]);    // above the bucket: wraps to the top
         }
-        freecols &= ~(1ull << cfin);
+        lo = dtfm_wave_min_u32(lo);
+        hi = dtfm_wave_min_u32(hi);
+        if (first + lo == last - hi) {
+            result = first + lo;
+            break;
+        }
+        base = first;
+        shift = 0;
     }
     if (lane == 0) {
-        const double v = T == 0xffffffffu ? INFINITY : rank_val[T];
+        const double v = result == 0xffffffffu ? INFINITY : rank_val[result];
         double *G = ghat + p * D_pp * D_pp;
         G[j1 * D_pp + j2] = v;
         G[j2 * D_pp + j1] = v;
@@ -636,12 +718,13 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
     DTFM_HIP(hipGetLastError());
     if (pr->npairs > 0) {
         const int match_pairs = inc_j >= 0 ? 2 * n - 3 : pr->npairs;
-        size_t total = rows * (size_t)match_pairs;
-        const int waves_per_block = 4;
-        size_t blocks = (total + waves_per_block - 1) / waves_per_block;
-        auto kern = pr->D_dp <= 16 ? k_match<1> : pr->D_dp <= 32 ? k_match<2> : pr->D_dp <= 48 ? k_match<3> : k_match<4>;
-        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(waves_per_block * DTFM_WAVE), 0, st,
-                           pr->W_rank, pr->rank_val, perm, N, pr->D_dp, n, match_pairs, total, b.ghat, inc_j, inc_jp);
+        const int nb = (pr->D_dp + 15) / 16;
+        if (rows > 0x7fffffffu) return DTFM_ERR_ARG;
+        auto kern = nb <= 1 ? k_match<1> : nb == 2 ? k_match<2> : nb == 3 ? k_match<3> : k_match<4>;
+        // one wavefront per (candidate, stage pair)
+        hipLaunchKernelGGL(kern, dim3((unsigned)rows, (unsigned)match_pairs), dim3(DTFM_WAVE),
+                           (size_t)16 * nb * DTFM_WAVE * sizeof(uint16_t), st, pr->W_rank, pr->rank_val, pr->rank_shift, perm, N, pr->D_dp, n,
+                           b.ghat, inc_j, inc_jp);
         DTFM_HIP(hipGetLastError());
     }
     if (cost == nullptr) return DTFM_OK;
