@@ -164,12 +164,13 @@ extern "C" int dtfm_create_problem(const double *latency, const double *bandwidt
         vals = w;
         std::sort(vals.begin(), vals.end());
         vals.erase(std::unique(vals.begin(), vals.end()), vals.end());
-        std::vector<uint32_t> rk(w.size());
-        for (size_t i = 0; i < w.size(); i++)
-            rk[i] = (uint32_t)(std::lower_bound(vals.begin(), vals.end(), w[i]) - vals.begin());
-        // the matching kernel's first solve works on 16-bit codes 2 + (rank >> shift) <= 0xfffe
+        // the matching kernel's first solve works on 16-bit codes 2 + (rank >> shift) <= 0xfffe; the table holds
+        // rank + (2 << shift), whose shift is that code
         pr->rank_shift = 0;
         while (((vals.size() - 1) >> pr->rank_shift) + 2 > 0xfffe) pr->rank_shift++;
+        std::vector<uint32_t> rk(w.size());
+        for (size_t i = 0; i < w.size(); i++)
+            rk[i] = (uint32_t)(std::lower_bound(vals.begin(), vals.end(), w[i]) - vals.begin()) + (2u << pr->rank_shift);
         CREATE_HIP(hipMalloc((void **)&pr->W_rank, rk.size() * sizeof(uint32_t)));
         CREATE_HIP(hipMalloc((void **)&pr->rank_val, vals.size() * sizeof(double)));
         CREATE_HIP(hipMemcpy(pr->W_rank, rk.data(), rk.size() * sizeof(uint32_t), hipMemcpyHostToDevice));

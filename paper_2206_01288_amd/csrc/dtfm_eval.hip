@@ -184,7 +184,21 @@ __device__ __forceinline__ uint32_t dtfm_wave_min_u32(uint32_t k)
     return min(min(m0, m1), min(m2, m3));
 }
 
-#define DTFM_MATCH_PAD 0x3fffffffu   // rank of the entries outside the block: above every rank, far from overflow
+// Scalar bit scans of a 64-bit mask in one instruction each: the index of the lowest set bit (-1 for an empty
+// mask), and the mask with one bit cleared.
+__device__ __forceinline__ int dtfm_first_bit(uint64_t m)
+{
+    int c;
+    asm("s_ff1_i32_b64 %0, %1" : "=s"(c) : "s"(m));
+    return c;
+}
+__device__ __forceinline__ uint64_t dtfm_clear_bit(uint64_t m, int bit)
+{
+    asm("s_bitset0_b64 %0, %1" : "+s"(m) : "s"(bit));
+    return m;
+}
+
+#define DTFM_MATCH_ROOT 127u   // `via` field of a dist that comes from the inserted row itself
 
 template <int NB>  // number of 16-row blocks: D_dp <= 16 * NB
 __global__ void __launch_bounds__(DTFM_WAVE) __attribute__((amdgpu_waves_per_eu(5)))
@@ -226,59 +240,65 @@ k_match(const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val,
     }
     const int32_t *row = perm + p * N;
     const int32_t *Ca = row + j1 * D_dp;   // wavefront-uniform: read through the scalar cache
-    const uint32_t *col = Wrank + (active ? row[j2 * D_dp + lane] : 0);
+    // byte offsets into Wrank (N * N * 4 <= 4 MiB): a uniform row term plus the lane's column
+    const uint32_t colbyte = active ? (uint32_t)row[j2 * D_dp + lane] * 4u : 0u, N4 = (uint32_t)N * 4u;
 
+    // Wrank holds rank + bias with bias = 2 << shift0, so that the first solve's code is one shift; entries outside
+    // the block take the pad, whose code is 0xffff and which is above every biased rank
+    const uint32_t pad = 0xffffu << shift0, bias = 2u << shift0;
     uint32_t E[R];
-    uint32_t colmin = DTFM_MATCH_PAD;
+    uint32_t colmin = pad;
 #pragma unroll
     for (int r = 0; r < R; r++) {
         const bool real = r < RS || r < D_dp;
-        const uint32_t v = col[(size_t)Ca[real ? r : 0] * N];
-        E[r] = (active && real) ? v : DTFM_MATCH_PAD;
+        const uint32_t v = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(Wrank) +
+                                                               ((uint32_t)Ca[real ? r : 0] * N4 + colbyte));
+        E[r] = (active && real) ? v : pad;
         colmin = min(colmin, E[r]);
     }
     // the largest column minimum = ~ the smallest of the complements (idle lanes: complement of 0)
     const uint32_t maxcolmin = ~dtfm_wave_min_u32(active ? ~colmin : 0xffffffffu);
 
     const uint64_t allcols = D_dp >= 64 ? ~0ull : ((1ull << D_dp) - 1ull);
-    uint32_t base = 0u;
+    uint32_t base = 0u;   // biased rank below which every entry has code 1 (second solve)
     int shift = shift0;
-    uint32_t result = 0xffffffffu;   // rank of the optimum; stays so if a search fails (cannot happen for a finite block)
+    uint32_t result = 0xffffffffu;   // biased rank of the optimum; stays so if a search fails (cannot happen for a finite block)
     for (int solve = 0; solve < 2; solve++) {
         // codes of this solve into LDS
         __syncthreads();   // one wavefront: orders its own LDS accesses
+        if (solve == 0) {
 #pragma unroll
-        for (int r = 0; r < R; r++) {
-            const uint32_t d = E[r] - base;
-            uint32_t code = min((d >> shift) + 2u, 0xffffu);
-            if (solve > 0 && E[r] < base) code = 1u;
-            s_E[r * DTFM_WAVE + lane] = (uint16_t)code;
+            for (int r = 0; r < R; r++) s_E[r * DTFM_WAVE + lane] = (uint16_t)(E[r] >> shift);
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; r++)
+                s_E[r * DTFM_WAVE + lane] = (uint16_t)(E[r] < base ? 1u : min(E[r] - base + 2u, 0xffffu));
         }
         __syncthreads();
-        // theta as a code; a key (code << 7 | field) is within theta iff key <= thr, a rank iff rank <= thr_rank
-        uint32_t theta = maxcolmin < base ? 1u : ((maxcolmin - base) >> shift) + 2u;
+        // theta as a code; a key (code << 7 | via) is within theta iff key <= thr, a biased rank iff it is <= thr_rank
+        uint32_t theta = solve == 0 ? maxcolmin >> shift : (maxcolmin < base ? 1u : maxcolmin - base + 2u);
         uint32_t thr = (theta << 7) | 127u;
-        uint32_t thr_rank = base + ((theta - 1u) << shift) - 1u;
+        uint32_t thr_rank = solve == 0 ? ((theta + 1u) << shift) - 1u : base + theta - 2u;
 
         // step 2
         uint64_t freecols = allcols, pending = 0ull;
-        int match_off = 0;   // s_E offset of the row matched to this lane's column (meaningful when not free)
+        int match_row = 0;   // row matched to this lane's column (meaningful when not free)
 #pragma unroll
         for (int r = 0; r < R; r++) {
             if (r < RS || r < D_dp) {
                 uint64_t m = __ballot(E[r] <= thr_rank);
                 if (m == 0ull) {
-                    const uint32_t rowmin = dtfm_wave_min_u32(E[r]);   // > thr_rank >= base - 1
-                    theta = ((rowmin - base) >> shift) + 2u;
+                    const uint32_t rowmin = dtfm_wave_min_u32(E[r]);   // > thr_rank
+                    theta = solve == 0 ? rowmin >> shift : rowmin - base + 2u;
                     thr = (theta << 7) | 127u;
-                    thr_rank = base + ((theta - 1u) << shift) - 1u;
+                    thr_rank = solve == 0 ? ((theta + 1u) << shift) - 1u : base + theta - 2u;
                     m = __ballot(E[r] <= thr_rank);
                 }
                 m &= freecols;
                 if (m != 0ull) {
-                    const int c = __builtin_ctzll(m);
-                    freecols &= ~(1ull << c);
-                    if (lane == c) match_off = r * DTFM_WAVE;
+                    const int c = dtfm_first_bit(m);
+                    freecols = dtfm_clear_bit(freecols, c);
+                    if (lane == c) match_row = r;
                 } else {
                     pending |= 1ull << r;
                 }
@@ -287,43 +307,42 @@ k_match(const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val,
 
         // step 3
         bool failed = false;
-        while (pending != 0ull && !failed) {
-            const int r0 = __builtin_ctzll(pending);
-            pending &= pending - 1ull;
-            uint32_t dist = (uint32_t)s_E[r0 * DTFM_WAVE + lane] << 7;
+        while (pending != 0ull) {
+            const int r0 = dtfm_first_bit(pending);
+            pending = dtfm_clear_bit(pending, r0);
+            uint32_t dist = ((uint32_t)s_E[r0 * DTFM_WAVE + lane] << 7) | DTFM_MATCH_ROOT;
             uint32_t parked = 0u;
             int cfin = -1;
-            // every pass visits at least one new column, ends the search, or follows a raise of theta
-            // that makes the next pass do so: at most 2 D_dp + 1 passes
-            for (int pass = 0; pass < 2 * R + 2; pass++) {
-                const bool newly = dist <= thr && dist != 0u;
-                uint64_t reach = __ballot(newly);
+            uint64_t reach = __ballot(dist - 1u < thr);   // unvisited (dist != 0) and within theta
+            // every turn parks at least one column or ends the search: at most D_dp turns
+            for (int turn = 0; turn <= R; turn++) {
                 if (reach == 0ull) {
-                    // smallest dist of an unvisited column; dist - 1 sends the visited ones (0) to the top
+                    // stuck: the smallest dist of an unvisited column; dist - 1 sends the visited ones (0) to the top
                     const uint32_t k = dtfm_wave_min_u32(dist - 1u);
                     if (k >= (0xffffu << 7) - 1u) break;   // no unvisited column with an entry of the block
                     thr = (k + 1u) | 127u;
-                    continue;
+                    reach = __ballot(dist - 1u < thr);
                 }
                 const uint64_t hit = reach & freecols;
                 if (hit != 0ull) {
-                    cfin = __builtin_ctzll(hit);
+                    cfin = dtfm_first_bit(hit);
                     break;
                 }
-                if (newly) {
+                if (dist - 1u < thr) {
                     parked = dist & 127u;
                     dist = 0u;
                 }
                 do {   // the rows matched to the newly reached columns join the search, two per turn
-                    const int c0 = __builtin_ctzll(reach);
-                    reach &= reach - 1ull;
-                    const int c1 = reach != 0ull ? __builtin_ctzll(reach) : c0;
-                    reach &= reach - 1ull;
-                    const int o0 = __builtin_amdgcn_readlane(match_off, c0), o1 = __builtin_amdgcn_readlane(match_off, c1);
-                    const uint32_t w0 = ((uint32_t)s_E[o0 + lane] << 7) | (uint32_t)(c0 + 1);
-                    const uint32_t w1 = ((uint32_t)s_E[o1 + lane] << 7) | (uint32_t)(c1 + 1);
+                    const int c0 = dtfm_first_bit(reach);
+                    reach = dtfm_clear_bit(reach, c0);
+                    const int c1 = max(dtfm_first_bit(reach), c0);   // none left: c0 once more
+                    reach = dtfm_clear_bit(reach, c1);
+                    const int m0 = __builtin_amdgcn_readlane(match_row, c0), m1 = __builtin_amdgcn_readlane(match_row, c1);
+                    const uint32_t w0 = ((uint32_t)s_E[m0 * DTFM_WAVE + lane] << 7) | (uint32_t)c0;
+                    const uint32_t w1 = ((uint32_t)s_E[m1 * DTFM_WAVE + lane] << 7) | (uint32_t)c1;
                     dist = min(dist, min(w0, w1));
                 } while (reach != 0ull);
+                reach = __ballot(dist - 1u < thr);
             }
             if (cfin < 0) {
                 failed = true;
@@ -334,16 +353,20 @@ k_match(const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val,
             int c = cfin;
             for (int step = 0; step <= D_dp; step++) {  // a path has at most D_dp columns
                 const int pc = __builtin_amdgcn_readlane(via, c);
-                const int poff = __builtin_amdgcn_readlane(match_off, pc == 0 ? 0 : pc - 1);
-                if (lane == c) match_off = pc == 0 ? r0 * DTFM_WAVE : poff;
-                if (pc == 0) break;
-                c = pc - 1;
+                const int prow = __builtin_amdgcn_readlane(match_row, pc & 63);
+                if (lane == c) match_row = pc == (int)DTFM_MATCH_ROOT ? r0 : prow;
+                if (pc == (int)DTFM_MATCH_ROOT) break;
+                c = pc;
             }
-            freecols &= ~(1ull << cfin);
+            freecols = dtfm_clear_bit(freecols, cfin);
         }
-        theta = thr >> 7;   // >= 2: the first solve has no code 1, the second no matching below its bucket
+        theta = thr >> 7;   // >= 2: the first solve has no code below 2, the second no matching below its bucket
         if (failed || theta < 2u) break;
-        const uint32_t first = base + ((theta - 2u) << shift);   // first rank of the optimum's bucket
+        if (solve > 0) {
+            result = base + theta - 2u;
+            break;
+        }
+        const uint32_t first = theta << shift;   // first biased rank of the optimum's bucket
         if (shift == 0) {
             result = first;
             break;
@@ -366,7 +389,7 @@ k_match(const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val,
         shift = 0;
     }
     if (lane == 0) {
-        const double v = result == 0xffffffffu ? INFINITY : rank_val[result];
+        const double v = result == 0xffffffffu ? INFINITY : rank_val[result - bias];
         double *G = ghat + p * D_pp * D_pp;
         G[j1 * D_pp + j2] = v;
         G[j2 * D_pp + j1] = v;
