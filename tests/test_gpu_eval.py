@@ -180,6 +180,23 @@ def test_odd_and_degenerate_shapes(D_dp, D_pp):
         assert_costs_equal(host(dtfm.eval_population(g, dev(perms))), o.eval_population(perms))
 
 
+@pytest.mark.parametrize("D_dp,D_pp,P", [(24, 16, 24), (40, 13, 24), (48, 16, 16), (64, 12, 12)])
+def test_matching_on_bucketed_ranks(D_dp, D_pp, P):
+    # more than 65,532 distinct pipeline weights: the matching kernel first solves on ranks shifted into 16 bits and,
+    # where a block holds several ranks of the optimum's bucket, solves again inside the bucket. Every stage pair of
+    # every candidate against the oracle's coarsened graph; a few whole costs too.
+    N = D_dp * D_pp
+    w = custom(N, D_dp, D_pp, seed=N + 3)
+    assert N * (N - 1) // 2 > 65532
+    o, g = both(w)
+    perms = workloads.random_population(P, N, seed=D_dp)
+    ghat, datap = dtfm.coarsened_graph(g, dev(perms))
+    ghat = host(ghat)
+    for p in range(P):
+        assert np.array_equal(ghat[p], o.coarsen(perms[p])), (D_dp, D_pp, p)
+    assert_costs_equal(host(dtfm.eval_population(g, dev(perms[:3]))), o.eval_population(perms[:3]))
+
+
 def test_ragged_population_sizes_and_empty():
     w = workloads.config("C2")
     o, g = both(w)
