@@ -227,7 +227,7 @@ extern "C" int dtfm_eval_population(dtfm_problem *pr, const int32_t *perm, int P
 static int carve_fixed(const dtfm_problem *pr, size_t P, dtfm_eval_bufs *b)
 {
     dtfm_arena measure = {nullptr, 0};
-    dtfm_eval_carve(pr, measure, P, 1);
+    dtfm_eval_carve(pr, measure, P, 1, true);
     if (measure.off > DTFM_FIXED_SCRATCH_BYTES) return DTFM_ERR_TOO_LARGE;
     size_t cap = 0;
     const size_t area = (dtfm_hk_exchange_bytes(pr) + 255) & ~(size_t)255;
@@ -237,13 +237,13 @@ static int carve_fixed(const dtfm_problem *pr, size_t P, dtfm_eval_bufs *b)
         // rounding of the carved pieces to 256 bytes: make sure the chosen number fits
         for (;; cap--) {
             dtfm_arena m2 = {nullptr, 0};
-            dtfm_eval_carve(pr, m2, P, cap);
+            dtfm_eval_carve(pr, m2, P, cap, true);
             if (m2.off <= DTFM_FIXED_SCRATCH_BYTES) break;
             if (cap == 1) return DTFM_ERR_TOO_LARGE;
         }
     }
     dtfm_arena ar = {pr->fixed_scratch, 0};
-    *b = dtfm_eval_carve(pr, ar, P, cap);
+    *b = dtfm_eval_carve(pr, ar, P, cap, true);
     return DTFM_OK;
 }
 

@@ -131,6 +131,72 @@ __global__ void k_datap_sliced(const double *__restrict__ W_dp, const int32_t *_
     }
 }
 
+// Eq. 2 by device, for the same large matrices as k_datap_sliced, when a stage is a whole number of 16-byte pieces of
+// the row (D_dp a multiple of 4, rows 16-byte aligned). A gather of W_dp from L2 moves a cache sector per 8 bytes
+// used; here every workgroup keeps DTFM_DATAP_DPW rows of W_dp in LDS and sums, for each candidate of its share,
+// the row sums of those devices: the device's position comes from the inverse of the row (k_positions), the
+// members of its stage are read as contiguous 16-byte pieces, and the entries come from LDS. The sum runs over
+// the stage's slots in order from +0.0; the device's own slot adds W_dp[d][d] = +0.0, which leaves the (non-
+// negative) sum as it is, so the bits are those of the sum that skips it. Row sums go to rowsum[p][position];
+// k_datap_reduce takes the maximum per candidate.
+#define DTFM_DATAP_DPW 4
+#define DTFM_DATAP_SPLIT 4   // workgroups that share a group of devices; each takes every SPLIT-th pass of candidates
+
+__global__ void k_positions(const int32_t *__restrict__ perm, int N, size_t total, int32_t *__restrict__ pos)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const size_t p = i / (size_t)N;
+    const uint32_t d = (uint32_t)perm[i];
+    if (d < (uint32_t)N) pos[p * N + d] = (int32_t)(i - p * N);
+}
+
+__global__ void __launch_bounds__(256)
+k_datap_rows(const double *__restrict__ W_dp, const int32_t *__restrict__ perm, const int32_t *__restrict__ pos, int N,
+             int D_dp, size_t P, double *__restrict__ rowsum)
+{
+    extern __shared__ double s_W[];   // DTFM_DATAP_DPW rows of W_dp
+    const int d0 = (int)(blockIdx.x / DTFM_DATAP_SPLIT) * DTFM_DATAP_DPW, share = (int)(blockIdx.x % DTFM_DATAP_SPLIT);
+    for (int e = threadIdx.x; e < DTFM_DATAP_DPW * N; e += blockDim.x) s_W[e] = W_dp[(size_t)d0 * N + e];
+    __syncthreads();
+    const int r = threadIdx.x % DTFM_DATAP_DPW;
+    const size_t per = blockDim.x / DTFM_DATAP_DPW;   // candidates per pass
+    const double *wr = s_W + r * N;
+    const uint32_t last = (uint32_t)N - 1u;
+    for (size_t p = (size_t)share * per + threadIdx.x / DTFM_DATAP_DPW; p < P; p += per * DTFM_DATAP_SPLIT) {
+        // a row that is not a permutation leaves positions unwritten: any value is kept inside the row
+        const uint32_t q = min((uint32_t)pos[p * N + d0 + r], last);
+        const uint32_t j = q / (uint32_t)D_dp;
+        const int4 *C = reinterpret_cast<const int4 *>(perm + p * N + (size_t)j * D_dp);
+        double sum = 0.0;
+        for (int k4 = 0; k4 < D_dp / 4; k4++) {
+            const int4 c = C[k4];
+            sum = __dadd_rn(sum, wr[min((uint32_t)c.x, last)]);
+            sum = __dadd_rn(sum, wr[min((uint32_t)c.y, last)]);
+            sum = __dadd_rn(sum, wr[min((uint32_t)c.z, last)]);
+            sum = __dadd_rn(sum, wr[min((uint32_t)c.w, last)]);
+        }
+        rowsum[p * N + q] = sum;
+    }
+}
+
+// max over a candidate's row sums (all weights are >= 0, so every row sum is >= +0.0); also zeroes the diagonal
+// of the candidate's coarsened graph
+__global__ void __launch_bounds__(256)
+k_datap_reduce(const double *__restrict__ rowsum, int N, int D_pp, double *__restrict__ datap, double *__restrict__ ghat)
+{
+    __shared__ double s_red[4];
+    const size_t p = blockIdx.x;
+    double worst = 0.0;
+    for (int q = threadIdx.x; q < N; q += blockDim.x) worst = fmax(worst, rowsum[p * N + q]);
+    if (ghat != nullptr)
+        for (int j = threadIdx.x; j < D_pp; j += blockDim.x) ghat[(p * D_pp + j) * D_pp + j] = 0.0;
+    for (int o = 32; o >= 1; o >>= 1) worst = fmax(worst, __shfl_xor(worst, o));
+    if ((threadIdx.x & (DTFM_WAVE - 1)) == 0) s_red[threadIdx.x / DTFM_WAVE] = worst;
+    __syncthreads();
+    if (threadIdx.x == 0) datap[p] = fmax(fmax(s_red[0], s_red[1]), fmax(s_red[2], s_red[3]));
+}
+
 __global__ void k_zero_f64(double *__restrict__ dst, size_t n)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -689,10 +755,22 @@ size_t dtfm_hk_exchange_bytes(const dtfm_problem *pr)
     return ((nh << nh) << DTFM_HK_BLOCK_LOW) * sizeof(double);
 }
 
-dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows, size_t hk_grid_cap)
+// DataP by device (k_datap_rows) pays when W_dp is too large for an XCD's L2; it needs D_dp a multiple of 4
+static bool datap_by_device(const dtfm_problem *pr)
+{
+    return (size_t)pr->N * pr->N * sizeof(double) > ((size_t)2 << 20) && pr->D_dp % 4 == 0 && pr->N % DTFM_DATAP_DPW == 0;
+}
+
+dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows, size_t hk_grid_cap, bool lean)
 {
     dtfm_eval_bufs b;
     size_t n = pr->D_pp;
+    b.pos = nullptr;
+    b.rowsum = nullptr;
+    if (!lean && datap_by_device(pr)) {
+        b.pos = ar.take<int32_t>(rows * pr->N);
+        b.rowsum = ar.take<double>(rows * pr->N);
+    }
     b.datap = ar.take<double>(rows);
     b.ghat = ar.take<double>(rows * n * n);
     b.hk_tab = nullptr;
@@ -726,7 +804,16 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
     const int N = pr->N, n = pr->D_pp;
     int threads = ((N + DTFM_WAVE - 1) / DTFM_WAVE) * DTFM_WAVE;
     if (threads > 1024) threads = 1024;
-    if ((size_t)N * N * sizeof(double) > ((size_t)2 << 20) && N % DTFM_XCDS == 0) {
+    if (b.pos != nullptr && rows >= 64 && (reinterpret_cast<uintptr_t>(perm) & 15u) == 0) {
+        // W_dp larger than half an XCD's L2 and stages made of 16-byte pieces: rows of W_dp in LDS, by device
+        const size_t total = rows * (size_t)N;
+        hipLaunchKernelGGL(k_positions, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, perm, N, total, b.pos);
+        DTFM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(k_datap_rows, dim3((unsigned)(N / DTFM_DATAP_DPW * DTFM_DATAP_SPLIT)), dim3(256),
+                           (size_t)DTFM_DATAP_DPW * N * sizeof(double), st, pr->W_dp, perm, b.pos, N, pr->D_dp, rows, b.rowsum);
+        DTFM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(k_datap_reduce, dim3((unsigned)rows), dim3(256), 0, st, b.rowsum, N, n, b.datap, b.ghat);
+    } else if ((size_t)N * N * sizeof(double) > ((size_t)2 << 20) && N % DTFM_XCDS == 0) {
         // W_dp larger than half an XCD's L2: one slice of its rows per XCD
         hipLaunchKernelGGL(k_zero_f64, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, b.datap, rows);
         DTFM_HIP(hipGetLastError());

@@ -76,6 +76,8 @@ int dtfm_hip_fail(hipError_t e, const char *what);
 
 // ---- general-shape evaluation (dtfm_eval.hip) -------------------------------------------------
 struct dtfm_eval_bufs {
+    int32_t *pos;    // rows * N: position of every device in its row, or null (DataP by candidate)
+    double *rowsum;  // rows * N: Eq. 2 row sum of the device at every position, or null
     double *datap;   // rows
     double *ghat;    // rows * D_pp * D_pp
     double *hk_tab;  // hk_grid exchange areas, or null when the table fits LDS
@@ -94,8 +96,9 @@ struct dtfm_trial_ref {
     const double *cur;        // rows: their cost (Eq. 1)
     int trials_per_row;       // consecutive trial rows made from one current row (1, or 4 for BEST4)
 };
-// hk_grid_cap: upper limit on the number of exchange areas (0: DTFM_HK_GLOBAL_GRID)
-dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows, size_t hk_grid_cap = 0);
+// hk_grid_cap: upper limit on the number of exchange areas (0: DTFM_HK_GLOBAL_GRID); lean: without the per-position
+// buffers of DataP by device (the evaluation then takes DataP by candidate)
+dtfm_eval_bufs dtfm_eval_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t rows, size_t hk_grid_cap = 0, bool lean = false);
 // bytes of one exchange area of the blocked Held-Karp kernel (0 when the table fits LDS)
 size_t dtfm_hk_exchange_bytes(const dtfm_problem *pr);
 // enqueues a2..a6 for `rows` candidates; cost may be null (then only datap/ghat are produced)
