@@ -197,6 +197,41 @@ def test_matching_on_bucketed_ranks(D_dp, D_pp, P):
     assert_costs_equal(host(dtfm.eval_population(g, dev(perms[:3]))), o.eval_population(perms[:3]))
 
 
+@pytest.mark.parametrize("D_dp,D_pp", [(48, 16), (64, 16), (44, 13)])
+def test_datap_by_device_and_by_candidate_agree_with_the_oracle(D_dp, D_pp):
+    # W_dp beyond an XCD's L2: launches of 64 rows and more take DataP by device (rows of W_dp in LDS, positions
+    # from the inverse of each row), smaller ones and rows that are not 16-byte aligned take it by candidate slices
+    N = D_dp * D_pp
+    w = custom(N, D_dp, D_pp, seed=N + 9)
+    o, g = both(w)
+    perms = workloads.random_population(150, N, seed=D_pp)
+    ref = np.array([o.datap(perms[p]) for p in range(150)])
+    for P in (150, 64, 63, 5):
+        _, datap = dtfm.coarsened_graph(g, dev(perms[:P]))
+        assert np.array_equal(host(datap), ref[:P]), (D_dp, D_pp, P)
+    # the same rows behind a 4-byte offset: not 16-byte aligned
+    buf = torch.empty(150 * N + 1, dtype=torch.int32, device="cuda")
+    buf[1:] = dev(perms).reshape(-1)
+    _, datap = dtfm.coarsened_graph(g, buf[1:].view(150, N))
+    assert np.array_equal(host(datap), ref)
+
+
+def test_rows_that_are_not_permutations_do_no_harm():
+    # entries inside 0..N-1 but repeated: the cost of such a row means nothing, the call must complete and the
+    # other rows keep their values
+    w = workloads.config("C5")
+    o, g = both(w)
+    perms = workloads.random_population(96, 1024, seed=11)
+    good = host(dtfm.eval_population(g, dev(perms)))
+    bad = perms.copy()
+    bad[7, :] = 3
+    bad[40, 100:200] = bad[40, 0:100]
+    c = host(dtfm.eval_population(g, dev(bad)))
+    keep = np.ones(96, dtype=bool)
+    keep[[7, 40]] = False
+    assert np.array_equal(c[keep], good[keep])
+
+
 def test_ragged_population_sizes_and_empty():
     w = workloads.config("C2")
     o, g = both(w)
