@@ -5,6 +5,13 @@ four-candidate local search per offspring) as the CPU ORACLE computes them.
 
     python tests/golden/make_c5_trace.py [--generations 2] [--threads 8]
 
+With other arguments it writes the same kind of file for another configuration, e.g. the stored
+tests/golden/c4_evolve_seed11_P1024_best4.txt (configuration 4 at its population, the four candidates of a
+round judged by the cost):
+
+    python tests/golden/make_c5_trace.py --config C4 --population 1024 --seed 11 --neighbourhood BEST4 \
+        --generations 3 --out tests/golden/c4_evolve_seed11_P1024_best4.txt
+
 Calls only oracle/ and the seeded input generator (workloads.py); nothing of the GPU library. The
 oracle's evaluations are independent per candidate and run on `--threads` host threads
 (oracle.Problem.evolve_by_generation, which tests/test_oracle_search.py shows equal to the oracle's
@@ -44,12 +51,24 @@ def main():
     ap.add_argument("--generations", type=int, default=2)
     ap.add_argument("--threads", type=int, default=os.cpu_count() or 1)
     ap.add_argument("--out", default=OUT)
+    ap.add_argument("--config", default="C5")
+    ap.add_argument("--population", type=int, default=P)
+    ap.add_argument("--seed", type=int, default=SEED)
+    ap.add_argument("--neighbourhood", default="GAIN4", choices=["GAIN4", "KL", "BEST4"])
     args = ap.parse_args()
-    w = workloads.config("C5")
+    return write_trace(args.config, args.seed, args.population, LS_MOVES, args.neighbourhood, args.generations,
+                       args.threads, args.out)
+
+
+def write_trace(config, SEED, P, LS_MOVES, neighbourhood, generations, threads, out):
+    class args:   # the names used below
+        pass
+    args.generations, args.threads, args.out = generations, threads, out
+    w = workloads.config(config)
     o = oracle.Problem(w.latency, w.bandwidth, w.c_dp, w.c_pp, w.D_dp, w.D_pp)
     lines = ["# written by tests/golden/make_c5_trace.py from the CPU oracle; do not edit",
-             "# configuration 5: N=%d D_dp=%d D_pp=%d, workloads.config('C5'), defaults m_x=N/4, m_m=1" % (w.N, w.D_dp, w.D_pp),
-             "seed %d" % SEED, "population %d" % P, "ls_moves %d" % LS_MOVES, "neighbourhood GAIN4",
+             "# configuration %s: N=%d D_dp=%d D_pp=%d, workloads.config('%s'), defaults m_x=N/4, m_m=1" % (config[1:], w.N, w.D_dp, w.D_pp, config),
+             "seed %d" % SEED, "population %d" % P, "ls_moves %d" % LS_MOVES, "neighbourhood %s" % neighbourhood,
              "generations %d" % args.generations]
     t0 = time.time()
 
@@ -60,7 +79,7 @@ def main():
             g, hexd(cost.min()), hashlib.sha256(pop.tobytes()).hexdigest(), hashlib.sha256(cost.tobytes()).hexdigest()))
         print("generation %d done after %.0f s, best %.6f" % (g, time.time() - t0, cost.min()), flush=True)
 
-    pop, cost, trace = o.evolve_by_generation(SEED, args.generations, P, ls_moves=LS_MOVES, neighbourhood=oracle.GAIN4,
+    pop, cost, trace = o.evolve_by_generation(SEED, args.generations, P, ls_moves=LS_MOVES, neighbourhood=getattr(oracle, neighbourhood),
                                               threads=args.threads, on_generation=report)
     lines.append("best_trace " + " ".join(hexd(x) for x in trace))
     lines.append("final_costs")

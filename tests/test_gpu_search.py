@@ -350,11 +350,11 @@ def test_evolve_with_best4():
     _evolve_parity(custom(48, 4, 12, seed=3), 1, 2, 6, ls_moves=2, neighbourhood=dtfm.BEST4)
 
 
-def _read_c5_golden():
+def _read_golden(name="c5_evolve_seed7_P4096.txt"):
     """tests/golden/c5_evolve_seed7_P4096.txt, written by tests/golden/make_c5_trace.py from the CPU oracle."""
     import os
     import struct
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "c5_evolve_seed7_P4096.txt")
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
     unhex = lambda t: struct.unpack("<d", struct.pack("<Q", int(t, 16)))[0]
     meta, gens, costs, in_costs = {}, {}, [], False
     with open(path) as f:
@@ -380,7 +380,7 @@ def test_config5_trajectory_against_stored_oracle_run():
     # generations against the run of the CPU oracle stored under tests/golden (initial population, every generation's
     # population and costs by their SHA-256, the best-cost trace and the final costs bit for bit)
     import hashlib
-    meta, gens, final_costs = _read_c5_golden()
+    meta, gens, final_costs = _read_golden()
     G, P = int(meta["generations"]), int(meta["population"])
     assert (int(meta["seed"]), P, int(meta["ls_moves"]), meta["neighbourhood"]) == (7, 4096, 8, "GAIN4") and G >= 2
     w = workloads.config("C5")
@@ -391,6 +391,27 @@ def test_config5_trajectory_against_stored_oracle_run():
         pop, cost, trace = host(pop), host(cost), host(trace)
         want = gens[gen - 1]
         assert pop.dtype == np.int32 and cost.dtype == np.float64
+        assert sha(pop) == want["pop"], "population after generation %d" % (gen - 1)
+        assert sha(cost) == want["cost"], "costs after generation %d" % (gen - 1)
+        assert cost.min() == want["best"]
+    assert np.array_equal(trace, meta["trace"]) and np.array_equal(cost, final_costs)
+
+
+def test_config4_best4_trajectory_against_stored_oracle_run():
+    # configuration 4 at its population (1024, Philox seed 11, 8 rounds in which the round's four candidates are
+    # judged by the cost): every generation of the stored CPU-oracle run, populations and costs by SHA-256, the
+    # best-cost trace and the final costs bit for bit
+    import hashlib
+    meta, gens, final_costs = _read_golden("c4_evolve_seed11_P1024_best4.txt")
+    G, P = int(meta["generations"]), int(meta["population"])
+    assert (int(meta["seed"]), P, int(meta["ls_moves"]), meta["neighbourhood"]) == (11, 1024, 8, "BEST4") and G >= 2
+    w = workloads.config("C4")
+    _, g = both(w)
+    sha = lambda a: hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()
+    for gen in (0, 1, G):
+        pop, cost, trace = dtfm.evolve(g, 11, gen, P, ls_moves=8, neighbourhood=dtfm.BEST4)
+        pop, cost, trace = host(pop), host(cost), host(trace)
+        want = gens[gen - 1]
         assert sha(pop) == want["pop"], "population after generation %d" % (gen - 1)
         assert sha(cost) == want["cost"], "costs after generation %d" % (gen - 1)
         assert cost.min() == want["best"]
