@@ -561,34 +561,41 @@ __device__ __forceinline__ void hk_block_layers(double *tab, const uint16_t *lsu
     static_assert(NL % 2 == 0 && 16 - NL <= 6, "slot pairs (NL + 2 q, NL + 2 q + 1), q < 3");
     constexpr int GROUPS = (1 << NL) / 16, RS = DTFM_HK_ROW_STRIDE;
     uint32_t Lnext = 0;   // layer 0 is the empty low part alone (group 0)
+    const bool can_push = v < n;
 #pragma unroll
     for (int k = 0; k <= NL; k++) {
         const int first = dtfm_layer_first(NL, k), cnt = dtfm_binom(NL, k);
-        for (int i = grp; i < cnt; i += GROUPS) {
+        const int turns = (cnt + GROUPS - 1) / GROUPS;   // every group takes part in all turns but, maybe, the last
+        const uint16_t *next = lsub + first + grp + GROUPS;
+#pragma nounroll
+        for (int t = 0; t < turns; t++) {
             const uint32_t L = Lnext;
-            if (i + GROUPS < cnt) Lnext = lsub[first + i + GROUPS];
-            const uint32_t S = (H << NL) | L;
-            const bool in = (S >> v) & 1u;
-            const double2 *row = reinterpret_cast<const double2 *>(tab + L * RS);
-            double y = INFINITY;
+            Lnext = next[t * GROUPS];   // lsub is padded: the read behind the layer's last row stays inside it
+            if (t + 1 < turns || grp + (turns - 1) * GROUPS < cnt) {
+                const uint32_t S = (H << NL) | L;
+                const bool in = (S >> v) & 1u;
+                const double2 *row = reinterpret_cast<const double2 *>(tab + L * RS);
+                double y = INFINITY;
 #pragma unroll
-            for (int h = 0; h < NPAIR; h++) {
-                // HM: bit q set = the pair of slots NL + 2 q, NL + 2 q + 1 holds a stage of H
-                const bool present = 2 * h >= NL ? ((HM >> ((2 * h - NL) / 2)) & 1u) != 0u : true;
-                if (!present) continue;
-                const double2 x = row[h];
-                y = fmin(y, __dadd_rn(x.x, Gc[2 * h]));
-                y = fmin(y, __dadd_rn(x.y, Gc[2 * h + 1]));
-            }
-            if (!in && v < n && S != 0u) {
-                if (v < NL)
-                    tab[(L | (1u << v)) * RS + v] = y;
-                else
-                    X[(((size_t)(H | (1u << (v - NL))) * nh + (v - NL)) << NL) + L] = y;
+                for (int h = 0; h < NPAIR; h++) {
+                    // HM: bit q set = the pair of slots NL + 2 q, NL + 2 q + 1 holds a stage of H
+                    const bool present = 2 * h >= NL ? ((HM >> ((2 * h - NL) / 2)) & 1u) != 0u : true;
+                    if (!present) continue;
+                    const double2 x = row[h];
+                    y = fmin(y, __dadd_rn(x.x, Gc[2 * h]));
+                    y = fmin(y, __dadd_rn(x.y, Gc[2 * h + 1]));
+                }
+                // the empty set (layer 0 of block 0) pushes nothing: a single stage alone is a path of one node
+                if (!in && can_push && (k > 0 || H != 0u)) {
+                    if (v < NL)
+                        tab[(L | (1u << v)) * RS + v] = y;
+                    else
+                        X[(((size_t)(H | (1u << (v - NL))) * nh + (v - NL)) << NL) + L] = y;
+                }
             }
         }
         if (k < NL) {
-            if (grp < dtfm_binom(NL, k + 1)) Lnext = lsub[dtfm_layer_first(NL, k + 1) + grp];
+            Lnext = lsub[dtfm_layer_first(NL, k + 1) + grp];
             DTFM_LDS_BARRIER();
         } else {
             __syncthreads();
@@ -628,6 +635,7 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
         int first = 0;
         for (int j = 0; j < k; j++) first += dtfm_binom10[NL][j];
         lsub[first + rank] = (uint16_t)L;
+        if (L < 2 * (THREADS / 16)) lsub[(1 << NL) + L] = 0;   // the entries read ahead behind the last layer
         if (L < (1 << nh)) {   // the same order for the sets H of the nh high stages
             int hfirst = 0;
             for (int j = 0; j < k; j++) hfirst += dtfm_binom10[nh][j];
@@ -859,7 +867,8 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
     } else {
         size_t grid = b.hk_grid;
         constexpr int NL = DTFM_HK_BLOCK_LOW;
-        size_t lds = ((size_t)(DTFM_HK_ROW_STRIDE << NL) + 256) * sizeof(double) + ((size_t)sizeof(uint16_t) << NL);
+        // rows, Ghat, and the low parts in layer order with two more turns of entries behind them (read ahead, never used)
+        size_t lds = ((size_t)(DTFM_HK_ROW_STRIDE << NL) + 256) * sizeof(double) + sizeof(uint16_t) * (((size_t)1 << NL) + 2 * (((size_t)1 << NL) / 16));
         auto kern = n <= 12 ? k_held_karp_blocked<NL, 6> : n <= 14 ? k_held_karp_blocked<NL, 7> : k_held_karp_blocked<NL, 8>;
         DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds));
