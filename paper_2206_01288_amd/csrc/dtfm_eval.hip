@@ -555,7 +555,7 @@ constexpr int dtfm_layer_first(int NL, int k)
 // in LDS) is fetched one row ahead, across the barrier too. The barrier after the last layer also completes
 // the block's stores to the exchange area.
 template <int NL, int NPAIR, uint32_t HM>
-__device__ __forceinline__ void hk_block_layers(double *tab, const uint16_t *lsub, const double (&Gc)[16],
+__device__ __forceinline__ void hk_block_layers(double *tab, const uint32_t *lsub, const double (&Gc)[16],
                                                 double *X, uint32_t H, int nh, int n, int v, int grp)
 {
     static_assert(NL % 2 == 0 && 16 - NL <= 6, "slot pairs (NL + 2 q, NL + 2 q + 1), q < 3");
@@ -566,7 +566,7 @@ __device__ __forceinline__ void hk_block_layers(double *tab, const uint16_t *lsu
     for (int k = 0; k <= NL; k++) {
         const int first = dtfm_layer_first(NL, k), cnt = dtfm_binom(NL, k);
         const int turns = (cnt + GROUPS - 1) / GROUPS;   // every group takes part in all turns but, maybe, the last
-        const uint16_t *next = lsub + first + grp + GROUPS;
+        const uint32_t *next = lsub + first + grp + GROUPS;
 #pragma nounroll
         for (int t = 0; t < turns; t++) {
             const uint32_t L = Lnext;
@@ -588,7 +588,7 @@ __device__ __forceinline__ void hk_block_layers(double *tab, const uint16_t *lsu
                 // the empty set (layer 0 of block 0) pushes nothing: a single stage alone is a path of one node
                 if (!in && can_push && (k > 0 || H != 0u)) {
                     if (v < NL)
-                        tab[(L | (1u << v)) * RS + v] = y;
+                        tab[L * RS + ((1u << v) * RS + v)] = y;   // v is not in L: L | 1 << v = L + (1 << v)
                     else
                         X[(((size_t)(H | (1u << (v - NL))) * nh + (v - NL)) << NL) + L] = y;
                 }
@@ -617,7 +617,7 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
     extern __shared__ double smem[];
     double *tab = smem;                                           // [ROWS][RS], 16 slots used
     double *G = smem + ROWS * RS;                                 // [16][16], +inf outside n x n
-    uint16_t *lsub = reinterpret_cast<uint16_t *>(G + 256);       // low parts ordered by popcount
+    uint32_t *lsub = reinterpret_cast<uint32_t *>(G + 256);       // low parts ordered by popcount
     __shared__ unsigned char horder[1 << (16 - NL)];              // the sets H ordered by popcount
     constexpr int NHMAX = 16 - NL;
     const int nh = n - NL;
@@ -634,7 +634,7 @@ k_held_karp_blocked(const double *__restrict__ ghat, const double *__restrict__ 
         }
         int first = 0;
         for (int j = 0; j < k; j++) first += dtfm_binom10[NL][j];
-        lsub[first + rank] = (uint16_t)L;
+        lsub[first + rank] = (uint32_t)L;
         if (L < 2 * (THREADS / 16)) lsub[(1 << NL) + L] = 0;   // the entries read ahead behind the last layer
         if (L < (1 << nh)) {   // the same order for the sets H of the nh high stages
             int hfirst = 0;
@@ -868,7 +868,7 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
         size_t grid = b.hk_grid;
         constexpr int NL = DTFM_HK_BLOCK_LOW;
         // rows, Ghat, and the low parts in layer order with two more turns of entries behind them (read ahead, never used)
-        size_t lds = ((size_t)(DTFM_HK_ROW_STRIDE << NL) + 256) * sizeof(double) + sizeof(uint16_t) * (((size_t)1 << NL) + 2 * (((size_t)1 << NL) / 16));
+        size_t lds = ((size_t)(DTFM_HK_ROW_STRIDE << NL) + 256) * sizeof(double) + sizeof(uint32_t) * (((size_t)1 << NL) + 2 * (((size_t)1 << NL) / 16));
         auto kern = n <= 12 ? k_held_karp_blocked<NL, 6> : n <= 14 ? k_held_karp_blocked<NL, 7> : k_held_karp_blocked<NL, 8>;
         DTFM_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds));
