@@ -253,6 +253,21 @@ def test_ties_heavy_matching_blocks():
     assert_costs_equal(host(dtfm.eval_population(g, dev(perms))), o.eval_population(perms))
 
 
+@pytest.mark.parametrize("D_dp,D_pp", [(6, 4), (20, 3), (64, 12)])
+def test_homogeneous_network_on_general_shapes(D_dp, D_pp):
+    # one link class: every matching block holds a single weight (one rank besides the diagonal's), every path the
+    # same sum; the closed form is (D_dp - 1) w_dp + (D_pp - 1) w_pp summed left to right
+    N = D_dp * D_pp
+    lat = np.full((N, N), 1e-3)
+    bw = np.full((N, N), 1e9)
+    w = workloads.Workload("flat", N, D_dp, D_pp, 6e7, 5e6, lat, bw, 0)
+    o, g = both(w)
+    perms = workloads.random_population(70, N, seed=N)
+    c = host(dtfm.eval_population(g, dev(perms)))
+    assert_costs_equal(c, o.eval_population(perms))
+    assert np.all(c == c[0])
+
+
 def test_deterministic_and_stream_ordered():
     w = workloads.config("C2")
     o, g = both(w)
