@@ -346,11 +346,11 @@ extern "C" int dtfm_move_costs(dtfm_problem *pr, const int32_t *perm, int P, dou
     if (P == 0 || pr->N < 2) return DTFM_OK;
     if (perm == nullptr || move_cost == nullptr) return DTFM_ERR_NULL;
     dtfm_arena measure = {nullptr, 0};
-    dtfm_ls_carve(pr, measure, (size_t)P, DTFM_ALL_PAIRS);
+    dtfm_ls_carve(pr, measure, (size_t)P, DTFM_ALL_PAIRS, true);
     int rc = ensure_scratch(pr, measure.off);
     if (rc != DTFM_OK) return rc;
     dtfm_arena ar = {pr->scratch, 0};
-    dtfm_ls_bufs b = dtfm_ls_carve(pr, ar, (size_t)P, DTFM_ALL_PAIRS);
+    dtfm_ls_bufs b = dtfm_ls_carve(pr, ar, (size_t)P, DTFM_ALL_PAIRS, true);
     return dtfm_move_costs_enqueue(pr, b, perm, (size_t)P, move_cost, (hipStream_t)hip_stream);
 }
 
@@ -389,6 +389,11 @@ extern "C" int dtfm_reserve(dtfm_problem *pr, int P, int lambda, int neighbourho
     m = {nullptr, 0};
     dtfm_ls_carve(pr, m, rows, neighbourhood);
     grow(m);
+    if (neighbourhood == DTFM_ALL_PAIRS) {   // dtfm_move_costs materialises every swap of a chunk
+        m = {nullptr, 0};
+        dtfm_ls_carve(pr, m, rows, neighbourhood, true);
+        grow(m);
+    }
     m = {nullptr, 0};
     dtfm_assign_carve(pr, m, rows);
     grow(m);

@@ -835,15 +835,18 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
     }
     DTFM_HIP(hipGetLastError());
     if (pr->npairs > 0) {
-        const int match_pairs = inc_j >= 0 ? 2 * n - 3 : pr->npairs;
+        // trial rows that differ from their current rows inside one stage only (inc_j = inc_jp) keep every edge
+        const int match_pairs = inc_j >= 0 ? (inc_j == inc_jp ? 0 : 2 * n - 3) : pr->npairs;
         const int nb = (pr->D_dp + 15) / 16;
         if (rows > 0x7fffffffu) return DTFM_ERR_ARG;
+        if (match_pairs > 0) {
         auto kern = nb <= 1 ? k_match<1> : nb == 2 ? k_match<2> : nb == 3 ? k_match<3> : k_match<4>;
         // one wavefront per (candidate, stage pair)
         hipLaunchKernelGGL(kern, dim3((unsigned)rows, (unsigned)match_pairs), dim3(DTFM_WAVE),
                            (size_t)16 * nb * DTFM_WAVE * sizeof(uint16_t), st, pr->W_rank, pr->rank_val, pr->rank_shift, perm, N, pr->D_dp, n,
                            b.ghat, inc_j, inc_jp);
         DTFM_HIP(hipGetLastError());
+        }
     }
     if (cost == nullptr) return DTFM_OK;
     const int32_t *list = nullptr, *count = nullptr;

@@ -163,13 +163,16 @@ struct dtfm_ls_bufs {
     int32_t *tmp_perm;  // rows * N: candidates with a move applied
     double *tmp_cost;   // rows
     int32_t *move_ab;   // 2 * P (GAIN4: proposed positions)
-    size_t chunk;       // candidates per ALL_PAIRS chunk
+    size_t chunk;       // candidates per ALL_PAIRS chunk (every swap materialised)
+    size_t group_chunk; // candidates per ALL_PAIRS chunk when the swaps go by stage pair, else 0
+    double *all_cost;   // group_chunk * N (N - 1) / 2: the costs of a chunk's swaps by move index, or null
     size_t rows;        // rows evaluated per eval call
     double *ghat_cur;   // P * D_pp * D_pp: coarsened graphs of the current rows (GAIN4 / KL rounds)
     double *pp_cur;     // P: PipelineP-Cost of the current rows (GAIN4 / KL rounds)
     dtfm_eval_bufs ev;
 };
-dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int neighbourhood);
+// pricing: for dtfm_move_costs (every swap's exact cost, materialised)
+dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int neighbourhood, bool pricing = false);
 int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm, size_t P, int moves,
                     int neighbourhood, double *cost, int64_t *applied, hipStream_t st);
 

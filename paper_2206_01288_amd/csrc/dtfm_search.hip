@@ -53,6 +53,50 @@ __global__ void k_make_swapped(const int32_t *__restrict__ perm, int N, long lon
     }
 }
 
+// ALL_PAIRS by stage pair (general shapes): the swaps between a slot of stage j and a slot of stage jp (j < jp:
+// D_dp^2 of them; j = jp: the D_dp (D_dp - 1) / 2 swaps inside the stage), in the order of their move index.
+// Trial g of group (j, jp) exchanges positions a < b:
+__device__ __forceinline__ void group_move(int D_dp, int j, int jp, long long g, int &a, int &b)
+{
+    if (j == jp) {
+        int i, k;
+        pair_decode(D_dp, g, i, k);
+        a = j * D_dp + i;
+        b = j * D_dp + k;
+    } else {
+        a = j * D_dp + (int)(g / D_dp);
+        b = jp * D_dp + (int)(g % D_dp);
+    }
+}
+
+// row (p - p0) * G + g = candidate p with trial g of the group applied
+__global__ void k_make_swapped_group(const int32_t *__restrict__ perm, int N, int D_dp, int j, int jp, long long G,
+                                     size_t p0, int32_t *__restrict__ tmp_perm)
+{
+    const size_t rowi = blockIdx.x;
+    const size_t pc = rowi / (size_t)G;
+    int a, b;
+    group_move(D_dp, j, jp, (long long)(rowi - pc * (size_t)G), a, b);
+    const int32_t *src = perm + (p0 + pc) * N;
+    int32_t *dst = tmp_perm + rowi * N;
+    for (int q = threadIdx.x; q < N; q += blockDim.x) {
+        const int s = q == a ? b : (q == b ? a : q);
+        dst[q] = src[s];
+    }
+}
+
+// the group's costs to their places among all N (N - 1) / 2 moves of their candidate
+__global__ void k_scatter_group(const double *__restrict__ group_cost, size_t T, int N, int D_dp, int j, int jp,
+                                long long G, long long M, double *__restrict__ all_cost)
+{
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const size_t pc = t / (size_t)G;
+    int a, b;
+    group_move(D_dp, j, jp, (long long)(t - pc * (size_t)G), a, b);
+    all_cost[pc * (size_t)M + (size_t)pair_encode(N, a, b)] = group_cost[t];
+}
+
 // ALL_PAIRS: per candidate, the cheapest move (lowest index on ties); applied only if strictly
 // cheaper than the current cost.
 __global__ void k_pick_apply(int32_t *__restrict__ perm, int N, long long M, size_t p0,
@@ -400,17 +444,32 @@ __global__ void k_fill_i64(int64_t *__restrict__ dst, int64_t v, size_t n)
     if (i < n) dst[i] = v;
 }
 
-dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int neighbourhood)
+// ALL_PAIRS of the local search on general shapes goes by stage pair (see dtfm_ls_enqueue) when there are at least
+// three stages; pricing (dtfm_move_costs) and the other cases materialise every swap of a chunk of candidates
+static bool all_pairs_by_group(const dtfm_problem *pr) { return !pr->fast64 && pr->D_pp >= 3; }
+
+dtfm_ls_bufs dtfm_ls_carve(const dtfm_problem *pr, dtfm_arena &ar, size_t P, int neighbourhood, bool pricing)
 {
     dtfm_ls_bufs b;
     size_t N = pr->N, M = N * (N - 1) / 2;
     b.cur = ar.take<double>(P);
+    b.all_cost = nullptr;
+    b.group_chunk = 0;
     if (neighbourhood == DTFM_ALL_PAIRS && M > 0) {
         size_t chunk = DTFM_LS_ROWS_MAX / M;
         if (chunk < 1) chunk = 1;
         if (chunk > P) chunk = P;
         b.chunk = chunk;
         b.rows = chunk * M > P ? chunk * M : P;
+        if (!pricing && all_pairs_by_group(pr)) {
+            const size_t G = (size_t)pr->D_dp * pr->D_dp;   // the largest group: swaps between two stages
+            size_t gc = DTFM_LS_ROWS_MAX / G;
+            if (gc < 1) gc = 1;
+            if (gc > P) gc = P;
+            b.group_chunk = gc;
+            b.rows = gc * G > P ? gc * G : P;
+            b.all_cost = ar.take<double>(gc * M);
+        }
     } else {
         b.chunk = P;
         b.rows = neighbourhood == DTFM_BEST4 ? 4 * P : P;   // BEST4 prices four trials per candidate
@@ -464,6 +523,49 @@ int dtfm_ls_enqueue(const dtfm_problem *pr, const dtfm_ls_bufs &b, int32_t *perm
                     DTFM_HIP(hipGetLastError());
                 }
                 break;
+            }
+            if (b.all_cost != nullptr) {
+                // By stage pair: the swaps between two stages leave every other stage's DataP rows and every
+                // coarsened edge outside those two stages as they are, so a group's trial rows start from their
+                // current row's graph, match again only the 2 D_pp - 3 edges of the two stages (none for swaps
+                // inside a stage) and skip Held-Karp where the graph settles the trial (k_trial_shortcut: a trial
+                // it rejects gets +inf, which is never picked: it is not below the current cost).
+                const int n = pr->D_pp, nn = n * n, D = pr->D_dp;
+                if (r > 0) {   // graphs and PipelineP of the rows as they are now (round 0: just evaluated)
+                    rc = dtfm_eval_enqueue(pr, b.ev, perm, P, b.cur, st);
+                    if (rc != DTFM_OK) return rc;
+                }
+                hipLaunchKernelGGL(k_copy_f64, dim3((unsigned)((P * nn + 255) / 256)), dim3(256), 0, st, b.ev.ghat, b.ghat_cur,
+                                   P * nn);
+                DTFM_HIP(hipGetLastError());
+                hipLaunchKernelGGL(k_copy_f64, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, b.ev.pp, b.pp_cur, P);
+                DTFM_HIP(hipGetLastError());
+                for (size_t p0 = 0; p0 < P; p0 += b.group_chunk) {
+                    const size_t cp = P - p0 < b.group_chunk ? P - p0 : b.group_chunk;
+                    for (int j = 0; j < n; j++) {
+                        for (int jp = j; jp < n; jp++) {
+                            const long long G = j == jp ? (long long)D * (D - 1) / 2 : (long long)D * D;
+                            if (G == 0) continue;
+                            const size_t T = cp * (size_t)G;
+                            hipLaunchKernelGGL(k_make_swapped_group, dim3((unsigned)T), dim3(DTFM_WAVE), 0, st, perm, N, D, j, jp,
+                                               G, p0, b.tmp_perm);
+                            DTFM_HIP(hipGetLastError());
+                            hipLaunchKernelGGL(k_replicate_f64, dim3((unsigned)((T * nn + 255) / 256)), dim3(256), 0, st,
+                                               b.ghat_cur + p0 * nn, b.ev.ghat, nn, (int)G, T * nn);
+                            DTFM_HIP(hipGetLastError());
+                            const dtfm_trial_ref ref = {b.ghat_cur + p0 * nn, b.pp_cur + p0, b.cur + p0, (int)G};
+                            rc = dtfm_eval_inc_enqueue(pr, b.ev, b.tmp_perm, T, b.tmp_cost, j, jp, st, &ref);
+                            if (rc != DTFM_OK) return rc;
+                            hipLaunchKernelGGL(k_scatter_group, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, b.tmp_cost, T,
+                                               N, D, j, jp, G, M, b.all_cost);
+                            DTFM_HIP(hipGetLastError());
+                        }
+                    }
+                    hipLaunchKernelGGL(k_pick_apply, dim3((unsigned)cp), dim3(256), 0, st, perm, N, M, p0, b.all_cost, b.cur,
+                                       applied, moves, r);
+                    DTFM_HIP(hipGetLastError());
+                }
+                continue;
             }
             for (size_t p0 = 0; p0 < P; p0 += b.chunk) {
                 size_t cp = P - p0 < b.chunk ? P - p0 : b.chunk;

@@ -116,8 +116,10 @@ def test_all_pairs_ties_take_lowest_index():
     _ls_parity(w, workloads.random_population(40, 12, seed=8), 4, dtfm.ALL_PAIRS)
 
 
-@pytest.mark.parametrize("D_dp,D_pp,P,moves", [(2, 2, 9, 3), (3, 4, 33, 5), (1, 6, 5, 2), (6, 1, 5, 2), (1, 1, 3, 2)])
+@pytest.mark.parametrize("D_dp,D_pp,P,moves", [(2, 2, 9, 3), (3, 4, 33, 5), (1, 6, 5, 2), (6, 1, 5, 2), (1, 1, 3, 2),
+                                                (4, 5, 19, 4), (1, 3, 7, 3), (7, 3, 6, 3), (17, 3, 3, 2), (5, 11, 4, 2)])
 def test_all_pairs_odd_shapes(D_dp, D_pp, P, moves):
+    # three stages and more: the swaps go by stage pair, from the current rows' coarsened graphs
     N = D_dp * D_pp
     _ls_parity(custom(N, D_dp, D_pp, seed=N), workloads.random_population(P, N, seed=4), moves, dtfm.ALL_PAIRS)
 
