@@ -164,13 +164,18 @@ extern "C" int dtfm_create_problem(const double *latency, const double *bandwidt
         vals = w;
         std::sort(vals.begin(), vals.end());
         vals.erase(std::unique(vals.begin(), vals.end()), vals.end());
-        // the matching kernel's first solve works on 16-bit codes 2 + (rank >> shift) <= 0xfffe; the table holds
-        // rank + (2 << shift), whose shift is that code
+        // the matching kernel's first solve works on the table of 16-bit codes 2 + (rank >> shift) <= 0xfffe; the
+        // table of ranks serves the entries inside the optimum's bucket when shift > 0
         pr->rank_shift = 0;
         while (((vals.size() - 1) >> pr->rank_shift) + 2 > 0xfffe) pr->rank_shift++;
         std::vector<uint32_t> rk(w.size());
-        for (size_t i = 0; i < w.size(); i++)
-            rk[i] = (uint32_t)(std::lower_bound(vals.begin(), vals.end(), w[i]) - vals.begin()) + (2u << pr->rank_shift);
+        std::vector<uint16_t> code(w.size());
+        for (size_t i = 0; i < w.size(); i++) {
+            rk[i] = (uint32_t)(std::lower_bound(vals.begin(), vals.end(), w[i]) - vals.begin());
+            code[i] = (uint16_t)(2u + (rk[i] >> pr->rank_shift));
+        }
+        CREATE_HIP(hipMalloc((void **)&pr->W_code, code.size() * sizeof(uint16_t)));
+        CREATE_HIP(hipMemcpy(pr->W_code, code.data(), code.size() * sizeof(uint16_t), hipMemcpyHostToDevice));
         CREATE_HIP(hipMalloc((void **)&pr->W_rank, rk.size() * sizeof(uint32_t)));
         CREATE_HIP(hipMalloc((void **)&pr->rank_val, vals.size() * sizeof(double)));
         CREATE_HIP(hipMemcpy(pr->W_rank, rk.data(), rk.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
@@ -189,6 +194,7 @@ extern "C" void dtfm_destroy_problem(dtfm_problem *pr)
     if (pr->W_pp) (void)hipFree(pr->W_pp);
     if (pr->hk_subsets) (void)hipFree(pr->hk_subsets);
     if (pr->W_rank) (void)hipFree(pr->W_rank);
+    if (pr->W_code) (void)hipFree(pr->W_code);
     if (pr->rank_val) (void)hipFree(pr->rank_val);
     if (pr->scratch) (void)hipFree(pr->scratch);
     dtfm_fast64_release(pr);

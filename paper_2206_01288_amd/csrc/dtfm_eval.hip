@@ -268,7 +268,7 @@ __device__ __forceinline__ uint64_t dtfm_clear_bit(uint64_t m, int bit)
 
 template <int NB>  // number of 16-row blocks: D_dp <= 16 * NB
 __global__ void __launch_bounds__(DTFM_WAVE) __attribute__((amdgpu_waves_per_eu(5)))
-k_match(const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val, int shift0,
+k_match(const uint16_t *__restrict__ Wcode, const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val, int shift0,
         const int32_t *__restrict__ perm, int N, int D_dp, int D_pp,
         double *__restrict__ ghat, int inc_j, int inc_jp)
 {
@@ -306,45 +306,33 @@ k_match(const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val,
     }
     const int32_t *row = perm + p * N;
     const int32_t *Ca = row + j1 * D_dp;   // wavefront-uniform: read through the scalar cache
-    // byte offsets into Wrank (N * N * 4 <= 4 MiB): a uniform row term plus the lane's column
-    const uint32_t colbyte = active ? (uint32_t)row[j2 * D_dp + lane] * 4u : 0u, N4 = (uint32_t)N * 4u;
+    const uint32_t coldev = active ? (uint32_t)row[j2 * D_dp + lane] : 0u;
 
-    // Wrank holds rank + bias with bias = 2 << shift0, so that the first solve's code is one shift; entries outside
-    // the block take the pad, whose code is 0xffff and which is above every biased rank
-    const uint32_t pad = 0xffffu << shift0, bias = 2u << shift0;
+    // The block as codes of the first solve, Wcode = 2 + (rank >> shift0), 2 bytes an entry: a wavefront's gather of
+    // one row of the block falls into a 2 N-byte row of the table, a quarter of the cache lines the 32-bit ranks
+    // would touch, and it is the number of lines a gather touches that its time goes by. Entries outside the block
+    // take the pad 0xffff, above every code.
     uint32_t E[R];
-    uint32_t colmin = pad;
+    uint32_t colmin = 0xffffu;
 #pragma unroll
     for (int r = 0; r < R; r++) {
         const bool real = r < RS || r < D_dp;
-        const uint32_t v = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(Wrank) +
-                                                               ((uint32_t)Ca[real ? r : 0] * N4 + colbyte));
-        E[r] = (active && real) ? v : pad;
+        const uint32_t v = Wcode[(uint32_t)Ca[real ? r : 0] * (uint32_t)N + coldev];
+        E[r] = (active && real) ? v : 0xffffu;
         colmin = min(colmin, E[r]);
     }
     // the largest column minimum = ~ the smallest of the complements (idle lanes: complement of 0)
-    const uint32_t maxcolmin = ~dtfm_wave_min_u32(active ? ~colmin : 0xffffffffu);
+    uint32_t theta = ~dtfm_wave_min_u32(active ? ~colmin : 0xffffffffu);   // the threshold, as a code
 
     const uint64_t allcols = D_dp >= 64 ? ~0ull : ((1ull << D_dp) - 1ull);
-    uint32_t base = 0u;   // biased rank below which every entry has code 1 (second solve)
-    int shift = shift0;
-    uint32_t result = 0xffffffffu;   // biased rank of the optimum; stays so if a search fails (cannot happen for a finite block)
+    uint32_t base = 0u;              // second solve: first rank of the bucket
+    uint32_t result = 0xffffffffu;   // rank of the optimum; stays so if a search fails (cannot happen for a finite block)
     for (int solve = 0; solve < 2; solve++) {
-        // codes of this solve into LDS
         __syncthreads();   // one wavefront: orders its own LDS accesses
-        if (solve == 0) {
 #pragma unroll
-            for (int r = 0; r < R; r++) s_E[r * DTFM_WAVE + lane] = (uint16_t)(E[r] >> shift);
-        } else {
-#pragma unroll
-            for (int r = 0; r < R; r++)
-                s_E[r * DTFM_WAVE + lane] = (uint16_t)(E[r] < base ? 1u : min(E[r] - base + 2u, 0xffffu));
-        }
+        for (int r = 0; r < R; r++) s_E[r * DTFM_WAVE + lane] = (uint16_t)E[r];
         __syncthreads();
-        // theta as a code; a key (code << 7 | via) is within theta iff key <= thr, a biased rank iff it is <= thr_rank
-        uint32_t theta = solve == 0 ? maxcolmin >> shift : (maxcolmin < base ? 1u : maxcolmin - base + 2u);
-        uint32_t thr = (theta << 7) | 127u;
-        uint32_t thr_rank = solve == 0 ? ((theta + 1u) << shift) - 1u : base + theta - 2u;
+        uint32_t thr = (theta << 7) | 127u;   // a key (code << 7 | via) is within theta iff key <= thr
 
         // step 2
         uint64_t freecols = allcols, pending = 0ull;
@@ -352,13 +340,11 @@ k_match(const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val,
 #pragma unroll
         for (int r = 0; r < R; r++) {
             if (r < RS || r < D_dp) {
-                uint64_t m = __ballot(E[r] <= thr_rank);
+                uint64_t m = __ballot(E[r] <= theta);
                 if (m == 0ull) {
-                    const uint32_t rowmin = dtfm_wave_min_u32(E[r]);   // > thr_rank
-                    theta = solve == 0 ? rowmin >> shift : rowmin - base + 2u;
+                    theta = dtfm_wave_min_u32(E[r]);
                     thr = (theta << 7) | 127u;
-                    thr_rank = solve == 0 ? ((theta + 1u) << shift) - 1u : base + theta - 2u;
-                    m = __ballot(E[r] <= thr_rank);
+                    m = __ballot(E[r] <= theta);
                 }
                 m &= freecols;
                 if (m != 0ull) {
@@ -432,30 +418,46 @@ k_match(const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val,
             result = base + theta - 2u;
             break;
         }
-        const uint32_t first = theta << shift;   // first biased rank of the optimum's bucket
-        if (shift == 0) {
-            result = first;
+        if (shift0 == 0) {
+            result = theta - 2u;
             break;
         }
-        // ranks of the block inside the bucket: the smallest and the largest
-        const uint32_t last = first + (1u << shift) - 1u;
-        uint32_t lo = 0xffffffffu, hi = 0xffffffffu;
+        // The optimum lies in the bucket of 2^shift0 ranks with code theta. The block's entries with that code, as
+        // ranks (few: they are looked up one row at a time, and only by the lanes that hold one): if they are one
+        // rank, that is the optimum; else they are told apart by a second solve on 1 (below the bucket),
+        // 2 + rank - first rank of the bucket (inside), 0xffff (above it: never needed).
+        base = (theta - 2u) << shift0;
+        uint32_t lo = 0xffffffffu, hi = 0u;
 #pragma unroll
         for (int r = 0; r < R; r++) {
-            lo = min(lo, E[r] - first);   // below the bucket: wraps to the top
-            hi = min(hi, last - E[r]);    // above the bucket: wraps to the top
+            const bool inside = E[r] == theta;
+            if (__ballot(inside) != 0ull) {   // wavefront-uniform
+                uint32_t code2 = E[r] < theta ? 1u : 0xffffu;
+                if (inside) {
+                    const uint32_t rk = Wrank[(uint32_t)Ca[r] * (uint32_t)N + coldev];
+                    lo = min(lo, rk);
+                    hi = max(hi, rk);
+                    code2 = 2u + (rk - base);
+                }
+                E[r] = code2;
+            } else {
+                E[r] = E[r] < theta ? 1u : 0xffffu;
+            }
         }
         lo = dtfm_wave_min_u32(lo);
-        hi = dtfm_wave_min_u32(hi);
-        if (first + lo == last - hi) {
-            result = first + lo;
+        hi = ~dtfm_wave_min_u32(~hi);
+        if (lo == hi) {
+            result = lo;
             break;
         }
-        base = first;
-        shift = 0;
+        // theta of the second solve starts at the largest column minimum again
+        uint32_t cm = 0xffffu;
+#pragma unroll
+        for (int r = 0; r < R; r++) cm = min(cm, E[r]);
+        theta = ~dtfm_wave_min_u32(active ? ~cm : 0xffffffffu);
     }
     if (lane == 0) {
-        const double v = result == 0xffffffffu ? INFINITY : rank_val[result - bias];
+        const double v = result == 0xffffffffu ? INFINITY : rank_val[result];
         double *G = ghat + p * D_pp * D_pp;
         G[j1 * D_pp + j2] = v;
         G[j2 * D_pp + j1] = v;
@@ -843,7 +845,7 @@ int dtfm_eval_inc_enqueue(const dtfm_problem *pr, const dtfm_eval_bufs &b, const
         auto kern = nb <= 1 ? k_match<1> : nb == 2 ? k_match<2> : nb == 3 ? k_match<3> : k_match<4>;
         // one wavefront per (candidate, stage pair)
         hipLaunchKernelGGL(kern, dim3((unsigned)rows, (unsigned)match_pairs), dim3(DTFM_WAVE),
-                           (size_t)16 * nb * DTFM_WAVE * sizeof(uint16_t), st, pr->W_rank, pr->rank_val, pr->rank_shift, perm, N, pr->D_dp, n,
+                           (size_t)16 * nb * DTFM_WAVE * sizeof(uint16_t), st, pr->W_code, pr->W_rank, pr->rank_val, pr->rank_shift, perm, N, pr->D_dp, n,
                            b.ghat, inc_j, inc_jp);
         DTFM_HIP(hipGetLastError());
         }

@@ -39,8 +39,9 @@ struct dtfm_problem {
     double *W_dp;           // device, N*N
     double *W_pp;           // device, N*N
     uint32_t *hk_subsets;   // device, 2^D_pp - 1 subsets ordered by (popcount, value)
-    uint32_t *W_rank;       // device, N*N: (2 << rank_shift) + dense rank of W_pp[d][d'] among all entries (general shapes)
-    int rank_shift;         // 2 + (rank >> rank_shift) fits the 16-bit codes of the matching kernel's first solve
+    uint32_t *W_rank;       // device, N*N: dense rank of W_pp[d][d'] among all entries (general shapes)
+    uint16_t *W_code;       // device, N*N: 2 + (rank >> rank_shift), the codes of the matching kernel's first solve
+    int rank_shift;         // smallest shift with which the codes stay below 0xffff
     double *rank_val;       // device: rank -> weight
     dtfm_layer_off hk_off;
     char *scratch;          // device arena, grown on demand
