@@ -266,72 +266,32 @@ __device__ __forceinline__ uint64_t dtfm_clear_bit(uint64_t m, int bit)
 
 #define DTFM_MATCH_ROOT 127u   // `via` field of a dist that comes from the inserted row itself
 
-template <int NB>  // number of 16-row blocks: D_dp <= 16 * NB
-__global__ void __launch_bounds__(DTFM_WAVE) __attribute__((amdgpu_waves_per_eu(5)))
-k_match(const uint16_t *__restrict__ Wcode, const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val, int shift0,
-        const int32_t *__restrict__ perm, int N, int D_dp, int D_pp,
-        double *__restrict__ ghat, int inc_j, int inc_jp)
+// Steps 2 and 3 and the second solve for one block, by one wavefront. E: the lane's column as codes (pad 0xffff for the
+// rows and lanes outside the block); tile: the block's LDS copy, entry (row r, this lane) at tile[r * RSTR] (the caller
+// passes its lane's base); TILE_READY: the tile already holds the codes of the first solve. rank_of(r): the rank of
+// the lane's entry in row r (looked up only inside the optimum's bucket). Returns the optimum's rank, or 0xffffffff
+// if a search fails (cannot happen for a finite block).
+template <int NB, int RSTR, bool TILE_READY, typename RankOf>
+__device__ __forceinline__ uint32_t match_block(uint16_t *tile, uint32_t (&E)[16 * NB], int lane, bool active, int D_dp,
+                                                int shift0, RankOf rank_of)
 {
     constexpr int R = 16 * NB, RS = R - 16;   // rows below RS exist for every D_dp this instance is launched for
-    extern __shared__ uint16_t s_E[];   // R x 64 codes
-    const int lane = threadIdx.x;
-    const bool active = lane < D_dp;
-    const size_t p = blockIdx.x;   // candidate
-    const int t = (int)blockIdx.y; // stage pair
-    int j1, j2;
-    if (inc_j < 0) {
-        // t-th stage pair (j1 < j2) in lexicographic order
-        int rem = t;
-        j1 = 0;
-        while (rem >= D_pp - 1 - j1) {
-            rem -= D_pp - 1 - j1;
-            j1++;
-        }
-        j2 = j1 + 1 + rem;
-    } else {
-        // only the 2 D_pp - 3 pairs that contain stage inc_j or inc_jp (inc_j < inc_jp): (inc_j, k) for
-        // the D_pp - 1 stages k != inc_j, then (inc_jp, k) for the D_pp - 2 others
-        int a, k;
-        if (t < D_pp - 1) {
-            a = inc_j;
-            k = t + (t >= inc_j ? 1 : 0);
-        } else {
-            a = inc_jp;
-            k = t - (D_pp - 1);
-            k += k >= inc_j ? 1 : 0;
-            k += k >= inc_jp ? 1 : 0;
-        }
-        j1 = a < k ? a : k;
-        j2 = a < k ? k : a;
-    }
-    const int32_t *row = perm + p * N;
-    const int32_t *Ca = row + j1 * D_dp;   // wavefront-uniform: read through the scalar cache
-    const uint32_t coldev = active ? (uint32_t)row[j2 * D_dp + lane] : 0u;
-
-    // The block as codes of the first solve, Wcode = 2 + (rank >> shift0), 2 bytes an entry: a wavefront's gather of
-    // one row of the block falls into a 2 N-byte row of the table, a quarter of the cache lines the 32-bit ranks
-    // would touch, and it is the number of lines a gather touches that its time goes by. Entries outside the block
-    // take the pad 0xffff, above every code.
-    uint32_t E[R];
     uint32_t colmin = 0xffffu;
 #pragma unroll
-    for (int r = 0; r < R; r++) {
-        const bool real = r < RS || r < D_dp;
-        const uint32_t v = Wcode[(uint32_t)Ca[real ? r : 0] * (uint32_t)N + coldev];
-        E[r] = (active && real) ? v : 0xffffu;
-        colmin = min(colmin, E[r]);
-    }
+    for (int r = 0; r < R; r++) colmin = min(colmin, E[r]);
     // the largest column minimum = ~ the smallest of the complements (idle lanes: complement of 0)
     uint32_t theta = ~dtfm_wave_min_u32(active ? ~colmin : 0xffffffffu);   // the threshold, as a code
 
     const uint64_t allcols = D_dp >= 64 ? ~0ull : ((1ull << D_dp) - 1ull);
     uint32_t base = 0u;              // second solve: first rank of the bucket
-    uint32_t result = 0xffffffffu;   // rank of the optimum; stays so if a search fails (cannot happen for a finite block)
+    uint32_t result = 0xffffffffu;
     for (int solve = 0; solve < 2; solve++) {
-        __syncthreads();   // one wavefront: orders its own LDS accesses
+        if (!TILE_READY || solve > 0) {
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int r = 0; r < R; r++) s_E[r * DTFM_WAVE + lane] = (uint16_t)E[r];
-        __syncthreads();
+            for (int r = 0; r < R; r++) tile[r * RSTR] = (uint16_t)E[r];
+            __builtin_amdgcn_wave_barrier();   // one wavefront: its LDS accesses are executed in order
+        }
         uint32_t thr = (theta << 7) | 127u;   // a key (code << 7 | via) is within theta iff key <= thr
 
         // step 2
@@ -362,7 +322,7 @@ k_match(const uint16_t *__restrict__ Wcode, const uint32_t *__restrict__ Wrank, 
         while (pending != 0ull) {
             const int r0 = dtfm_first_bit(pending);
             pending = dtfm_clear_bit(pending, r0);
-            uint32_t dist = ((uint32_t)s_E[r0 * DTFM_WAVE + lane] << 7) | DTFM_MATCH_ROOT;
+            uint32_t dist = ((uint32_t)tile[r0 * RSTR] << 7) | DTFM_MATCH_ROOT;
             uint32_t parked = 0u;
             int cfin = -1;
             uint64_t reach = __ballot(dist - 1u < thr);   // unvisited (dist != 0) and within theta
@@ -390,8 +350,8 @@ k_match(const uint16_t *__restrict__ Wcode, const uint32_t *__restrict__ Wrank, 
                     const int c1 = max(dtfm_first_bit(reach), c0);   // none left: c0 once more
                     reach = dtfm_clear_bit(reach, c1);
                     const int m0 = __builtin_amdgcn_readlane(match_row, c0), m1 = __builtin_amdgcn_readlane(match_row, c1);
-                    const uint32_t w0 = ((uint32_t)s_E[m0 * DTFM_WAVE + lane] << 7) | (uint32_t)c0;
-                    const uint32_t w1 = ((uint32_t)s_E[m1 * DTFM_WAVE + lane] << 7) | (uint32_t)c1;
+                    const uint32_t w0 = ((uint32_t)tile[m0 * RSTR] << 7) | (uint32_t)c0;
+                    const uint32_t w1 = ((uint32_t)tile[m1 * RSTR] << 7) | (uint32_t)c1;
                     dist = min(dist, min(w0, w1));
                 } while (reach != 0ull);
                 reach = __ballot(dist - 1u < thr);
@@ -434,7 +394,7 @@ k_match(const uint16_t *__restrict__ Wcode, const uint32_t *__restrict__ Wrank, 
             if (__ballot(inside) != 0ull) {   // wavefront-uniform
                 uint32_t code2 = E[r] < theta ? 1u : 0xffffu;
                 if (inside) {
-                    const uint32_t rk = Wrank[(uint32_t)Ca[r] * (uint32_t)N + coldev];
+                    const uint32_t rk = rank_of(r);
                     lo = min(lo, rk);
                     hi = max(hi, rk);
                     code2 = 2u + (rk - base);
@@ -456,6 +416,62 @@ k_match(const uint16_t *__restrict__ Wcode, const uint32_t *__restrict__ Wrank, 
         for (int r = 0; r < R; r++) cm = min(cm, E[r]);
         theta = ~dtfm_wave_min_u32(active ? ~cm : 0xffffffffu);
     }
+    return result;
+}
+
+// One wavefront (= one workgroup) per (candidate, stage pair): the lane gathers its column of the block from the
+// table of codes, 2 bytes an entry (pad 0xffff outside the block), and keeps the block's LDS copy as s_E[r * 64 + c].
+template <int NB>  // number of 16-row blocks: D_dp <= 16 * NB
+__global__ void __launch_bounds__(DTFM_WAVE) __attribute__((amdgpu_waves_per_eu(5)))
+k_match(const uint16_t *__restrict__ Wcode, const uint32_t *__restrict__ Wrank, const double *__restrict__ rank_val, int shift0,
+        const int32_t *__restrict__ perm, int N, int D_dp, int D_pp,
+        double *__restrict__ ghat, int inc_j, int inc_jp)
+{
+    constexpr int R = 16 * NB, RS = R - 16;
+    extern __shared__ uint16_t s_E[];   // R x 64 codes
+    const int lane = threadIdx.x;
+    const bool active = lane < D_dp;
+    const size_t p = blockIdx.x;   // candidate
+    const int t = (int)blockIdx.y; // stage pair
+    int j1, j2;
+    if (inc_j < 0) {
+        // t-th stage pair (j1 < j2) in lexicographic order
+        int rem = t;
+        j1 = 0;
+        while (rem >= D_pp - 1 - j1) {
+            rem -= D_pp - 1 - j1;
+            j1++;
+        }
+        j2 = j1 + 1 + rem;
+    } else {
+        // only the 2 D_pp - 3 pairs that contain stage inc_j or inc_jp (inc_j < inc_jp): (inc_j, k) for
+        // the D_pp - 1 stages k != inc_j, then (inc_jp, k) for the D_pp - 2 others
+        int a, k;
+        if (t < D_pp - 1) {
+            a = inc_j;
+            k = t + (t >= inc_j ? 1 : 0);
+        } else {
+            a = inc_jp;
+            k = t - (D_pp - 1);
+            k += k >= inc_j ? 1 : 0;
+            k += k >= inc_jp ? 1 : 0;
+        }
+        j1 = a < k ? a : k;
+        j2 = a < k ? k : a;
+    }
+    const int32_t *row = perm + p * N;
+    const int32_t *Ca = row + j1 * D_dp;   // wavefront-uniform: read through the scalar cache
+    const uint32_t coldev = active ? (uint32_t)row[j2 * D_dp + lane] : 0u;
+    uint32_t E[R];
+#pragma unroll
+    for (int r = 0; r < R; r++) {
+        const bool real = r < RS || r < D_dp;
+        const uint32_t v = Wcode[(uint32_t)Ca[real ? r : 0] * (uint32_t)N + coldev];
+        E[r] = (active && real) ? v : 0xffffu;
+    }
+    const uint32_t result = match_block<NB, DTFM_WAVE, false>(s_E + lane, E, lane, active, D_dp, shift0, [&](int r) {
+        return Wrank[(uint32_t)Ca[r] * (uint32_t)N + coldev];
+    });
     if (lane == 0) {
         const double v = result == 0xffffffffu ? INFINITY : rank_val[result];
         double *G = ghat + p * D_pp * D_pp;
