@@ -267,11 +267,10 @@ __device__ __forceinline__ uint64_t dtfm_clear_bit(uint64_t m, int bit)
 #define DTFM_MATCH_ROOT 127u   // `via` field of a dist that comes from the inserted row itself
 
 // Steps 2 and 3 and the second solve for one block, by one wavefront. E: the lane's column as codes (pad 0xffff for the
-// rows and lanes outside the block); tile: the block's LDS copy, entry (row r, this lane) at tile[r * RSTR] (the caller
-// passes its lane's base); TILE_READY: the tile already holds the codes of the first solve. rank_of(r): the rank of
-// the lane's entry in row r (looked up only inside the optimum's bucket). Returns the optimum's rank, or 0xffffffff
-// if a search fails (cannot happen for a finite block).
-template <int NB, int RSTR, bool TILE_READY, typename RankOf>
+// rows and lanes outside the block); tile: room for the block's LDS copy, entry (row r, this lane) at tile[r * 64] (the
+// caller passes its lane's base). rank_of(r): the rank of the lane's entry in row r (looked up only inside the
+// optimum's bucket). Returns the optimum's rank, or 0xffffffff if a search fails (cannot happen for a finite block).
+template <int NB, typename RankOf>
 __device__ __forceinline__ uint32_t match_block(uint16_t *tile, uint32_t (&E)[16 * NB], int lane, bool active, int D_dp,
                                                 int shift0, RankOf rank_of)
 {
@@ -286,10 +285,10 @@ __device__ __forceinline__ uint32_t match_block(uint16_t *tile, uint32_t (&E)[16
     uint32_t base = 0u;              // second solve: first rank of the bucket
     uint32_t result = 0xffffffffu;
     for (int solve = 0; solve < 2; solve++) {
-        if (!TILE_READY || solve > 0) {
+        {
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int r = 0; r < R; r++) tile[r * RSTR] = (uint16_t)E[r];
+            for (int r = 0; r < R; r++) tile[r * DTFM_WAVE] = (uint16_t)E[r];
             __builtin_amdgcn_wave_barrier();   // one wavefront: its LDS accesses are executed in order
         }
         uint32_t thr = (theta << 7) | 127u;   // a key (code << 7 | via) is within theta iff key <= thr
@@ -322,7 +321,7 @@ __device__ __forceinline__ uint32_t match_block(uint16_t *tile, uint32_t (&E)[16
         while (pending != 0ull) {
             const int r0 = dtfm_first_bit(pending);
             pending = dtfm_clear_bit(pending, r0);
-            uint32_t dist = ((uint32_t)tile[r0 * RSTR] << 7) | DTFM_MATCH_ROOT;
+            uint32_t dist = ((uint32_t)tile[r0 * DTFM_WAVE] << 7) | DTFM_MATCH_ROOT;
             uint32_t parked = 0u;
             int cfin = -1;
             uint64_t reach = __ballot(dist - 1u < thr);   // unvisited (dist != 0) and within theta
@@ -350,8 +349,8 @@ __device__ __forceinline__ uint32_t match_block(uint16_t *tile, uint32_t (&E)[16
                     const int c1 = max(dtfm_first_bit(reach), c0);   // none left: c0 once more
                     reach = dtfm_clear_bit(reach, c1);
                     const int m0 = __builtin_amdgcn_readlane(match_row, c0), m1 = __builtin_amdgcn_readlane(match_row, c1);
-                    const uint32_t w0 = ((uint32_t)tile[m0 * RSTR] << 7) | (uint32_t)c0;
-                    const uint32_t w1 = ((uint32_t)tile[m1 * RSTR] << 7) | (uint32_t)c1;
+                    const uint32_t w0 = ((uint32_t)tile[m0 * DTFM_WAVE] << 7) | (uint32_t)c0;
+                    const uint32_t w1 = ((uint32_t)tile[m1 * DTFM_WAVE] << 7) | (uint32_t)c1;
                     dist = min(dist, min(w0, w1));
                 } while (reach != 0ull);
                 reach = __ballot(dist - 1u < thr);
@@ -469,7 +468,7 @@ k_match(const uint16_t *__restrict__ Wcode, const uint32_t *__restrict__ Wrank, 
         const uint32_t v = Wcode[(uint32_t)Ca[real ? r : 0] * (uint32_t)N + coldev];
         E[r] = (active && real) ? v : 0xffffu;
     }
-    const uint32_t result = match_block<NB, DTFM_WAVE, false>(s_E + lane, E, lane, active, D_dp, shift0, [&](int r) {
+    const uint32_t result = match_block<NB>(s_E + lane, E, lane, active, D_dp, shift0, [&](int r) {
         return Wrank[(uint32_t)Ca[r] * (uint32_t)N + coldev];
     });
     if (lane == 0) {
