@@ -592,15 +592,23 @@ __device__ __forceinline__ void hk_block_layers(double *tab, const uint32_t *lsu
                 const uint32_t S = (H << NL) | L;
                 const bool in = (S >> v) & 1u;
                 const double2 *row = reinterpret_cast<const double2 *>(tab + L * RS);
-                double y = INFINITY;
+                // HM: bit q set = the pair of slots NL + 2 q, NL + 2 q + 1 holds a stage of H. All reads of the row
+                // are issued before the first relaxation (left to itself the compiler reuses the registers of the
+                // first four and waits for LDS three times per turn).
+                double2 x[NPAIR];
 #pragma unroll
                 for (int h = 0; h < NPAIR; h++) {
-                    // HM: bit q set = the pair of slots NL + 2 q, NL + 2 q + 1 holds a stage of H
+                    const bool present = 2 * h >= NL ? ((HM >> ((2 * h - NL) / 2)) & 1u) != 0u : true;
+                    if (present) x[h] = row[h];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                double y = fmin(__dadd_rn(x[0].x, Gc[0]), __dadd_rn(x[0].y, Gc[1]));
+#pragma unroll
+                for (int h = 1; h < NPAIR; h++) {
                     const bool present = 2 * h >= NL ? ((HM >> ((2 * h - NL) / 2)) & 1u) != 0u : true;
                     if (!present) continue;
-                    const double2 x = row[h];
-                    y = fmin(y, __dadd_rn(x.x, Gc[2 * h]));
-                    y = fmin(y, __dadd_rn(x.y, Gc[2 * h + 1]));
+                    y = fmin(y, __dadd_rn(x[h].x, Gc[2 * h]));
+                    y = fmin(y, __dadd_rn(x[h].y, Gc[2 * h + 1]));
                 }
                 // the empty set (layer 0 of block 0) pushes nothing: a single stage alone is a path of one node
                 if (!in && can_push && (k > 0 || H != 0u)) {
