@@ -313,7 +313,12 @@ def main():
                                            "exchange_bytes_per_s": xchg * Pg / t_hk,
                                            "exchange_frac_of_8TBps": xchg * Pg / t_hk / 8e12},
                              "datap_and_matching": {"block_entries_per_s": og["matching_compulsory_ops"] * Pg / t_front,
-                                                    "datap_adds_per_s": wg.N * (wg.D_dp - 1) * Pg / t_front},
+                                                    "datap_adds_per_s": wg.N * (wg.D_dp - 1) * Pg / t_front,
+                                                    # every block entry is one lane of a gather from the table of codes;
+                                                    # a CU's address unit takes four lane addresses per cycle
+                                                    "gather_lanes_peak_per_s": 256 * 4 * 2.4e9,
+                                                    "frac_of_gather_rate": og["matching_compulsory_ops"] * Pg / t_front
+                                                                           / (256 * 4 * 2.4e9)},
                              "timing": "HIP events over 5 launches each of dtfm_eval_population and of dtfm_coarsened_graph "
                                        "(DataP + matching only); Held-Karp = the difference"}
             dtfm.destroy_problem(pg)
