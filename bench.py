@@ -315,7 +315,8 @@ def main():
                              "datap_and_matching": {"block_entries_per_s": og["matching_compulsory_ops"] * Pg / t_front,
                                                     "datap_adds_per_s": wg.N * (wg.D_dp - 1) * Pg / t_front,
                                                     # every block entry is one lane of a gather from the table of codes;
-                                                    # a CU's address unit takes four lane addresses per cycle
+                                                    # assumed limit: four divergent lane addresses per cycle and CU
+                                                    # (the kernel's gathers alone were measured at 3.5)
                                                     "gather_lanes_peak_per_s": 256 * 4 * 2.4e9,
                                                     "frac_of_gather_rate": og["matching_compulsory_ops"] * Pg / t_front
                                                                            / (256 * 4 * 2.4e9)},
