@@ -315,11 +315,11 @@ def main():
                              "datap_and_matching": {"block_entries_per_s": og["matching_compulsory_ops"] * Pg / t_front,
                                                     "datap_adds_per_s": wg.N * (wg.D_dp - 1) * Pg / t_front,
                                                     # every block entry is one lane of a gather from the table of codes;
-                                                    # assumed limit: four divergent lane addresses per cycle and CU
-                                                    # (the kernel's gathers alone were measured at 3.5)
-                                                    "gather_lanes_peak_per_s": 256 * 4 * 2.4e9,
+                                                    # bare gathers of 64 random 2-byte columns of a table row run at 1.74
+                                                    # lanes per cycle and CU (profiles/gather_rate_gfx950.md)
+                                                    "gather_lanes_peak_per_s": 256 * 1.74 * 2.4e9,
                                                     "frac_of_gather_rate": og["matching_compulsory_ops"] * Pg / t_front
-                                                                           / (256 * 4 * 2.4e9)},
+                                                                           / (256 * 1.74 * 2.4e9)},
                              "timing": "HIP events over 5 launches each of dtfm_eval_population and of dtfm_coarsened_graph "
                                        "(DataP + matching only); Held-Karp = the difference"}
             dtfm.destroy_problem(pg)

@@ -1,9 +1,11 @@
-"""Builds (hipcc, gfx950) and runs the issue-rate microbenchmark on the current GPU:
+"""Builds (hipcc, gfx950) and runs the microbenchmarks on the current GPU:
 
-    python -m paper_2206_01288_amd.microbench
+    python -m paper_2206_01288_amd.microbench            # issue rates
+    python -m paper_2206_01288_amd.microbench gather     # gather rate
 
-Prints, per instruction kind, number of independent chains and wavefronts per SIMD, the time per launch, the
-time per instruction per wavefront and the shader-clock ticks per instruction of one wavefront.
+Issue rates: per instruction kind, number of independent chains and wavefronts per SIMD, the time per launch, the
+time per instruction per wavefront and the shader-clock ticks per instruction of one wavefront. Gather rate: the
+cycles a CU spends per 64-lane gather from a table row, by entry size and order of the columns.
 """
 import os
 import subprocess
@@ -14,20 +16,22 @@ BUILD = os.path.join(os.path.dirname(HERE), "_build")
 
 
 def build():
-    """Compiles issue_rates.hip for gfx950 and returns the path of the executable."""
+    """Compiles the microbenchmarks for gfx950 and returns the paths of the executables by name."""
     os.makedirs(BUILD, exist_ok=True)
-    exe = os.path.join(BUILD, "issue_rates")
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-                           "-packed-fp32-ops", "-Wno-unused-value", os.path.join(HERE, "issue_rates.hip"), "-o", exe])
-    return exe
+    exes = {}
+    for name in ("issue_rates", "gather_rate"):
+        exes[name] = os.path.join(BUILD, name)
+        subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                               "-packed-fp32-ops", "-Wno-unused-value", os.path.join(HERE, name + ".hip"), "-o", exes[name]])
+    return exes
 
 
 def main():
-    exe = build()
+    exes = build()
     if "--build-only" in sys.argv:
         return
-    sys.exit(subprocess.call([exe]))
+    sys.exit(subprocess.call([exes["gather_rate" if "gather" in sys.argv else "issue_rates"]]))
 
 
 if __name__ == "__main__":
