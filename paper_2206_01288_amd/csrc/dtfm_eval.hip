@@ -206,8 +206,8 @@ __global__ void k_zero_f64(double *__restrict__ dst, size_t n)
 // ------------------------------------------------------------------------------------------------
 // a4: bottleneck assignment for one (candidate, stage pair) per wavefront (one wavefront per workgroup),
 // lane c = column c (device at slot c of the second stage). The optimum of Eq. 3 is one of the block's
-// entries and depends only on their order, so the search runs on `Wrank`, the dense ranks of W_pp (equal
-// weights share a rank), and the result is mapped back through `rank_val`: no rounding is involved.
+// entries and depends only on their order, so the search runs on the dense ranks of W_pp (equal weights share
+// a rank), and the result is mapped back through `rank_val`: no rounding is involved.
 //
 // Invariant: a matching of some of the rows within the threshold theta, and theta <= the optimum T*.
 //  1. theta starts at the largest column minimum (every column is matched through one of its entries).
@@ -223,20 +223,21 @@ __global__ void k_zero_f64(double *__restrict__ dst, size_t n)
 //     matching does (Berge), so after the last insertion theta = T*.
 // The order in which rows are inserted and ties between paths do not change the value.
 //
-// Lane c keeps its column of the block (ranks) in registers for the steps whose row index is known at
-// compile time (1 and 2). For the search, where the row comes from a lane, the wavefront keeps the block in
-// LDS as 16-bit codes, s_E[r * 64 + c] (all lanes read one row: no bank conflicts); 8 KiB per wavefront, and
-// the number of resident wavefronts is what this latency-bound search lives on. A code is an order-preserving
-// image of the rank, code = rank < base ? 1 : 2 + ((rank - base) >> shift), capped at 0xffff:
-//  - first solve: base 0 and the `shift` that fits the largest rank (0 up to 65,532 distinct weights): the
-//    result is the exact optimum when shift = 0, else the bucket of 2^shift ranks that holds it (a matching
-//    within a bucket exists iff one exists within the bucket's largest rank);
-//  - if the block holds more than one distinct rank of that bucket, a second solve with base = the bucket's
-//    first rank and shift 0 separates them (ranks below the bucket all count as "within", ranks above it are
-//    never needed).
-// dist carries, in its low 7 bits, 1 + the column whose matched row gave it (0: the inserted row), so relaxing
-// is one shift-OR and one unsigned minimum; a visited column parks that field in `parked` and holds
-// dist = 0 from then on, which no minimum changes. Lanes c >= D_dp hold the pad rank and never take part.
+// Lane c keeps its column of the block in registers for the steps whose row index is known at compile time
+// (1 and 2). For the search, where the row comes from a lane, the wavefront keeps the block in LDS,
+// s_E[r * 64 + c] (all lanes read one row: no bank conflicts); 8 KiB per wavefront, and the number of resident
+// wavefronts is what this latency-bound search lives on. Registers and LDS hold 16-bit codes, order-preserving
+// images of the ranks:
+//  - first solve: the entries are gathered from `Wcode`, 2 + (rank >> shift) with the `shift` that fits the
+//    problem's largest rank (0 up to 65,532 distinct weights), pad 0xffff: the result is the exact optimum when
+//    shift = 0, else the bucket of 2^shift ranks that holds it (a matching within a bucket exists iff one
+//    exists within the bucket's largest rank);
+//  - if the block holds more than one distinct rank of that bucket (looked up in `Wrank`, only by the lanes that
+//    hold an entry of the bucket), a second solve on 1 (ranks below the bucket: all "within"), 2 + rank - the
+//    bucket's first rank (inside), 0xffff (above: never needed) separates them.
+// dist carries, in its low 7 bits, the column whose matched row gave it (127: the inserted row), so relaxing is
+// one shift-OR and one unsigned minimum; a visited column parks that field in `parked` and holds dist = 0 from
+// then on, which no minimum changes. Lanes c >= D_dp hold the pad code and never take part.
 __device__ __forceinline__ uint32_t dtfm_wave_min_u32(uint32_t k)
 {
     // prefix minima inside each row of 16 lanes by data-parallel shifts (a lane without a source keeps its own
