@@ -1,9 +1,11 @@
 // General-shape kernels for the cost model (any N <= 1024, D_dp <= 64, D_pp <= 16):
 //   k_weights     Sec. 2 symmetrisation + the per-link terms of Eqs. 2 and 3
-//   k_datap       Eq. 2 per stage and the max over stages (Sec. 3.2)
+//   k_datap       Eq. 2 per stage and the max over stages (Sec. 3.2); for matrices beyond an XCD's L2
+//                 k_datap_sliced (by slice of devices) or k_positions + k_datap_rows + k_datap_reduce (by device)
 //   k_match       Eq. 3: bottleneck perfect matching of one stage pair per wavefront
 //   k_held_karp   Eq. 4: open-loop TSP over the coarsened graph, exact, by subset dynamic
-//                 programming; adds the two parts (Eq. 1)
+//                 programming; adds the two parts (Eq. 1); k_held_karp_blocked from 11 stages on
+//   k_trial_shortcut   trials of the local search that the coarsened graph settles without Eq. 4
 // All arithmetic is fp64 with one rounding per operation (compiled with -ffp-contract=off; the
 // sums that define the result's bits use __dadd_rn explicitly).
 #include "dtfm_internal.h"
